@@ -1,0 +1,231 @@
+"""CPU oracle for ragged paged attention with fused KV-cache update.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+HIP path is checked against.  It shares no code with the HIP path, is never
+imported by the product package, and must never be used as a fallback.
+
+What it computes (paper Sec. 3, Algorithm 1 "RPA Forward Pass with KV Cache
+Update Fusion"): for every sequence r of a ragged batch, the newly projected
+K/V rows are written into the paged cache at the sequence's last l_q
+positions (Alg. 1, the "update new KV entries" step; Sec. 3.3 "Update U_kv"),
+and every query token attends causally over the sequence's cached plus new KV
+(Alg. 1 inner loop).  The FlashAttention-2 recurrences of Alg. 1 (running max
+m, running sum l, rescaled accumulator, final diag(l)^-1) reach exactly plain
+softmax attention, and paging only changes addressing, so the oracle is the
+plain definition written out: scatter, explicit gather to contiguous arrays,
+dense masked two-pass softmax in fp64.  No tiling, no online softmax.
+
+Readings where the paper is silent (each also listed in the design notes):
+  * scores are sm_scale * (q . k); sm_scale is the fp32 value of the call,
+    promoted to fp64 (Alg. 1 writes S = C_q C_k^T without a scale);
+  * "mask S if needed" (Alg. 1) is the causal mask aligned to the end of the
+    sequence: query i (0-based in its sequence) sees positions
+    j <= kv_len - q_len + i;
+  * kv_len counts this call's new tokens (Sec. 4.1: the context length
+    "accounts for KV data fetched from both the KV cache and newly projected
+    KV");
+  * query head h reads KV head h // (Hq / Hkv) (Sec. 3.1.2: the h_g heads of
+    a group are stacked against one K/V operand);
+  * the result is as if the update finished before attention starts.
+
+Pins (tests/test_oracle_pins.py, all CPU): pure-Python brute force on
+contiguous KV, page-permutation invariance, decode == last prefill row,
+chunk composition across calls, torch's float64 scaled_dot_product_attention
+on the contiguous single-sequence case, closed forms (constant V, equal K,
+hand-built log-weights, shift invariance), the split-merge identity, sentinel
+bytes, idempotence.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------
+# bf16 <-> fp64 (exact decode; round-to-nearest-even encode)
+# --------------------------------------------------------------------------
+def bf16_to_f64(u16: np.ndarray) -> np.ndarray:
+    """Exact value of bf16 bit patterns: the pattern is the top half of an
+    IEEE float32."""
+    u32 = np.asarray(u16, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    with np.errstate(invalid="ignore"):       # signalling-NaN patterns are legal input
+        return u32.view(np.float32).astype(np.float64)
+
+
+def f64_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round fp64 -> fp32 -> bf16 (nearest even), returned as bit patterns.
+    Only used to report a rounded copy of the oracle output."""
+    f32 = np.asarray(x, dtype=np.float64).astype(np.float32)
+    u32 = f32.view(np.uint32)
+    lsb = (u32 >> np.uint32(16)) & np.uint32(1)
+    rounded = (u32 + np.uint32(0x7FFF) + lsb) >> np.uint32(16)
+    out = rounded.astype(np.uint16)
+    nan = np.isnan(f32)
+    out[nan] = 0x7FC0
+    return out
+
+
+# --------------------------------------------------------------------------
+# step 1: cache update (bit copy)
+# --------------------------------------------------------------------------
+def update_cache(k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens, num_seqs):
+    """Write the new rows of every sequence into its pages, in place.
+
+    k_new, v_new : uint16 [T, Hkv, D];  k_pages, v_pages : uint16 [P, ps, Hkv, D]
+    Token t of sequence r (0 <= t < l_q) lands at position ctx + t, i.e. in
+    page page_table[r][pos // ps], slot pos % ps.
+    """
+    ps = k_pages.shape[1]
+    for r in range(num_seqs):
+        q0 = int(cu_q_lens[r])
+        l_q = int(cu_q_lens[r + 1]) - q0
+        l_kv = int(kv_lens[r])
+        ctx = l_kv - l_q
+        if l_q < 0 or ctx < 0:
+            raise ValueError("bad lengths")
+        for t in range(l_q):
+            pos = ctx + t
+            pg = int(page_table[r, pos // ps])
+            if pg < 0:
+                raise ValueError("page table entry missing")
+            k_pages[pg, pos % ps] = k_new[q0 + t]
+            v_pages[pg, pos % ps] = v_new[q0 + t]
+
+
+# --------------------------------------------------------------------------
+# step 2: explicit gather of one sequence's KV
+# --------------------------------------------------------------------------
+def gather_sequence(pages, table_row, l_kv):
+    """pages uint16 [P, ps, Hkv, D] -> contiguous uint16 [l_kv, Hkv, D]."""
+    ps = pages.shape[1]
+    n_pages = (l_kv + ps - 1) // ps
+    ids = np.asarray(table_row[:n_pages], dtype=np.int64)
+    if (ids < 0).any():
+        raise ValueError("page table entry missing")
+    flat = pages[ids].reshape(n_pages * ps, pages.shape[2], pages.shape[3])
+    return flat[:l_kv]
+
+
+# --------------------------------------------------------------------------
+# step 3: dense causal GQA softmax attention of one sequence, fp64, two-pass
+# --------------------------------------------------------------------------
+def attend_sequence(q, k, v, sm_scale, heads=None):
+    """q fp64 [l_q, Hq, D]; k, v fp64 [l_kv, Hkv, D] -> fp64 [l_q, Hq, D].
+
+    The last l_q positions of k/v are the queries' own tokens."""
+    l_q, hq, d = q.shape
+    l_kv, hkv, _ = k.shape
+    hg = hq // hkv
+    ctx = l_kv - l_q
+    scale = float(np.float32(sm_scale))
+    out = np.zeros((l_q, hq, d), dtype=np.float64)
+    i = np.arange(l_q)[:, None]
+    j = np.arange(l_kv)[None, :]
+    hidden = j > (ctx + i)
+    for h in (range(hq) if heads is None else heads):
+        g = h // hg
+        s = scale * (q[:, h, :] @ k[:, g, :].T)
+        s[hidden] = -np.inf
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        out[:, h, :] = p @ v[:, g, :]
+    return out
+
+
+# --------------------------------------------------------------------------
+# the whole call
+# --------------------------------------------------------------------------
+def update_and_attend(q, k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens,
+                      num_seqs, sm_scale, seqs=None, heads=None):
+    """The oracle of the library call.
+
+    All tensor arguments are numpy uint16 arrays of bf16 bit patterns.
+    Returns (out fp64 [T, Hq, D], k_pages', v_pages').  The input pools are
+    not modified.  `seqs` restricts the attention part (not the update) to
+    some sequences, for sampled checks at large sizes; rows of other
+    sequences are NaN.
+    """
+    k_pages = np.array(k_pages, dtype=np.uint16, copy=True)
+    v_pages = np.array(v_pages, dtype=np.uint16, copy=True)
+    update_cache(k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens, num_seqs)
+    t_total = int(cu_q_lens[num_seqs]) if num_seqs > 0 else 0
+    out = np.full((q.shape[0], q.shape[1], q.shape[2]), np.nan, dtype=np.float64)
+    for r in (range(num_seqs) if seqs is None else seqs):
+        q0 = int(cu_q_lens[r])
+        l_q = int(cu_q_lens[r + 1]) - q0
+        if l_q == 0:
+            continue
+        l_kv = int(kv_lens[r])
+        kk = bf16_to_f64(gather_sequence(k_pages, page_table[r], l_kv))
+        vv = bf16_to_f64(gather_sequence(v_pages, page_table[r], l_kv))
+        qq = bf16_to_f64(q[q0:q0 + l_q])
+        res = attend_sequence(qq, kk, vv, sm_scale, heads=heads)
+        if heads is None:
+            out[q0:q0 + l_q] = res
+        else:
+            hs = list(heads)
+            out[q0:q0 + l_q, hs] = res[:, hs]
+    assert t_total <= q.shape[0]
+    return out, k_pages, v_pages
+
+
+# --------------------------------------------------------------------------
+# merge rule for partial results over disjoint KV ranges
+# --------------------------------------------------------------------------
+def partial_attention(q_row, k, v, scale):
+    """Un-normalised partial of one query row over a KV range:
+    (m, l, o) with m = max score, l = sum exp(s - m), o = sum exp(s - m) v.
+    An empty range gives (-inf, 0, 0)."""
+    if k.shape[0] == 0:
+        return -np.inf, 0.0, np.zeros(v.shape[1], dtype=np.float64)
+    s = scale * (k @ q_row)
+    m = float(s.max())
+    p = np.exp(s - m)
+    return m, float(p.sum()), p @ v
+
+
+def merge_partials(parts):
+    """Combine (m, l, o) partials of disjoint ranges (follows from the
+    rescaling step of Alg. 1: states with different running maxima are
+    brought to the common maximum before they are added)."""
+    big = max(m for m, _, _ in parts)
+    num = 0.0
+    den = 0.0
+    for m, l, o in parts:
+        w = 0.0 if m == -np.inf else math.exp(m - big)
+        num = num + w * o
+        den = den + w * l
+    return num / den
+
+
+# --------------------------------------------------------------------------
+# structurally different brute force, for pinning the above on tiny inputs
+# --------------------------------------------------------------------------
+def dense_bruteforce(q, k, v, sm_scale):
+    """Pure-Python triple loop over contiguous lists.
+
+    q: [l_q][Hq][D], k/v: [l_kv][Hkv][D] nested lists (or arrays) of floats;
+    the queries are the last l_q positions.  Returns nested lists."""
+    l_q, hq, d = len(q), len(q[0]), len(q[0][0])
+    l_kv, hkv = len(k), len(k[0])
+    hg = hq // hkv
+    ctx = l_kv - l_q
+    scale = float(np.float32(sm_scale))
+    out = [[[0.0] * d for _ in range(hq)] for _ in range(l_q)]
+    for i in range(l_q):
+        last = ctx + i
+        for h in range(hq):
+            g = h // hg
+            scores = []
+            for j in range(last + 1):
+                acc = 0.0
+                for c in range(d):
+                    acc += float(q[i][h][c]) * float(k[j][g][c])
+                scores.append(scale * acc)
+            top = max(scores)
+            w = [math.exp(s - top) for s in scores]
+            z = math.fsum(w)
+            for c in range(d):
+                out[i][h][c] = math.fsum(w[j] * float(v[j][g][c]) for j in range(last + 1)) / z
+    return out

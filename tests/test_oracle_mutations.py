@@ -1,0 +1,75 @@
+"""Plant plausible mistakes in a copy of the oracle (on the CPU) and check that
+the pins notice every one of them.  This is what justifies trusting the pins.
+"""
+import importlib.util
+import inspect
+import os
+import sys
+import types
+
+import pytest
+
+import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "rpa_oracle.py")
+
+MUTATIONS = {
+    "mask_excludes_own_token": ("hidden = j > (ctx + i)", "hidden = j >= (ctx + i)"),
+    "mask_one_too_many": ("hidden = j > (ctx + i)", "hidden = j > (ctx + i + 1)"),
+    "mask_aligned_to_start": ("hidden = j > (ctx + i)", "hidden = j > i"),
+    "no_mask": ("s[hidden] = -np.inf", "pass"),
+    "wrong_gqa_map": ("g = h // hg\n        s = scale", "g = h % hkv\n        s = scale"),
+    "missing_scale": ("s = scale * (q[:, h, :] @ k[:, g, :].T)", "s = (q[:, h, :] @ k[:, g, :].T)"),
+    "no_normalisation": ("p /= p.sum(axis=1, keepdims=True)", "pass"),
+    "v_head_wrong": ("out[:, h, :] = p @ v[:, g, :]", "out[:, h, :] = p @ v[:, 0, :]"),
+    "update_at_wrong_position": ("pos = ctx + t\n            pg", "pos = t\n            pg"),
+    "update_wrong_slot": ("k_pages[pg, pos % ps] = k_new[q0 + t]", "k_pages[pg, t % ps] = k_new[q0 + t]"),
+    "update_swaps_k_v": ("v_pages[pg, pos % ps] = v_new[q0 + t]", "v_pages[pg, pos % ps] = k_new[q0 + t]"),
+    "update_ignores_seq_offset": ("k_pages[pg, pos % ps] = k_new[q0 + t]", "k_pages[pg, pos % ps] = k_new[t]"),
+    "gather_ignores_table": ("ids = np.asarray(table_row[:n_pages], dtype=np.int64)",
+                             "ids = np.arange(n_pages, dtype=np.int64)"),
+    "no_update_before_attend": ("    update_cache(k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens, num_seqs)\n    t_total",
+                                "    t_total"),
+    "merge_without_rescale": ("w = 0.0 if m == -np.inf else math.exp(m - big)", "w = 1.0"),
+    "q_offset_ignored": ("qq = bf16_to_f64(q[q0:q0 + l_q])", "qq = bf16_to_f64(q[0:l_q])"),
+}
+
+
+def load_mutant(old, new):
+    with open(SRC) as f:
+        text = f.read()
+    assert text.count(old) == 1, f"mutation anchor not unique: {old!r}"
+    mod = types.ModuleType("rpa_oracle_mutant")
+    exec(compile(text.replace(old, new), SRC + ":mutant", "exec"), mod.__dict__)
+    return mod
+
+
+PIN_TESTS = [(n, f) for n, f in inspect.getmembers(pins, inspect.isfunction)
+             if n.startswith("test_") and n not in ("test_config_shapes",)]
+
+
+def _calls(fn):
+    """Expand pytest parametrisation by hand."""
+    marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
+    if not marks:
+        return [()]
+    names, values = marks[0].args
+    n = len([s for s in names.split(",")])
+    return [v if n > 1 else (v,) for v in values]
+
+
+@pytest.mark.parametrize("name", sorted(MUTATIONS))
+def test_pins_catch_mutation(name, monkeypatch):
+    mutant = load_mutant(*MUTATIONS[name])
+    monkeypatch.setattr(pins, "O", mutant)
+    caught = []
+    for tname, fn in PIN_TESTS:
+        for args in _calls(fn):
+            try:
+                fn(*args)
+            except (AssertionError, ValueError, IndexError, FloatingPointError):
+                caught.append(tname)
+                break
+        if caught:
+            break
+    assert caught, f"no pin noticed the planted mistake {name}"
