@@ -1,0 +1,188 @@
+/*
+ * rpa.h - C ABI of the MI355X (gfx950) ragged paged attention library.
+ *
+ * One call updates a paged KV cache with the newly projected K/V of a ragged
+ * batch and computes causal grouped-query softmax attention for every query
+ * token over its sequence's cached plus new KV (paper Sec. 3, Algorithm 1
+ * "RPA Forward Pass with KV Cache Update Fusion").
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses on the context's GPU, "host"
+ *     pointers are ordinary host memory.  No pointer is retained after a call
+ *     returns, except that device buffers must stay valid until the work
+ *     enqueued on `stream` has finished.
+ *   - All tensors are dense, row-major, 16-byte aligned; the 16-bit element
+ *     type is bfloat16.
+ *   - Every function returns RPA_OK (0) or a negative rpa_status.  Nothing
+ *     throws or aborts across this boundary.  On error nothing is enqueued and
+ *     no tensor is touched; rpa_last_error() gives a message.
+ *   - The library allocates only its own workspace, in rpa_create(); the call
+ *     path performs no allocation, creates no stream and does not synchronise.
+ *   - A context serves one stream at a time: calls on one context must be
+ *     issued in stream order (the work lists it uploads are reused).
+ */
+#ifndef RPA_H
+#define RPA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RPA_OK = 0,
+    RPA_ERR_INVALID_ARG = -1, /* null pointer, negative count, unknown enum           */
+    RPA_ERR_BAD_LENGTHS = -2, /* cu_q_lens not non-decreasing from 0, kv_len < q_len,
+                                 more tokens/sequences/pages than the shape allows     */
+    RPA_ERR_UNSUPPORTED = -3, /* shape outside what the kernels are built for          */
+    RPA_ERR_HIP = -4,         /* a HIP runtime call failed (message has the detail)    */
+    RPA_ERR_WORKSPACE = -5    /* the plan does not fit the workspace sized at create   */
+} rpa_status;
+
+/* Static problem shape, fixed at rpa_create().  max_tokens and max_seqs are the
+ * paper's static upper bounds s and n (Sec. 3.6 "Recompilation Handling"): a
+ * call may use fewer, the padding is neither read nor written.               */
+typedef struct {
+    int32_t num_q_heads;       /* h_q                                                */
+    int32_t num_kv_heads;      /* h_kv; num_q_heads must be a multiple of it        */
+    int32_t head_dim;          /* d_k: 64 or 128                                     */
+    int32_t page_size;         /* tokens per cache page: a power of two >= 16        */
+    int32_t max_tokens;        /* s: rows of q / k_new / v_new / out                 */
+    int32_t max_seqs;          /* n: rows of page_table                              */
+    int32_t max_pages_per_seq; /* row stride of page_table                           */
+    int32_t num_pages;         /* pages in each of k_pages and v_pages               */
+} rpa_shape;
+
+/* Kernel variants (Sec. 3.4 "Distribution-aware Compilation": decode-only,
+ * prefill-only and mixed).  AUTO picks from the batch's length distribution.
+ * Forcing a variant changes speed only: every variant is correct on any batch. */
+typedef enum {
+    RPA_VARIANT_AUTO = 0,
+    RPA_VARIANT_DECODE = 1,  /* every query tile through the narrow split-KV kernel   */
+    RPA_VARIANT_PREFILL = 2, /* every query tile through the wide MFMA tile kernel    */
+    RPA_VARIANT_MIXED = 3    /* short-query sequences narrow, the rest wide           */
+} rpa_variant;
+
+/* One unit of work = one workgroup: a query tile of one sequence against a
+ * range of that sequence's KV positions.  Exposed for rpa_plan_host().       */
+typedef struct {
+    int32_t seq;        /* sequence index r                                           */
+    int32_t q_start;    /* packed token index of the tile's first query token         */
+    int32_t q_pos0;     /* index of that token inside its sequence                     */
+    int32_t n_q;        /* query tokens in the tile                                   */
+    int32_t kv_begin;   /* first KV position of the range (multiple of 16)            */
+    int32_t kv_end;     /* one past the last KV position the tile may see in range    */
+    int32_t ctx;        /* kv_len - q_len of the sequence: positions >= ctx are new   */
+    int32_t seq_q0;     /* cu_q_lens[r]                                               */
+    int32_t part_row;   /* first row of this unit's split partial, or -1: write out   */
+    int32_t flags;      /* bit 0: this unit writes the tile's new K/V into the pages;
+                           bit 1: wide kernel (else narrow)                           */
+    int32_t reserved[2];
+} rpa_work_unit;
+
+/* Merge job for one query tile that was split over KV ranges.                */
+typedef struct {
+    int32_t part_row;   /* first partial row of split 0                               */
+    int32_t n_splits;
+    int32_t rows;       /* rows per split = n_q * num_q_heads                         */
+    int32_t q_start;    /* packed token index of the tile's first token               */
+} rpa_combine_item;
+
+typedef struct {
+    int32_t variant;         /* rpa_variant actually used                             */
+    int32_t num_narrow_units;
+    int32_t num_wide_units;
+    int32_t num_combine_items;
+    int32_t max_splits;      /* largest number of KV ranges one tile was cut into     */
+    int32_t kv_chunk;        /* target KV positions per unit                          */
+    int64_t partial_rows;    /* fp32 partial rows used                                */
+    int64_t workspace_bytes; /* device workspace owned by the context                 */
+} rpa_plan_stats;
+
+/* Tuning knobs; all-zero = defaults.  They change speed only, never results
+ * beyond floating-point summation order.                                      */
+typedef struct {
+    int32_t variant;   /* rpa_variant; AUTO selects from the length distribution      */
+    int32_t kv_chunk;  /* KV positions per narrow unit (rounded up to 16); 0 = auto   */
+    int32_t wide_kv_chunk; /* KV positions per wide unit (rounded up to 64); 0 = auto */
+    int32_t reserved[5];
+} rpa_options;
+
+typedef struct rpa_ctx rpa_ctx;
+
+/* Create a context on HIP device `device` for `shape`; allocates the workspace
+ * (work lists, pinned staging, split partials).  *out is set on success only. */
+int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device);
+
+/* Free the workspace.  The caller must have synchronised the stream last used
+ * with this context.  NULL is allowed.                                        */
+void rpa_destroy(rpa_ctx* ctx);
+
+/* The hot path (Algorithm 1).  For each sequence r < num_seqs with
+ *   l_q = cu_q_lens[r+1] - cu_q_lens[r],  l_kv = kv_lens[r],  ctx = l_kv - l_q:
+ *   - token t of the sequence (packed row cu_q_lens[r] + t of k_new / v_new) is
+ *     copied bit for bit into slot (ctx + t) % page_size of page
+ *     page_table[r][(ctx + t) / page_size] of k_pages / v_pages
+ *     (Sec. 3.3 "Update U_kv"; Alg. 1 "update new KV entries");
+ *   - out[cu_q_lens[r] + t, h, :] = softmax_j(sm_scale * q[.., h, :] . K_j) V_j over
+ *     positions j <= ctx + t of KV head h / (num_q_heads / num_kv_heads), K/V being
+ *     the sequence's pages after the update (Alg. 1 inner loop and final
+ *     diag(l)^-1 step; Sec. 3.1.2 for the head grouping).
+ * Products accumulate in fp32, softmax weights are rounded to bf16 before the
+ * second contraction, the result is rounded to bf16 (nearest even).
+ * No cache byte other than the sum(l_q) new slots changes.  Rows of out at or
+ * beyond cu_q_lens[num_seqs], sequences at or beyond num_seqs, page_table
+ * entries at or beyond ceil(l_kv / page_size) and cache slots at or beyond l_kv
+ * are never read or written.  A page that is written in this call must belong
+ * to one sequence only.  Calling twice with the same arguments gives the same
+ * result.  The call only enqueues work on `stream`.
+ *
+ *   out        dev  bf16 [max_tokens, num_q_heads,  head_dim]   written
+ *   q          dev  bf16 [max_tokens, num_q_heads,  head_dim]
+ *   k_new      dev  bf16 [max_tokens, num_kv_heads, head_dim]
+ *   v_new      dev  bf16 [max_tokens, num_kv_heads, head_dim]
+ *   k_pages    dev  bf16 [num_pages, page_size, num_kv_heads, head_dim]  updated in place
+ *   v_pages    dev  bf16 [num_pages, page_size, num_kv_heads, head_dim]  updated in place
+ *   page_table dev  int32 [max_seqs, max_pages_per_seq]; ids outside
+ *                   [0, num_pages) are clamped into range (wrong result, no fault)
+ *   cu_q_lens  host int32 [num_seqs + 1], cu_q_lens[0] = 0, non-decreasing
+ *   kv_lens    host int32 [num_seqs], each includes the sequence's new tokens
+ *   num_seqs   0 <= num_seqs <= max_seqs (0: success, nothing enqueued)
+ *   sm_scale   softmax scale applied to q . k in fp32
+ *   stream     hipStream_t (NULL = the default stream)
+ */
+int rpa_update_and_attend(rpa_ctx* ctx, void* out, const void* q, const void* k_new,
+                          const void* v_new, void* k_pages, void* v_pages,
+                          const int32_t* page_table, const int32_t* cu_q_lens,
+                          const int32_t* kv_lens, int32_t num_seqs, float sm_scale,
+                          void* stream);
+
+/* Message of the last failed call on this context (never NULL; "" if none).
+ * With ctx == NULL: the message of the last failed rpa_create / rpa_plan_host
+ * on this thread.                                                             */
+const char* rpa_last_error(const rpa_ctx* ctx);
+
+/* Statistics of the last successful rpa_update_and_attend on this context.   */
+int rpa_plan_info(const rpa_ctx* ctx, rpa_plan_stats* out);
+
+/* Set the tuning knobs for later calls (tests and tuning); NULL restores the
+ * defaults.                                                                   */
+int rpa_set_options(rpa_ctx* ctx, const rpa_options* opt);
+
+/* Host-only planning, no GPU needed: the work partition that
+ * rpa_update_and_attend would use on a device with `num_cus` compute units
+ * (Alg. 1's loops over sequences, Q blocks and KV blocks, flattened into units;
+ * the split of a tile's KV range over several units is this library's own).
+ * Writes at most max_units / max_items records (narrow units first, then wide
+ * units, each group in launch order); the counts go to *stats.  opt may be NULL.
+ * Returns RPA_ERR_WORKSPACE if a buffer is too small.                         */
+int rpa_plan_host(const rpa_shape* shape, const int32_t* cu_q_lens, const int32_t* kv_lens,
+                  int32_t num_seqs, const rpa_options* opt, int num_cus, rpa_work_unit* units,
+                  int32_t max_units, rpa_combine_item* items, int32_t max_items,
+                  rpa_plan_stats* stats);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RPA_H */

@@ -1,0 +1,265 @@
+// C ABI of the library: context, validation, per-call planning and launches.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "rpa_internal.h"
+
+using namespace rpa;
+
+namespace {
+
+constexpr int kRing = 4; // staging slots: the host may run this many calls ahead of the GPU
+
+thread_local std::string g_err; // errors without a context
+
+struct Staging {
+    void* host = nullptr;       // pinned
+    void* dev = nullptr;        // device copy of the same blob
+    hipEvent_t copied = nullptr; // host buffer may be overwritten once this has passed
+    bool used = false;
+};
+
+} // namespace
+
+struct rpa_ctx {
+    rpa_shape shape{};
+    rpa_options opt{};
+    int device = 0;
+    int num_cus = 0;
+    int max_units = 0;
+    int max_items = 0;
+    int64_t partial_row_cap = 0;
+    size_t blob_bytes = 0;
+    Staging ring[kRing];
+    int ring_pos = 0;
+    float* part_o = nullptr;
+    float* part_ml = nullptr;
+    int64_t workspace_bytes = 0;
+    Plan plan;
+    rpa_plan_stats last{};
+    std::string err;
+};
+
+static int fail(rpa_ctx* c, int code, const std::string& msg) {
+    if (c)
+        c->err = msg;
+    else
+        g_err = msg;
+    return code;
+}
+
+static int hip_fail(rpa_ctx* c, const char* what, hipError_t e) {
+    return fail(c, RPA_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+extern "C" int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device) {
+    if (!out || !shape) return fail(nullptr, RPA_ERR_INVALID_ARG, "rpa_create: null argument");
+    std::string msg;
+    int rc = check_shape(*shape, msg);
+    if (rc != RPA_OK) return fail(nullptr, rc, msg);
+    hipError_t e = hipSetDevice(device);
+    if (e != hipSuccess) return hip_fail(nullptr, "hipSetDevice", e);
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, device);
+    if (e != hipSuccess) return hip_fail(nullptr, "hipGetDeviceProperties", e);
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return fail(nullptr, RPA_ERR_UNSUPPORTED, std::string("device is ") + prop.gcnArchName + ", kernels are gfx950 only");
+
+    rpa_ctx* c = new (std::nothrow) rpa_ctx();
+    if (!c) return fail(nullptr, RPA_ERR_HIP, "out of host memory");
+    c->shape = *shape;
+    c->device = device;
+    c->num_cus = prop.multiProcessorCount;
+    // Units: every query tile once, plus the extra ranges of split tiles
+    // (bounded by the per-CU oversubscription of the partitioner).
+    const int hg = shape->num_q_heads / shape->num_kv_heads;
+    const int64_t tiles = (int64_t)shape->max_tokens / 1 + shape->max_seqs;
+    (void)hg;
+    c->max_units = (int)std::min<int64_t>(tiles + 64 * (int64_t)c->num_cus, 1 << 24);
+    c->max_items = c->max_units;
+    // Split partials: a narrow unit holds 16 rows per KV head, a wide unit 256;
+    // the partitioner keeps a handful of units per compute unit.
+    c->partial_row_cap = std::min<int64_t>(
+        std::max<int64_t>((int64_t)8 * shape->max_tokens * shape->num_q_heads,
+                          (int64_t)12 * c->num_cus * kNarrowRows * shape->num_kv_heads),
+        (int64_t)1 << 22);
+    c->blob_bytes = (size_t)c->max_units * sizeof(rpa_work_unit) + (size_t)c->max_items * sizeof(rpa_combine_item);
+
+    auto cleanup = [&](const char* what, hipError_t err) {
+        int r = hip_fail(nullptr, what, err);
+        rpa_destroy(c);
+        return r;
+    };
+    for (int i = 0; i < kRing; ++i) {
+        e = hipHostMalloc(&c->ring[i].host, c->blob_bytes, hipHostMallocDefault);
+        if (e != hipSuccess) return cleanup("hipHostMalloc", e);
+        e = hipMalloc(&c->ring[i].dev, c->blob_bytes);
+        if (e != hipSuccess) return cleanup("hipMalloc", e);
+        e = hipEventCreateWithFlags(&c->ring[i].copied, hipEventDisableTiming);
+        if (e != hipSuccess) return cleanup("hipEventCreate", e);
+        c->workspace_bytes += (int64_t)c->blob_bytes;
+    }
+    const size_t po = (size_t)c->partial_row_cap * shape->head_dim * sizeof(float);
+    const size_t pml = (size_t)c->partial_row_cap * 2 * sizeof(float);
+    e = hipMalloc((void**)&c->part_o, po);
+    if (e != hipSuccess) return cleanup("hipMalloc", e);
+    e = hipMalloc((void**)&c->part_ml, pml);
+    if (e != hipSuccess) return cleanup("hipMalloc", e);
+    c->workspace_bytes += (int64_t)(po + pml);
+    if (kernels_init(device, msg) != 0) {
+        rpa_destroy(c);
+        return fail(nullptr, RPA_ERR_HIP, msg);
+    }
+    *out = c;
+    return RPA_OK;
+}
+
+extern "C" void rpa_destroy(rpa_ctx* c) {
+    if (!c) return;
+    for (int i = 0; i < kRing; ++i) {
+        if (c->ring[i].copied) (void)hipEventDestroy(c->ring[i].copied);
+        if (c->ring[i].host) (void)hipHostFree(c->ring[i].host);
+        if (c->ring[i].dev) (void)hipFree(c->ring[i].dev);
+    }
+    if (c->part_o) (void)hipFree(c->part_o);
+    if (c->part_ml) (void)hipFree(c->part_ml);
+    delete c;
+}
+
+extern "C" const char* rpa_last_error(const rpa_ctx* c) { return c ? c->err.c_str() : g_err.c_str(); }
+
+extern "C" int rpa_plan_info(const rpa_ctx* c, rpa_plan_stats* out) {
+    if (!c || !out) return RPA_ERR_INVALID_ARG;
+    *out = c->last;
+    out->workspace_bytes = c->workspace_bytes;
+    return RPA_OK;
+}
+
+extern "C" int rpa_set_options(rpa_ctx* c, const rpa_options* opt) {
+    if (!c) return RPA_ERR_INVALID_ARG;
+    rpa_options o{};
+    if (opt) o = *opt;
+    if (o.variant < RPA_VARIANT_AUTO || o.variant > RPA_VARIANT_MIXED || o.kv_chunk < 0 || o.wide_kv_chunk < 0)
+        return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: bad value");
+    c->opt = o;
+    return RPA_OK;
+}
+
+extern "C" int rpa_plan_host(const rpa_shape* shape, const int32_t* cu_q_lens, const int32_t* kv_lens,
+                             int32_t num_seqs, const rpa_options* opt, int num_cus, rpa_work_unit* units,
+                             int32_t max_units, rpa_combine_item* items, int32_t max_items,
+                             rpa_plan_stats* stats) {
+    if (!shape || !stats || max_units < 0 || max_items < 0 || (max_units > 0 && !units) || (max_items > 0 && !items))
+        return fail(nullptr, RPA_ERR_INVALID_ARG, "rpa_plan_host: bad argument");
+    std::string msg;
+    int rc = check_shape(*shape, msg);
+    if (rc != RPA_OK) return fail(nullptr, rc, msg);
+    rpa_options o{};
+    if (opt) o = *opt;
+    Plan plan;
+    rc = build_plan(*shape, cu_q_lens, kv_lens, num_seqs, o, num_cus, (int64_t)1 << 40, plan, msg);
+    if (rc != RPA_OK) return fail(nullptr, rc, msg);
+    *stats = plan.stats;
+    const size_t nu = plan.narrow.size() + plan.wide.size();
+    if (nu > (size_t)max_units || plan.items.size() > (size_t)max_items)
+        return fail(nullptr, RPA_ERR_WORKSPACE, "rpa_plan_host: output buffers too small");
+    if (!plan.narrow.empty()) std::memcpy(units, plan.narrow.data(), plan.narrow.size() * sizeof(rpa_work_unit));
+    if (!plan.wide.empty())
+        std::memcpy(units + plan.narrow.size(), plan.wide.data(), plan.wide.size() * sizeof(rpa_work_unit));
+    if (!plan.items.empty()) std::memcpy(items, plan.items.data(), plan.items.size() * sizeof(rpa_combine_item));
+    return RPA_OK;
+}
+
+extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const void* k_new, const void* v_new,
+                                     void* k_pages, void* v_pages, const int32_t* page_table,
+                                     const int32_t* cu_q_lens, const int32_t* kv_lens, int32_t num_seqs,
+                                     float sm_scale, void* stream) {
+    if (!c) return RPA_ERR_INVALID_ARG;
+    if (num_seqs == 0) {
+        c->last = rpa_plan_stats{};
+        return RPA_OK;
+    }
+    if (!out || !q || !k_new || !v_new || !k_pages || !v_pages || !page_table)
+        return fail(c, RPA_ERR_INVALID_ARG, "rpa_update_and_attend: null tensor pointer");
+    const uintptr_t align = (uintptr_t)out | (uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new |
+                            (uintptr_t)k_pages | (uintptr_t)v_pages;
+    if (align & 15) return fail(c, RPA_ERR_INVALID_ARG, "rpa_update_and_attend: tensors must be 16-byte aligned");
+    if (!std::isfinite(sm_scale)) return fail(c, RPA_ERR_INVALID_ARG, "rpa_update_and_attend: sm_scale not finite");
+
+    std::string msg;
+    int rc = build_plan(c->shape, cu_q_lens, kv_lens, num_seqs, c->opt, c->num_cus, c->partial_row_cap, c->plan, msg);
+    if (rc != RPA_OK) return fail(c, rc, msg);
+    Plan& plan = c->plan;
+    const size_t n_narrow = plan.narrow.size(), n_wide = plan.wide.size(), n_items = plan.items.size();
+    if (n_narrow + n_wide == 0) {
+        c->last = plan.stats;
+        return RPA_OK;
+    }
+    if (n_narrow + n_wide > (size_t)c->max_units || n_items > (size_t)c->max_items)
+        return fail(c, RPA_ERR_WORKSPACE, "work list larger than the workspace sized at create");
+
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, "hipSetDevice", e);
+    hipStream_t st = (hipStream_t)stream;
+    Staging& slot = c->ring[c->ring_pos];
+    if (slot.used) {
+        e = hipEventSynchronize(slot.copied);
+        if (e != hipSuccess) return hip_fail(c, "hipEventSynchronize", e);
+    }
+    char* h = (char*)slot.host;
+    const size_t units_bytes = (n_narrow + n_wide) * sizeof(rpa_work_unit);
+    const size_t items_off = (size_t)c->max_units * sizeof(rpa_work_unit);
+    if (n_narrow) std::memcpy(h, plan.narrow.data(), n_narrow * sizeof(rpa_work_unit));
+    if (n_wide) std::memcpy(h + n_narrow * sizeof(rpa_work_unit), plan.wide.data(), n_wide * sizeof(rpa_work_unit));
+    e = hipMemcpyAsync(slot.dev, h, units_bytes, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return hip_fail(c, "hipMemcpyAsync", e);
+    if (n_items) {
+        std::memcpy(h + items_off, plan.items.data(), n_items * sizeof(rpa_combine_item));
+        e = hipMemcpyAsync((char*)slot.dev + items_off, h + items_off, n_items * sizeof(rpa_combine_item),
+                           hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) return hip_fail(c, "hipMemcpyAsync", e);
+    }
+    e = hipEventRecord(slot.copied, st);
+    if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
+    slot.used = true;
+    c->ring_pos = (c->ring_pos + 1) % kRing;
+
+    KernelArgs a{};
+    a.q = (const uint16_t*)q;
+    a.k_new = (const uint16_t*)k_new;
+    a.v_new = (const uint16_t*)v_new;
+    a.k_pages = (uint16_t*)k_pages;
+    a.v_pages = (uint16_t*)v_pages;
+    a.out = (uint16_t*)out;
+    a.page_table = page_table;
+    a.part_o = c->part_o;
+    a.part_ml = c->part_ml;
+    a.num_q_heads = c->shape.num_q_heads;
+    a.num_kv_heads = c->shape.num_kv_heads;
+    a.hg = c->shape.num_q_heads / c->shape.num_kv_heads;
+    a.head_dim = c->shape.head_dim;
+    a.page_size_log2 = __builtin_ctz((unsigned)c->shape.page_size);
+    a.max_pages_per_seq = c->shape.max_pages_per_seq;
+    a.num_pages = c->shape.num_pages;
+    a.scale_log2 = sm_scale * 1.4426950408889634f;
+
+    const rpa_work_unit* dev_units = (const rpa_work_unit*)slot.dev;
+    int hrc;
+    a.units = dev_units;
+    hrc = launch_narrow(a, (int)n_narrow, stream);
+    if (hrc != 0) return hip_fail(c, "narrow kernel launch", (hipError_t)hrc);
+    a.units = dev_units + n_narrow;
+    hrc = launch_wide(a, (int)n_wide, stream);
+    if (hrc != 0) return hip_fail(c, "wide kernel launch", (hipError_t)hrc);
+    hrc = launch_combine((const rpa_combine_item*)((char*)slot.dev + items_off), (int)n_items, c->part_o, c->part_ml,
+                         (uint16_t*)out, a.num_q_heads, a.head_dim, stream);
+    if (hrc != 0) return hip_fail(c, "combine kernel launch", (hipError_t)hrc);
+    c->last = plan.stats;
+    return RPA_OK;
+}

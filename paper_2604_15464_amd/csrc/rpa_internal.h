@@ -1,0 +1,70 @@
+// Internal declarations shared by the host side and the kernel launchers.
+#pragma once
+
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "rpa.h"
+
+namespace rpa {
+
+// Tile geometry the kernels are compiled for.
+constexpr int kNarrowRows = 16;   // query rows (tokens x heads of one group) per narrow tile
+constexpr int kNarrowKvTile = 16; // KV positions per narrow pipeline stage
+constexpr int kWideQTokens = 64;  // query tokens per wide tile (x h_g heads = rows)
+constexpr int kWideKvTile = 64;   // KV positions per wide pipeline stage
+constexpr int kMaxWaves = 8;      // waves per narrow workgroup (one KV head each)
+
+struct Plan {
+    std::vector<rpa_work_unit> narrow; // launch order
+    std::vector<rpa_work_unit> wide;   // launch order
+    std::vector<rpa_combine_item> items;
+    rpa_plan_stats stats{};
+};
+
+// Validates shape; returns RPA_OK or an error with a message.
+int check_shape(const rpa_shape& s, std::string& err);
+
+// Validates the lengths and builds the work partition.
+int build_plan(const rpa_shape& s, const int32_t* cu_q_lens, const int32_t* kv_lens,
+               int32_t num_seqs, const rpa_options& opt, int num_cus, int64_t partial_row_cap,
+               Plan& plan, std::string& err);
+
+// Number of narrow query tokens per tile for a head-group size, or 0 if unsupported.
+inline int narrow_q_tokens(int hg) { return (hg >= 1 && hg <= kNarrowRows && kNarrowRows % hg == 0) ? kNarrowRows / hg : 0; }
+
+// Waves per narrow workgroup: the largest divisor of num_kv_heads not above kMaxWaves.
+inline int narrow_waves(int hkv) {
+    int w = 1;
+    for (int d = 1; d <= kMaxWaves; ++d)
+        if (hkv % d == 0) w = d;
+    return w;
+}
+
+struct KernelArgs {
+    const uint16_t* q;
+    const uint16_t* k_new;
+    const uint16_t* v_new;
+    uint16_t* k_pages;
+    uint16_t* v_pages;
+    uint16_t* out;
+    const int32_t* page_table;
+    const rpa_work_unit* units;
+    float* part_o;  // [rows, D] un-normalised partial outputs
+    float* part_ml; // [rows, 2] running max (log2 domain) and running sum
+    int32_t num_q_heads, num_kv_heads, hg, head_dim;
+    int32_t page_size_log2, max_pages_per_seq, num_pages;
+    float scale_log2; // sm_scale * log2(e)
+};
+
+// Launchers (rpa_kernels.hip).  Return a hipError_t value as int.
+int launch_narrow(const KernelArgs& a, int num_units, void* stream);
+int launch_wide(const KernelArgs& a, int num_units, void* stream);
+int launch_combine(const rpa_combine_item* items, int num_items, const float* part_o,
+                   const float* part_ml, uint16_t* out, int num_q_heads, int head_dim,
+                   void* stream);
+int kernels_init(int device, std::string& err);
+
+} // namespace rpa

@@ -1,0 +1,431 @@
+// gfx950 kernels of the ragged paged attention hot path (paper Algorithm 1).
+//
+// Orientation used by every MFMA here (CDNA4, 64-lane waves): the score tile is
+// computed transposed, S^T = K Q^T, so that KV positions run along the MFMA's
+// M index and query rows along its N index.  In the accumulator layout a lane
+// then holds values of ONE query row (column n = lane % 16) for four KV
+// positions (4 * (lane / 16) + v), which is exactly the B-operand layout the
+// second contraction O^T = V^T P^T needs: the softmax weights never leave the
+// registers, and the row statistics (running max m, running sum l of Alg. 1)
+// are reduced with two cross-lane steps.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rpa_internal.h"
+
+namespace rpa {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short short4v;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// Read-only tables are read through the constant address space so that
+// wave-uniform reads become scalar loads (and stay so next to the inline asm).
+typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+
+// ---------------------------------------------------------------------------
+// small device helpers
+// ---------------------------------------------------------------------------
+
+// 16-byte asynchronous global -> LDS copy: lane i's 16 bytes land at
+// lds_byte_off + 16 * i.  Completion is tracked by vmcnt only; the compiler
+// does not know about the LDS write, so every consumer waits explicitly with
+// wait_vmcnt<N>() before reading the stage.
+__device__ __forceinline__ void async_load16(const void* gptr, uint32_t lds_byte_off) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_byte_off)
+                 : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+// two floats -> packed bf16 pair (round to nearest even), low half = a
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    f32x2 f = {a, b};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ int clamp_page(int page, int num_pages) {
+    return min(max(page, 0), num_pages - 1);
+}
+
+// ---------------------------------------------------------------------------
+// Narrow kernel: query tile of up to 16 rows (16 / h_g tokens x the h_g heads of
+// one KV head).  One wave per KV head; every wave runs its own LDS ring fed by
+// asynchronous 16-byte loads (the GPU analogue of the paper's double-buffered
+// B_kv fetch, Sec. 2.3 / Alg. 1 "start DMA ... wait DMA"), so there is no
+// workgroup barrier in the loop.  Used for decode (q_len 1) and short query
+// runs; bandwidth-bound.  A unit covers KV positions [kv_begin, kv_end) and
+// either writes the final rows or an un-normalised partial (m, l, O).
+// ---------------------------------------------------------------------------
+template <int D, int NST>
+__global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a) {
+    constexpr int ROWB = D * 2;                 // bytes of one token row of one head
+    constexpr int NC = D / 8;                   // 16-byte chunks per row
+    constexpr int TPI = 64 / NC;                // tokens covered by one wave-wide load
+    constexpr int NLD = kNarrowKvTile / TPI;    // loads per K (or V) tile
+    constexpr int TILEB = kNarrowKvTile * ROWB; // bytes of a K (or V) tile
+    constexpr int STAGEB = 2 * TILEB;
+    constexpr int LOADS_PER_STAGE = 2 * NLD;
+    constexpr int KSTEPS = D / 32;              // MFMA 16x16x32 steps over head_dim
+    constexpr int MT = D / 16;                  // 16-dim output tiles
+
+    extern __shared__ uint4 smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int nwaves = blockDim.x >> 6;
+    const int g = blockIdx.y * nwaves + wave; // KV head of this wave
+    const int n = lane & 15;                  // query row of this lane (MFMA column)
+    const int quad = lane >> 4;
+
+    const rpa_work_unit u = a.units[blockIdx.x];
+    const int hg = a.hg;
+    const int Hq = a.num_q_heads, Hkv = a.num_kv_heads;
+    const int ps_log2 = a.page_size_log2;
+    const int ps_mask = (1 << ps_log2) - 1;
+    const int num_pages = a.num_pages;
+    const int ctx = u.ctx;
+    const char* const k_pages = (const char*)a.k_pages;
+    const char* const v_pages = (const char*)a.v_pages;
+    const char* const k_new = (const char*)a.k_new;
+    const char* const v_new = (const char*)a.v_new;
+    const const_i32_ptr pt_row = (const_i32_ptr)(uintptr_t)(a.page_table + (size_t)u.seq * a.max_pages_per_seq);
+    const uint32_t tokstride = (uint32_t)Hkv * ROWB; // bytes between consecutive tokens
+    const uint64_t k_delta = (uint64_t)k_pages - (uint64_t)k_new;
+    const uint64_t v_delta = (uint64_t)v_pages - (uint64_t)v_new;
+
+    // ---- query operand: row n = (token n / hg, head g*hg + n % hg) -----------
+    const int tok_n = n / hg;
+    const int hh = n - tok_n * hg;
+    const bool row_ok = tok_n < u.n_q;
+    const int limit_n = row_ok ? ctx + u.q_pos0 + tok_n : -1; // last visible KV position
+    bf16x8 qreg[KSTEPS];
+    {
+        const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok ? tok_n : 0)) * Hq + g * hg + hh) * D;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (row_ok) raw = *(const uint4*)(qrow + kk * 32 + quad * 8);
+            qreg[kk] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    // All ordinary loads are complete from here on: inside the loop vmcnt counts
+    // the ring's asynchronous loads only.
+    wait_vmcnt<0>();
+
+    const uint32_t lds_wave = lds_offset(smem) + wave * (NST * STAGEB);
+    const char* lds_wave_ptr = (const char*)smem + wave * (NST * STAGEB);
+
+    const int kv_begin = u.kv_begin, kv_end = u.kv_end;
+    const int ntiles = max(0, (kv_end - kv_begin + kNarrowKvTile - 1) / kNarrowKvTile);
+
+    // per-lane constants of the gather: load i of a tile brings token
+    // m = i*TPI + lane/NC; the lane fetches the 16-byte chunk that the XOR
+    // swizzle assigns to its LDS slot.
+    const int ld_tok = lane / NC;
+    const int ld_chunk = lane % NC;
+    uint32_t lane_off[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int m = i * TPI + ld_tok;
+        lane_off[i] = (uint32_t)g * ROWB + (uint32_t)((ld_chunk ^ (m % NC)) * 16);
+    }
+
+    auto issue_tile = [&](int t) {
+        const int pos0 = kv_begin + t * kNarrowKvTile;
+        const int slot = t % NST;
+        const int pidx = __builtin_amdgcn_readfirstlane(pos0 >> ps_log2);
+        const int page = clamp_page(pt_row[pidx], num_pages); // a tile never straddles pages
+        const uint32_t ldsK = lds_wave + slot * STAGEB;
+        const uint32_t ldsV = ldsK + TILEB;
+        const int last = kv_end - 1 - pos0; // tokens past the range re-read its last token
+        if (pos0 + kNarrowKvTile <= ctx) {
+            // whole tile is cached content: one scalar base per pool
+            const size_t tile_off = (((size_t)page << ps_log2) + (size_t)(pos0 & ps_mask)) * tokstride;
+            const char* kb = k_pages + tile_off;
+            const char* vb = v_pages + tile_off;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                const int m = min(i * TPI + ld_tok, last);
+                const uint32_t voff = (uint32_t)m * tokstride + lane_off[i];
+                async_load16(kb + voff, ldsK + i * 1024);
+                async_load16(vb + voff, ldsV + i * 1024);
+            }
+        } else {
+            // tile holds new tokens: those come from k_new / v_new, never from the
+            // page slots this call writes
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                const int pos = pos0 + min(i * TPI + ld_tok, last);
+                const bool cached = pos < ctx;
+                const size_t tokidx = cached ? (((size_t)page << ps_log2) + (size_t)(pos & ps_mask))
+                                             : (size_t)(u.seq_q0 + pos - ctx);
+                // select the pool by adding a wave-uniform pointer difference
+                const uint64_t off = (uint64_t)tokidx * tokstride + lane_off[i];
+                const uint64_t ka = (uint64_t)k_new + off + (cached ? k_delta : 0);
+                const uint64_t va = (uint64_t)v_new + off + (cached ? v_delta : 0);
+                async_load16((const void*)ka, ldsK + i * 1024);
+                async_load16((const void*)va, ldsV + i * 1024);
+            }
+        }
+    };
+
+    f32x4 acc[MT];
+#pragma unroll
+    for (int j = 0; j < MT; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY; // running max, log2 domain (score * sm_scale * log2 e)
+    float l_run = 0.f;       // this lane's share of the running sum
+
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s)
+        if (s < ntiles) issue_tile(s);
+
+    for (int t = 0; t < ntiles; ++t) {
+        if (t + NST - 1 < ntiles) issue_tile(t + NST - 1);
+        // tiles still in flight behind tile t
+        const int behind = min(NST - 1, ntiles - 1 - t);
+        if (NST >= 4 && behind >= 3) wait_vmcnt<(NST >= 4 ? 3 : 0) * LOADS_PER_STAGE>();
+        else if (NST >= 3 && behind == 2) wait_vmcnt<(NST >= 3 ? 2 : 0) * LOADS_PER_STAGE>();
+        else if (NST >= 2 && behind == 1) wait_vmcnt<(NST >= 2 ? 1 : 0) * LOADS_PER_STAGE>();
+        else wait_vmcnt<0>();
+
+        const char* ldsK = lds_wave_ptr + (t % NST) * STAGEB;
+        const char* ldsV = ldsK + TILEB;
+        const int pos0 = kv_begin + t * kNarrowKvTile;
+
+        // ---- S^T = K Q^T (Alg. 1: S <- C_q C_k^T) --------------------------------
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            const int c = 4 * kk + quad;
+            const bf16x8 kop = *(const bf16x8*)(ldsK + n * ROWB + ((c ^ (n % NC)) * 16));
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[kk], s, 0, 0, 0);
+        }
+
+        // ---- mask + online softmax (Alg. 1: m~, P, l~) ------------------------
+        float sv[4];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int pos = pos0 + 4 * quad + v;
+            const bool ok = (pos < kv_end) && (pos <= limit_n);
+            sv[v] = ok ? s[v] * a.scale_log2 : -INFINITY;
+            mx = fmaxf(mx, sv[v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = fast_exp2(m_run - m_use);
+        float p[4];
+        float psum = 0.f;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            p[v] = fast_exp2(sv[v] - m_use);
+            psum += p[v];
+        }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int j = 0; j < MT; ++j) acc[j] *= alpha;
+
+        union {
+            uint32_t w[2];
+            short4v v;
+        } pop;
+        pop.w[0] = pack_bf16(p[0], p[1]);
+        pop.w[1] = pack_bf16(p[2], p[3]);
+
+        // ---- O^T += V^T P^T (Alg. 1: C_o <- ... + P C_v) --------------------------
+        // lane (m = lane%16, quad) reads 16 bytes (8 dims) of its four tokens and
+        // transposes them in registers into eight 4-token operands.
+        uint32_t vr[4][4];
+        const int ch = n % NC;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+            const int tok = 4 * quad + tt;
+            const uint4 raw = *(const uint4*)(ldsV + tok * ROWB + ((ch ^ (tok % NC)) * 16));
+            vr[tt][0] = raw.x;
+            vr[tt][1] = raw.y;
+            vr[tt][2] = raw.z;
+            vr[tt][3] = raw.w;
+        }
+        short4v vop[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+            union {
+                uint32_t w[2];
+                short4v v;
+            } o;
+            o.w[0] = __builtin_amdgcn_perm(vr[1][j / 2], vr[0][j / 2], sel);
+            o.w[1] = __builtin_amdgcn_perm(vr[3][j / 2], vr[2][j / 2], sel);
+            vop[j] = o.v;
+        }
+        if constexpr (D == 128) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[j], pop.v, acc[j], 0, 0, 0);
+        } else {
+            const bool upper = n >= NC; // lanes 8..15 serve dims j+4 of their chunk
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                short4v pick;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pick[e] = upper ? vop[j + 4][e] : vop[j][e];
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pick, pop.v, acc[j], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- fused cache update (Alg. 1: "update new KV entries"), once per tile.
+    // Readers never take positions >= ctx from the pages (they read k_new / v_new),
+    // so this store races with nothing; it sits after the loop so that only loads
+    // are in flight while the ring's vmcnt bookkeeping runs.
+    if (u.flags & 1) {
+        const int c = lane % NC;
+        for (int t = lane / NC; t < u.n_q; t += TPI) {
+            const int pos = ctx + u.q_pos0 + t;
+            const int page = clamp_page(pt_row[pos >> ps_log2], num_pages);
+            const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * D + c * 8;
+            const size_t dst = ((((size_t)page << ps_log2) + (pos & ps_mask)) * Hkv + g) * D + c * 8;
+            const uint4 kk = *(const uint4*)(a.k_new + src);
+            const uint4 vv = *(const uint4*)(a.v_new + src);
+            *(uint4*)(a.k_pages + dst) = kk;
+            *(uint4*)(a.v_pages + dst) = vv;
+        }
+    }
+
+    // ---- finalize (Alg. 1: diag(l)^-1 B_o) or store the partial state ------------
+    float l_tot = l_run + __shfl_xor(l_run, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (!row_ok) return;
+    const int head = g * hg + hh;
+    if (u.part_row < 0) {
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        uint16_t* orow = a.out + ((size_t)(u.q_start + tok_n) * Hq + head) * D;
+#pragma unroll
+        for (int j = 0; j < MT; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int mrow = 4 * quad + v;
+                const int dim = 8 * (mrow % NC) + j + MT * (mrow / NC);
+                orow[dim] = (uint16_t)(pack_bf16(acc[j][v] * inv, 0.f) & 0xFFFFu);
+            }
+    } else {
+        const size_t prow = (size_t)u.part_row + (size_t)tok_n * Hq + head;
+        float* po = a.part_o + prow * D;
+#pragma unroll
+        for (int j = 0; j < MT; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int mrow = 4 * quad + v;
+                const int dim = 8 * (mrow % NC) + j + MT * (mrow / NC);
+                po[dim] = acc[j][v];
+            }
+        if (quad == 0) {
+            a.part_ml[prow * 2] = m_run;
+            a.part_ml[prow * 2 + 1] = l_tot;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Combine: merge the partial states of a tile that was cut into KV ranges.
+// States with different running maxima are rescaled to the common maximum and
+// added, as in the rescaling step of Alg. 1.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) rpa_combine_kernel(const rpa_combine_item* __restrict__ items,
+                                                          const float* __restrict__ part_o,
+                                                          const float* __restrict__ part_ml,
+                                                          uint16_t* __restrict__ out, int Hq, int D) {
+    const rpa_combine_item it = items[blockIdx.x];
+    const int dim = threadIdx.x % D;
+    const int rstep = blockDim.x / D;
+    for (int row = blockIdx.y * rstep + threadIdx.x / D; row < it.rows; row += rstep * gridDim.y) {
+        float big = -INFINITY;
+        for (int s = 0; s < it.n_splits; ++s)
+            big = fmaxf(big, part_ml[((size_t)it.part_row + (size_t)s * it.rows + row) * 2]);
+        float num = 0.f, den = 0.f;
+        for (int s = 0; s < it.n_splits; ++s) {
+            const size_t prow = (size_t)it.part_row + (size_t)s * it.rows + row;
+            const float m = part_ml[prow * 2];
+            const float w = (m == -INFINITY) ? 0.f : fast_exp2(m - big);
+            num += w * part_o[prow * D + dim];
+            den += w * part_ml[prow * 2 + 1];
+        }
+        const float r = den > 0.f ? num / den : 0.f;
+        out[((size_t)it.q_start * Hq + row) * D + dim] = (uint16_t)(pack_bf16(r, 0.f) & 0xFFFFu);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+constexpr int kNarrowStages = 2;
+
+template <int D>
+static size_t narrow_lds_bytes(int waves) {
+    return (size_t)waves * kNarrowStages * 2 * kNarrowKvTile * D * 2;
+}
+
+int kernels_init(int device, std::string& err) {
+    (void)device;
+    hipError_t e;
+    e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<128, kNarrowStages>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<128>(kMaxWaves));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<64, kNarrowStages>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<64>(kMaxWaves));
+    if (e != hipSuccess) {
+        err = std::string("hipFuncSetAttribute: ") + hipGetErrorString(e);
+        return (int)e;
+    }
+    return 0;
+}
+
+int launch_narrow(const KernelArgs& a, int num_units, void* stream) {
+    if (num_units <= 0) return 0;
+    const int waves = narrow_waves(a.num_kv_heads);
+    dim3 grid(num_units, a.num_kv_heads / waves);
+    dim3 block(64 * waves);
+    hipStream_t st = (hipStream_t)stream;
+    if (a.head_dim == 128)
+        hipLaunchKernelGGL((rpa_narrow_kernel<128, kNarrowStages>), grid, block, narrow_lds_bytes<128>(waves), st, a);
+    else
+        hipLaunchKernelGGL((rpa_narrow_kernel<64, kNarrowStages>), grid, block, narrow_lds_bytes<64>(waves), st, a);
+    return (int)hipGetLastError();
+}
+
+int launch_wide(const KernelArgs& a, int num_units, void* stream) {
+    (void)a;
+    (void)stream;
+    return num_units > 0 ? (int)hipErrorNotSupported : 0;
+}
+
+int launch_combine(const rpa_combine_item* items, int num_items, const float* part_o, const float* part_ml,
+                   uint16_t* out, int num_q_heads, int head_dim, void* stream) {
+    if (num_items <= 0) return 0;
+    dim3 grid(num_items, 4);
+    hipLaunchKernelGGL(rpa_combine_kernel, grid, dim3(256), 0, (hipStream_t)stream, items, part_o, part_ml, out,
+                       num_q_heads, head_dim);
+    return (int)hipGetLastError();
+}
+
+} // namespace rpa

@@ -1,0 +1,217 @@
+"""ctypes binding of librpa.so: argument marshalling only.
+
+Every step of the path (cache update, attention, split merge, and the host
+work partition) runs inside the library.  There is no fallback: if the library
+is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librpa.so")
+
+RPA_OK = 0
+ERR_INVALID_ARG, ERR_BAD_LENGTHS, ERR_UNSUPPORTED, ERR_HIP, ERR_WORKSPACE = -1, -2, -3, -4, -5
+VARIANT_AUTO, VARIANT_DECODE, VARIANT_PREFILL, VARIANT_MIXED = 0, 1, 2, 3
+VARIANT_NAMES = {0: "auto", 1: "decode", 2: "prefill", 3: "mixed"}
+
+
+class Shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "num_q_heads", "num_kv_heads", "head_dim", "page_size", "max_tokens", "max_seqs",
+        "max_pages_per_seq", "num_pages")]
+
+
+class WorkUnit(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "seq", "q_start", "q_pos0", "n_q", "kv_begin", "kv_end", "ctx", "seq_q0", "part_row",
+        "flags")] + [("reserved", C.c_int32 * 2)]
+
+
+class CombineItem(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("part_row", "n_splits", "rows", "q_start")]
+
+
+class PlanStats(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "variant", "num_narrow_units", "num_wide_units", "num_combine_items", "max_splits",
+        "kv_chunk")] + [("partial_rows", C.c_int64), ("workspace_bytes", C.c_int64)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class Options(C.Structure):
+    _fields_ = [("variant", C.c_int32), ("kv_chunk", C.c_int32), ("wide_kv_chunk", C.c_int32),
+                ("reserved", C.c_int32 * 5)]
+
+
+class RpaError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"rpa error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+EXPORTS = ("rpa_create", "rpa_destroy", "rpa_update_and_attend", "rpa_last_error", "rpa_plan_info",
+           "rpa_set_options", "rpa_plan_host")
+
+
+def lib():
+    """Load librpa.so (built in-tree by paper_2604_15464_amd/build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_15464_amd.build` "
+                           "(there is no fallback path)")
+    l = C.CDLL(LIB_PATH)
+    l.rpa_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(Shape), C.c_int]
+    l.rpa_create.restype = C.c_int
+    l.rpa_destroy.argtypes = [C.c_void_p]
+    l.rpa_destroy.restype = None
+    l.rpa_update_and_attend.argtypes = [C.c_void_p] + [C.c_void_p] * 7 + [C.c_void_p, C.c_void_p,
+                                                                            C.c_int32, C.c_float, C.c_void_p]
+    l.rpa_update_and_attend.restype = C.c_int
+    l.rpa_last_error.argtypes = [C.c_void_p]
+    l.rpa_last_error.restype = C.c_char_p
+    l.rpa_plan_info.argtypes = [C.c_void_p, C.POINTER(PlanStats)]
+    l.rpa_plan_info.restype = C.c_int
+    l.rpa_set_options.argtypes = [C.c_void_p, C.POINTER(Options)]
+    l.rpa_set_options.restype = C.c_int
+    l.rpa_plan_host.argtypes = [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(Options), C.c_int,
+                                C.POINTER(WorkUnit), C.c_int32, C.POINTER(CombineItem), C.c_int32,
+                                C.POINTER(PlanStats)]
+    l.rpa_plan_host.restype = C.c_int
+    _lib = l
+    return l
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.c_void_p)
+
+
+def make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs, max_pages_per_seq,
+               num_pages) -> Shape:
+    return Shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs, max_pages_per_seq,
+                 num_pages)
+
+
+def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUTO, kv_chunk=0,
+              wide_kv_chunk=0, max_units=1 << 20):
+    """Host-only work partition (no GPU needed).  Returns (units, items, stats)
+    with units/items as numpy structured views."""
+    l = lib()
+    cu, cu_p = _i32(cu_q_lens)
+    kv, kv_p = _i32(kv_lens)
+    n = len(kv)
+    units = (WorkUnit * max_units)()
+    items = (CombineItem * max_units)()
+    stats = PlanStats()
+    opt = Options(variant, kv_chunk, wide_kv_chunk)
+    rc = l.rpa_plan_host(C.byref(shape), cu_p, kv_p, n, C.byref(opt), num_cus, units, max_units, items,
+                         max_units, C.byref(stats))
+    if rc != RPA_OK:
+        raise RpaError(rc, l.rpa_last_error(None).decode())
+    nu = stats.num_narrow_units + stats.num_wide_units
+    u = np.frombuffer(units, dtype=np.int32).reshape(max_units, 12)[:nu].copy()
+    it = np.frombuffer(items, dtype=np.int32).reshape(max_units, 4)[:stats.num_combine_items].copy()
+    return u, it, stats.as_dict()
+
+
+UNIT_FIELDS = ("seq", "q_start", "q_pos0", "n_q", "kv_begin", "kv_end", "ctx", "seq_q0", "part_row", "flags")
+
+
+class RaggedPagedAttention:
+    """One context = one static shape on one GPU."""
+
+    def __init__(self, num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs,
+                 max_pages_per_seq, num_pages, device=0):
+        self._lib = lib()
+        self.shape = make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs,
+                                max_pages_per_seq, num_pages)
+        self._ctx = C.c_void_p()
+        rc = self._lib.rpa_create(C.byref(self._ctx), C.byref(self.shape), int(device))
+        if rc != RPA_OK:
+            raise RpaError(rc, self._lib.rpa_last_error(None).decode())
+        self.device = int(device)
+
+    @classmethod
+    def for_workload(cls, wl, max_tokens=None, max_seqs=None, device=0):
+        return cls(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size,
+                   max(1, max_tokens or wl.num_tokens), max(1, max_seqs or wl.num_seqs),
+                   wl.max_pages_per_seq, wl.num_pages, device)
+
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx.value:
+            self._lib.rpa_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_options(self, variant=VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0):
+        opt = Options(variant, kv_chunk, wide_kv_chunk)
+        rc = self._lib.rpa_set_options(self._ctx, C.byref(opt))
+        if rc != RPA_OK:
+            raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())
+
+    def plan_info(self) -> dict:
+        st = PlanStats()
+        rc = self._lib.rpa_plan_info(self._ctx, C.byref(st))
+        if rc != RPA_OK:
+            raise RpaError(rc, "rpa_plan_info")
+        return st.as_dict()
+
+    def update_and_attend_raw(self, out_ptr, q_ptr, k_new_ptr, v_new_ptr, k_pages_ptr, v_pages_ptr,
+                              page_table_ptr, cu_q_lens, kv_lens, num_seqs, sm_scale, stream_ptr):
+        """Pointers in, status out: cu_q_lens / kv_lens are contiguous int32 numpy arrays."""
+        rc = self._lib.rpa_update_and_attend(
+            self._ctx, out_ptr, q_ptr, k_new_ptr, v_new_ptr, k_pages_ptr, v_pages_ptr, page_table_ptr,
+            cu_q_lens.ctypes.data, kv_lens.ctypes.data, num_seqs, sm_scale, stream_ptr)
+        if rc != RPA_OK:
+            raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())
+
+    def update_and_attend(self, q, k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens,
+                          sm_scale, out=None, stream=None):
+        """torch tensors on this context's GPU (bf16; page_table int32);
+        cu_q_lens / kv_lens host arrays.  k_pages / v_pages are updated in
+        place; returns out.  The call is asynchronous on `stream` (default:
+        torch's current stream)."""
+        import torch
+
+        cu = np.ascontiguousarray(cu_q_lens, dtype=np.int32)
+        kv = np.ascontiguousarray(kv_lens, dtype=np.int32)
+        n = int(kv.shape[0])
+        if cu.shape[0] != n + 1:
+            raise ValueError("cu_q_lens must have num_seqs + 1 entries")
+        sh = self.shape
+        for name, t, shape in (("q", q, (sh.max_tokens, sh.num_q_heads, sh.head_dim)),
+                               ("k_new", k_new, (sh.max_tokens, sh.num_kv_heads, sh.head_dim)),
+                               ("v_new", v_new, (sh.max_tokens, sh.num_kv_heads, sh.head_dim)),
+                               ("k_pages", k_pages, (sh.num_pages, sh.page_size, sh.num_kv_heads, sh.head_dim)),
+                               ("v_pages", v_pages, (sh.num_pages, sh.page_size, sh.num_kv_heads, sh.head_dim))):
+            if tuple(t.shape) != shape or t.dtype != torch.bfloat16 or not t.is_contiguous() or not t.is_cuda:
+                raise ValueError(f"{name}: expected contiguous cuda bf16 tensor of shape {shape}, "
+                                 f"got {tuple(t.shape)} {t.dtype}")
+        if (tuple(page_table.shape) != (sh.max_seqs, sh.max_pages_per_seq) or page_table.dtype != torch.int32
+                or not page_table.is_contiguous() or not page_table.is_cuda):
+            raise ValueError("page_table: expected contiguous cuda int32 [max_seqs, max_pages_per_seq]")
+        if out is None:
+            out = torch.empty_like(q)
+        elif tuple(out.shape) != tuple(q.shape) or out.dtype != torch.bfloat16 or not out.is_contiguous():
+            raise ValueError("out: wrong shape / dtype")
+        st = torch.cuda.current_stream(q.device) if stream is None else stream
+        self.update_and_attend_raw(out.data_ptr(), q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                   k_pages.data_ptr(), v_pages.data_ptr(), page_table.data_ptr(), cu, kv, n,
+                                   float(sm_scale), st.cuda_stream)
+        return out

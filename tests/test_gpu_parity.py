@@ -1,0 +1,200 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  KV cache: bit-exact.  Outputs (bf16, fp32
+accumulation) against the fp64 oracle: max-abs <= 1.5e-2, mean-abs <= 2e-3.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rpa_oracle as O
+from paper_2604_15464_amd import rpa
+from paper_2604_15464_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS = 1.5e-2
+MEAN_ABS = 2e-3
+
+
+def to_f64(t):
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=True, pad_tokens=0,
+             pad_seqs=0, seqs=None, calls=1):
+    """Run the HIP path and the oracle on the workload; returns a dict of results."""
+    dev = torch.device("cuda:0")
+    max_tokens = wl.num_tokens + pad_tokens
+    max_seqs = wl.num_seqs + pad_seqs
+    x = W.materialize(wl, dev, poison=poison, max_tokens=max(1, max_tokens))
+    host = {k: W.bits(v) for k, v in x.items()}
+    table = np.full((max(1, max_seqs), wl.max_pages_per_seq), -1, dtype=np.int32)
+    table[:wl.num_seqs] = wl.page_table
+    table_dev = torch.from_numpy(table).to(dev)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl, max_tokens=max(1, max_tokens), max_seqs=max(1, max_seqs))
+    ctx.set_options(variant=variant, kv_chunk=kv_chunk, wide_kv_chunk=wide_kv_chunk)
+    out = torch.full_like(x["q"], float("nan"))
+    sentinel = out.clone()
+    for _ in range(calls):
+        ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], table_dev,
+                              wl.cu_q_lens, wl.kv_lens, wl.sm_scale, out=out)
+    torch.cuda.synchronize()
+    info = ctx.plan_info()
+    ctx.close()
+    ref, kp, vp = O.update_and_attend(host["q"], host["k_new"], host["v_new"], host["k_pages"],
+                                      host["v_pages"], wl.page_table, wl.cu_q_lens, wl.kv_lens,
+                                      wl.num_seqs, wl.sm_scale, seqs=seqs)
+    return {"out": out, "ref": ref, "kp": W.bits(x["k_pages"]), "vp": W.bits(x["v_pages"]), "kp_ref": kp,
+            "vp_ref": vp, "info": info, "sentinel": sentinel, "x": x}
+
+
+def check(wl, res, seqs=None):
+    t = wl.num_tokens
+    # cache: bit-exact, including every byte that must not change
+    assert np.array_equal(res["kp"], res["kp_ref"]), "k_pages differ from the oracle"
+    assert np.array_equal(res["vp"], res["vp_ref"]), "v_pages differ from the oracle"
+    got = to_f64(res["out"])
+    rows = np.zeros(got.shape[0], dtype=bool)
+    cu = wl.cu_q_lens
+    for r in (range(wl.num_seqs) if seqs is None else seqs):
+        rows[cu[r]:cu[r + 1]] = True
+    if rows.any():
+        err = np.abs(got[rows] - res["ref"][rows])
+        assert np.isfinite(got[rows]).all(), "non-finite output"
+        assert err.max() <= MAX_ABS, f"max abs err {err.max():.4g}"
+        assert err.mean() <= MEAN_ABS, f"mean abs err {err.mean():.4g}"
+    # padding rows are never written
+    if got.shape[0] > t:
+        assert torch.equal(res["out"][t:].view(torch.int16), res["sentinel"][t:].view(torch.int16))
+
+
+def test_config1_tiny_mixed():
+    wl = W.config(1)
+    res = run_case(wl)
+    check(wl, res)
+
+
+@pytest.mark.parametrize("variant", [rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL, rpa.VARIANT_MIXED])
+def test_config1_forced_variants(variant):
+    wl = W.config(1)
+    res = run_case(wl, variant=variant)
+    check(wl, res)
+    assert res["info"]["variant"] == variant
+
+
+@pytest.mark.parametrize("kv_chunk", [16, 32, 48])
+def test_config1_forced_splits(kv_chunk):
+    wl = W.config(1)
+    res = run_case(wl, kv_chunk=kv_chunk, wide_kv_chunk=64)
+    check(wl, res)
+    assert res["info"]["max_splits"] > 1
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_ragged_small_heads(seed):
+    wl = W.ragged(200 + seed, num_seqs=7, hq=4, hkv=2, d=64, ps=16, max_q=70, max_ctx=300)
+    res = run_case(wl, kv_chunk=(0, 32, 64, 16)[seed % 4], wide_kv_chunk=(0, 64, 128, 64)[seed % 4],
+                   pad_tokens=3, pad_seqs=2)
+    check(wl, res)
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("variant", [rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL])
+def test_random_ragged_llama_heads(seed, variant):
+    wl = W.ragged(300 + seed, num_seqs=6, hq=32, hkv=8, d=128, ps=(16, 64, 32)[seed % 3], max_q=150,
+                  max_ctx=700)
+    res = run_case(wl, variant=variant, kv_chunk=(0, 64, 128)[seed % 3], wide_kv_chunk=(0, 128, 64)[seed % 3],
+                   pad_tokens=5)
+    check(wl, res)
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 8), (16, 8), (16, 2), (16, 1), (8, 1)])
+def test_group_sizes(hq, hkv):
+    wl = W.ragged(400 + hq + hkv, num_seqs=5, hq=hq, hkv=hkv, d=128, ps=16, max_q=40, max_ctx=200)
+    for variant in (rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL):
+        res = run_case(wl, variant=variant, kv_chunk=64, wide_kv_chunk=64)
+        check(wl, res)
+
+
+@pytest.mark.parametrize("idx,scale", [(2, 0.125), (3, 0.125), (4, 0.0625), (5, 0.03125)])
+def test_shrunken_configs(idx, scale):
+    wl = W.config(idx, scale=scale)
+    res = run_case(wl)
+    check(wl, res)
+
+
+def test_idempotent_repeated_calls():
+    wl = W.ragged(500, num_seqs=6, hq=32, hkv=8, d=128, ps=16, max_q=90, max_ctx=400)
+    once = run_case(wl, kv_chunk=64)
+    thrice = run_case(wl, kv_chunk=64, calls=3)
+    check(wl, thrice)
+    assert torch.equal(once["out"].view(torch.int16)[:wl.num_tokens],
+                       thrice["out"].view(torch.int16)[:wl.num_tokens])
+
+
+def test_degenerate_lengths():
+    hq, hkv, d, ps = 32, 8, 128, 16
+    # kv_len = q_len = 1; a q_len 0 sequence; exact page boundaries; one token past a boundary
+    q = [1, 0, 16, 1, 17, 1, 64]
+    kv = [1, 33, 16, 16, 17, 17, 128]
+    rng = np.random.default_rng(6)
+    wl = W.Workload("degenerate", 6, hq, hkv, d, ps, 40, q, kv, W.make_page_table(kv, ps, 40, rng))
+    for variant in (rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL):
+        res = run_case(wl, variant=variant)
+        check(wl, res)
+
+
+def test_empty_batch_and_errors():
+    wl = W.config(1)
+    dev = torch.device("cuda:0")
+    x = W.materialize(wl, dev)
+    table = torch.from_numpy(wl.page_table).to(dev)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl)
+    before_k = x["k_pages"].clone()
+    out = torch.full_like(x["q"], float("nan"))
+    keep = out.clone()
+    # num_seqs = 0: success, nothing happens
+    ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], table,
+                          np.zeros(1, np.int32), np.zeros(0, np.int32), wl.sm_scale, out=out)
+    # bad lengths: error, nothing enqueued, nothing touched
+    bad_kv = wl.kv_lens.copy()
+    bad_kv[2] = 10
+    with pytest.raises(rpa.RpaError) as e:
+        ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], table,
+                              wl.cu_q_lens, bad_kv, wl.sm_scale, out=out)
+    assert e.value.code == rpa.ERR_BAD_LENGTHS
+    torch.cuda.synchronize()
+    assert torch.equal(before_k.view(torch.int16), x["k_pages"].view(torch.int16))
+    assert torch.equal(out.view(torch.int16), keep.view(torch.int16))
+    ctx.close()
+
+
+def test_chunked_prefill_carries_cache_across_calls():
+    """Four calls of 128 tokens must leave the same cache as one call of 512 and
+    give outputs within tolerance of the single-call oracle."""
+    hq, hkv, d, ps = 32, 8, 128, 16
+    total, chunk = 512, 128
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(9)
+    table = W.make_page_table([total], ps, 40, rng)
+    wl_full = W.Workload("full", 9, hq, hkv, d, ps, 40, [total], [total], table)
+    x = W.materialize(wl_full, dev)
+    host = {k: W.bits(v) for k, v in x.items()}
+    ref, kp_ref, vp_ref = O.update_and_attend(host["q"], host["k_new"], host["v_new"], host["k_pages"],
+                                              host["v_pages"], table, wl_full.cu_q_lens, wl_full.kv_lens, 1,
+                                              wl_full.sm_scale)
+    ctx = rpa.RaggedPagedAttention(hq, hkv, d, ps, chunk, 1, table.shape[1], 40)
+    table_dev = torch.from_numpy(table).to(dev)
+    outs = []
+    for c0 in range(0, total, chunk):
+        o = ctx.update_and_attend(x["q"][c0:c0 + chunk].contiguous(), x["k_new"][c0:c0 + chunk].contiguous(),
+                                  x["v_new"][c0:c0 + chunk].contiguous(), x["k_pages"], x["v_pages"], table_dev,
+                                  np.array([0, chunk], np.int32), np.array([c0 + chunk], np.int32),
+                                  wl_full.sm_scale)
+        outs.append(o)
+    torch.cuda.synchronize()
+    ctx.close()
+    assert np.array_equal(W.bits(x["k_pages"]), kp_ref)
+    assert np.array_equal(W.bits(x["v_pages"]), vp_ref)
+    err = np.abs(to_f64(torch.cat(outs)) - ref)
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS

@@ -1,0 +1,171 @@
+"""CPU tests of the C-ABI library's host side: it loads, exports what the header
+declares, validates lengths, and its work partition covers every (query token,
+KV position) pair exactly once with exactly one cache writer per token."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2604_15464_amd import rpa
+from paper_2604_15464_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+F = {n: i for i, n in enumerate(rpa.UNIT_FIELDS)}
+
+
+def shape_of(wl, max_tokens=None, max_seqs=None):
+    return rpa.make_shape(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size,
+                          max_tokens or max(1, wl.num_tokens), max_seqs or max(1, wl.num_seqs),
+                          wl.max_pages_per_seq, wl.num_pages)
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "rpa.h")) as f:
+        text = f.read()
+    declared = set(re.findall(r"^(?:int|void|const char\*)\s+(rpa_\w+)\s*\(", text, flags=re.M))
+    assert declared == set(rpa.EXPORTS)
+    l = rpa.lib()
+    for name in declared:
+        assert hasattr(l, name), name
+
+
+def check_plan(wl, units, items, stats, narrow_tq, wide_tq=64):
+    cu = wl.cu_q_lens
+    # per token: covered KV positions and writers
+    cover = {}
+    writers = np.zeros(wl.num_tokens, dtype=np.int64)
+    tile_units = {}
+    for u in units:
+        seq, q_start, q_pos0, n_q = u[F["seq"]], u[F["q_start"]], u[F["q_pos0"]], u[F["n_q"]]
+        b, e, ctx, seq_q0, part, flags = (u[F["kv_begin"]], u[F["kv_end"]], u[F["ctx"]], u[F["seq_q0"]],
+                                          u[F["part_row"]], u[F["flags"]])
+        wide = bool(flags & 2)
+        assert seq_q0 == cu[seq] and q_start == seq_q0 + q_pos0
+        assert ctx == wl.kv_lens[seq] - wl.q_lens[seq]
+        assert 1 <= n_q <= (wide_tq if wide else narrow_tq)
+        assert q_pos0 + n_q <= wl.q_lens[seq]
+        assert 0 <= b < e <= ctx + q_pos0 + n_q
+        assert b % (64 if wide else 16) == 0
+        tile_units.setdefault((seq, q_pos0), []).append((b, e, part, flags, n_q))
+        if flags & 1:
+            writers[q_start:q_start + n_q] += 1
+    assert (writers == 1).all()
+    n_items = 0
+    for (seq, q_pos0), lst in tile_units.items():
+        lst.sort()
+        n_q = lst[0][4]
+        kv_hi = wl.kv_lens[seq] - wl.q_lens[seq] + q_pos0 + n_q
+        # ranges tile [0, kv_hi) without gap or overlap
+        assert lst[0][0] == 0 and lst[-1][1] == kv_hi
+        for (b0, e0, *_), (b1, *_rest) in zip(lst[:-1], lst[1:]):
+            assert e0 == b1
+        if len(lst) == 1:
+            assert lst[0][2] == -1
+        else:
+            n_items += 1
+            rows = n_q * wl.num_q_heads
+            parts = [p for _, _, p, _, _ in lst]
+            assert all(p >= 0 for p in parts)
+            assert [p - parts[0] for p in parts] == [i * rows for i in range(len(lst))]
+            match = [it for it in items if it[0] == parts[0]]
+            assert len(match) == 1
+            assert match[0].tolist() == [parts[0], len(lst), rows, cu[seq] + q_pos0]
+    assert n_items == len(items) == stats["num_combine_items"]
+    # every query token appears in exactly one tile
+    seen = np.zeros(wl.num_tokens, dtype=np.int64)
+    for (seq, q_pos0), lst in tile_units.items():
+        seen[cu[seq] + q_pos0: cu[seq] + q_pos0 + lst[0][4]] += 1
+    assert (seen == 1).all()
+    # partial rows do not overlap
+    spans = sorted((it[0], it[0] + it[1] * it[2]) for it in items)
+    for (a0, a1), (b0, b1) in zip(spans[:-1], spans[1:]):
+        assert a1 <= b0
+    if spans:
+        assert spans[-1][1] == stats["partial_rows"]
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("variant", [rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL, rpa.VARIANT_MIXED])
+def test_plan_covers_configs(idx, variant):
+    wl = W.config(idx) if idx in (1, 2, 5) else W.config(idx, scale=0.25)
+    units, items, stats = rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, variant=variant)
+    check_plan(wl, units, items, stats, narrow_tq=16 // (wl.num_q_heads // wl.num_kv_heads))
+    if variant == rpa.VARIANT_DECODE:
+        assert stats["num_wide_units"] == 0 and stats["variant"] == rpa.VARIANT_DECODE
+    if variant == rpa.VARIANT_PREFILL:
+        assert stats["num_narrow_units"] == 0 and stats["variant"] == rpa.VARIANT_PREFILL
+
+
+def test_auto_variant_follows_distribution():
+    s2 = rpa.plan_host(shape_of(W.config(2)), W.config(2).cu_q_lens, W.config(2).kv_lens)[2]
+    assert s2["variant"] == rpa.VARIANT_DECODE
+    c3 = W.config(3, scale=0.25)
+    assert rpa.plan_host(shape_of(c3), c3.cu_q_lens, c3.kv_lens)[2]["variant"] == rpa.VARIANT_PREFILL
+    c4 = W.config(4, scale=0.25)
+    assert rpa.plan_host(shape_of(c4), c4.cu_q_lens, c4.kv_lens)[2]["variant"] == rpa.VARIANT_MIXED
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("kv_chunk", [0, 16, 48])
+def test_plan_covers_random_ragged(seed, kv_chunk):
+    wl = W.ragged(100 + seed, num_seqs=9, max_q=150, max_ctx=400)
+    units, items, stats = rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, kv_chunk=kv_chunk,
+                                        wide_kv_chunk=64 if kv_chunk else 0)
+    check_plan(wl, units, items, stats, narrow_tq=8)
+    if kv_chunk:
+        assert stats["max_splits"] > 1
+
+
+def test_decode_units_balance_bytes():
+    """Equal-KV chunks: no decode unit of config 5 is more than ~2x the mean."""
+    wl = W.config(5)
+    units, _, stats = rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, num_cus=256)
+    span = units[:, F["kv_end"]] - units[:, F["kv_begin"]]
+    assert len(units) >= 4 * 256
+    assert span.max() <= 2 * span.mean()
+    assert (np.diff(span) <= 0).all()          # longest first
+
+
+def test_bad_lengths_are_rejected():
+    wl = W.config(1)
+    sh = shape_of(wl)
+    cu, kv = wl.cu_q_lens.copy(), wl.kv_lens.copy()
+
+    def code(cu_, kv_, shape=sh):
+        with pytest.raises(rpa.RpaError) as e:
+            rpa.plan_host(shape, cu_, kv_)
+        return e.value.code
+
+    bad = cu.copy(); bad[0] = 1
+    assert code(bad, kv) == rpa.ERR_BAD_LENGTHS
+    bad = cu.copy(); bad[2] = bad[1] - 1
+    assert code(bad, kv) == rpa.ERR_BAD_LENGTHS
+    badkv = kv.copy(); badkv[2] = 49                     # kv_len < q_len
+    assert code(cu, badkv) == rpa.ERR_BAD_LENGTHS
+    badkv = kv.copy(); badkv[1] = 16 * 6 + 1             # needs 7 pages, row holds 6
+    assert code(cu, badkv) == rpa.ERR_BAD_LENGTHS
+    small = shape_of(wl, max_tokens=71)
+    assert code(cu, kv, small) == rpa.ERR_BAD_LENGTHS
+    few = shape_of(wl, max_seqs=3)
+    assert code(cu, kv, few) == rpa.ERR_BAD_LENGTHS
+
+
+def test_unsupported_shapes_are_rejected():
+    for kw in ({"head_dim": 96}, {"page_size": 24}, {"page_size": 8}, {"num_q_heads": 6, "num_kv_heads": 4},
+               {"num_q_heads": 24, "num_kv_heads": 8}):
+        args = dict(num_q_heads=4, num_kv_heads=2, head_dim=64, page_size=16, max_tokens=8, max_seqs=2,
+                    max_pages_per_seq=4, num_pages=8)
+        args.update(kw)
+        with pytest.raises(rpa.RpaError) as e:
+            rpa.plan_host(rpa.make_shape(**args), [0, 1], [1])
+        assert e.value.code == rpa.ERR_UNSUPPORTED
+
+
+def test_empty_batches():
+    wl = W.config(1)
+    units, items, stats = rpa.plan_host(shape_of(wl), [0], np.zeros(0, np.int32))
+    assert len(units) == 0 and len(items) == 0
+    # sequences with q_len 0 contribute nothing
+    units, items, stats = rpa.plan_host(shape_of(wl), [0, 0, 3, 3], [5, 10, 7])
+    assert set(units[:, F["seq"]].tolist()) == {1}
