@@ -247,6 +247,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     a.page_size_log2 = __builtin_ctz((unsigned)c->shape.page_size);
     a.max_pages_per_seq = c->shape.max_pages_per_seq;
     a.num_pages = c->shape.num_pages;
+    a.wide_tq_log2 = __builtin_ctz((unsigned)wide_q_tokens(a.hg));
     a.scale_log2 = sm_scale * 1.4426950408889634f;
 
     const rpa_work_unit* dev_units = (const rpa_work_unit*)slot.dev;

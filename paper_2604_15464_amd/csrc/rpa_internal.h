@@ -13,7 +13,7 @@ namespace rpa {
 // Tile geometry the kernels are compiled for.
 constexpr int kNarrowRows = 16;   // query rows (tokens x heads of one group) per narrow tile
 constexpr int kNarrowKvTile = 16; // KV positions per narrow pipeline stage
-constexpr int kWideQTokens = 64;  // query tokens per wide tile (x h_g heads = rows)
+constexpr int kWideRows = 256;    // query rows per wide tile = (256 / h_g) tokens x h_g heads
 constexpr int kWideKvTile = 64;   // KV positions per wide pipeline stage
 constexpr int kMaxWaves = 8;      // waves per narrow workgroup (one KV head each)
 
@@ -34,6 +34,9 @@ int build_plan(const rpa_shape& s, const int32_t* cu_q_lens, const int32_t* kv_l
 
 // Number of narrow query tokens per tile for a head-group size, or 0 if unsupported.
 inline int narrow_q_tokens(int hg) { return (hg >= 1 && hg <= kNarrowRows && kNarrowRows % hg == 0) ? kNarrowRows / hg : 0; }
+
+// Query tokens per wide tile.
+inline int wide_q_tokens(int hg) { return kWideRows / hg; }
 
 // Waves per narrow workgroup: the largest divisor of num_kv_heads not above kMaxWaves.
 inline int narrow_waves(int hkv) {
@@ -56,6 +59,7 @@ struct KernelArgs {
     float* part_ml; // [rows, 2] running max (log2 domain) and running sum
     int32_t num_q_heads, num_kv_heads, hg, head_dim;
     int32_t page_size_log2, max_pages_per_seq, num_pages;
+    int32_t wide_tq_log2; // log2 of the wide tile's token count
     float scale_log2; // sm_scale * log2(e)
 };
 

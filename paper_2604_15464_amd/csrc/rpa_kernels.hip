@@ -346,6 +346,286 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Wide kernel: query tile of 256 rows = (256 / h_g) tokens x the h_g heads of one
+// KV head (the paper's stacking of a group's heads against one K/V operand,
+// Sec. 3.1.2), four waves of 64 rows each, 32x32x16 MFMA.  K/V tiles of 64
+// positions are staged once per workgroup in LDS by asynchronous 16-byte loads
+// (each wave brings 16 positions) and double-buffered, one barrier per tile.
+// Used for prefill and chunked prefill; MFMA-bound.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256) rpa_wide_kernel(KernelArgs a) {
+    constexpr int ROWB = D * 2;
+    constexpr int NC = D / 8;
+    constexpr int TPI = 64 / NC;
+    constexpr int KT = kWideKvTile;
+    constexpr int TILEB = KT * ROWB;
+    constexpr int STAGEB = 2 * TILEB;
+    constexpr int NLD = 16 / TPI;  // loads per wave per K (or V) tile: 16 positions
+    constexpr int KSTEPS = D / 16; // 32x32x16 steps over head_dim
+    constexpr int DPL = D / 32;    // output dims per lane and per 32-dim MFMA tile set
+
+    extern __shared__ uint4 smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int g = blockIdx.y;
+    const int n32 = lane & 31;
+    const int h = lane >> 5;
+
+    const rpa_work_unit u = a.units[blockIdx.x];
+    const int hg = a.hg;
+    const int Hq = a.num_q_heads, Hkv = a.num_kv_heads;
+    const int ps_log2 = a.page_size_log2;
+    const int ps_mask = (1 << ps_log2) - 1;
+    const int num_pages = a.num_pages;
+    const int ctx = u.ctx;
+    const int tq_log2 = a.wide_tq_log2;
+    const char* const k_pages = (const char*)a.k_pages;
+    const char* const v_pages = (const char*)a.v_pages;
+    const char* const k_new = (const char*)a.k_new;
+    const char* const v_new = (const char*)a.v_new;
+    const const_i32_ptr pt_row = (const_i32_ptr)(uintptr_t)(a.page_table + (size_t)u.seq * a.max_pages_per_seq);
+    const uint32_t tokstride = (uint32_t)Hkv * ROWB;
+    const uint64_t k_delta = (uint64_t)k_pages - (uint64_t)k_new;
+    const uint64_t v_delta = (uint64_t)v_pages - (uint64_t)v_new;
+
+    // ---- rows of this lane: rho = 64*wave + 32*nt + lane%32 = head * TQ + token
+    int tok[2], head[2], limit[2];
+    bool row_ok[2];
+    bf16x8 qreg[2][KSTEPS];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const int rho = 64 * wave + 32 * nt + n32;
+        const int hh = rho >> tq_log2;
+        tok[nt] = rho & ((1 << tq_log2) - 1);
+        head[nt] = g * hg + hh;
+        row_ok[nt] = tok[nt] < u.n_q;
+        limit[nt] = row_ok[nt] ? ctx + u.q_pos0 + tok[nt] : -1;
+        const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok[nt] ? tok[nt] : 0)) * Hq + head[nt]) * D;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (row_ok[nt]) raw = *(const uint4*)(qrow + kk * 16 + h * 8);
+            qreg[nt][kk] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    wait_vmcnt<0>();
+
+    const uint32_t lds_base = lds_offset(smem);
+    const char* lds_ptr = (const char*)smem;
+    const int kv_begin = u.kv_begin, kv_end = u.kv_end;
+    const int ntiles = max(0, (kv_end - kv_begin + KT - 1) / KT);
+    const int min_limit = ctx + u.q_pos0; // the tile's first token sees the least
+
+    const int ld_tok = lane / NC;
+    const int ld_chunk = lane % NC;
+    uint32_t lane_off[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int r = 16 * wave + i * TPI + ld_tok; // row inside the 64-position tile
+        lane_off[i] = (uint32_t)g * ROWB + (uint32_t)((ld_chunk ^ (r % NC)) * 16);
+    }
+
+    auto issue_tile = [&](int t) {
+        const int p0w = kv_begin + t * KT + 16 * wave; // this wave's 16 positions
+        const int slot = t & 1;
+        const int pidx = __builtin_amdgcn_readfirstlane(min(p0w, kv_end - 1) >> ps_log2);
+        const int page = clamp_page(pt_row[pidx], num_pages);
+        const uint32_t ldsK = lds_base + slot * STAGEB + (16 * wave) * ROWB;
+        const uint32_t ldsV = ldsK + TILEB;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int pos = min(p0w + i * TPI + ld_tok, kv_end - 1);
+            const bool cached = pos < ctx;
+            const size_t tokidx = cached ? (((size_t)page << ps_log2) + (size_t)(pos & ps_mask))
+                                         : (size_t)(u.seq_q0 + pos - ctx);
+            const uint64_t off = (uint64_t)tokidx * tokstride + lane_off[i];
+            const uint64_t ka = (uint64_t)k_new + off + (cached ? k_delta : 0);
+            const uint64_t va = (uint64_t)v_new + off + (cached ? v_delta : 0);
+            async_load16((const void*)ka, ldsK + i * 1024);
+            async_load16((const void*)va, ldsV + i * 1024);
+        }
+    };
+
+    f32x16 o[2][DPL];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int j = 0; j < DPL; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[nt][j][v] = 0.f;
+    float m_run[2] = {-INFINITY, -INFINITY};
+    float l_run[2] = {0.f, 0.f};
+
+    if (ntiles > 0) issue_tile(0);
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        if (t + 1 < ntiles) issue_tile(t + 1);
+        const char* ldsK = lds_ptr + (t & 1) * STAGEB;
+        const char* ldsV = ldsK + TILEB;
+        const int pos0 = kv_begin + t * KT;
+
+        // ---- S^T = K Q^T for both 32-row groups (Alg. 1: S <- C_q C_k^T) -------
+        f32x16 s[2][2]; // [nt][mt]
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                s[0][mt][v] = 0.f;
+                s[1][mt][v] = 0.f;
+            }
+            const int row = 32 * mt + n32;
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) {
+                const int c = 2 * kk + h;
+                const bf16x8 kop = *(const bf16x8*)(ldsK + row * ROWB + ((c ^ (row % NC)) * 16));
+                s[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[0][kk], s[0][mt], 0, 0, 0);
+                s[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[1][kk], s[1][mt], 0, 0, 0);
+            }
+        }
+
+        // ---- mask + online softmax (Alg. 1: m~, P, l~) ------------------------
+        const bool need_mask = (pos0 + KT > kv_end) || (pos0 + KT - 1 > min_limit);
+        bf16x8 pop[2][4]; // [nt][k-step of 16 positions]
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float x = s[nt][mt][v] * a.scale_log2;
+                    if (need_mask) {
+                        const int pos = pos0 + 32 * mt + 8 * (v / 4) + 4 * h + (v % 4);
+                        const bool ok = (pos < kv_end) && (pos <= limit[nt]);
+                        x = ok ? x : -INFINITY;
+                    }
+                    s[nt][mt][v] = x;
+                    mx = fmaxf(mx, x);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[nt], mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = fast_exp2(m_run[nt] - m_use);
+            float psum = 0.f;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float pv = fast_exp2(s[nt][mt][v] - m_use);
+                    s[nt][mt][v] = pv;
+                    psum += pv;
+                }
+            l_run[nt] = l_run[nt] * alpha + psum;
+            m_run[nt] = m_new;
+#pragma unroll
+            for (int j = 0; j < DPL; ++j) o[nt][j] *= alpha;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const int mt = ks >> 1, v0 = 8 * (ks & 1);
+                union {
+                    uint32_t w[4];
+                    bf16x8 v;
+                } pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pk.w[e] = pack_bf16(s[nt][mt][v0 + 2 * e], s[nt][mt][v0 + 2 * e + 1]);
+                pop[nt][ks] = pk.v;
+            }
+        }
+
+        // ---- O^T += V^T P^T (Alg. 1: C_o <- ... + P C_v) --------------------------
+        // k-step ks covers positions 32*(ks/2) + 8*(2*(ks%2) + e/4) + 4*h + e%4,
+        // e = 0..7, which is the order the packed weights above are in.
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            uint32_t vr[8][DPL / 2];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int row = 32 * (ks >> 1) + 8 * (2 * (ks & 1) + (e >> 2)) + 4 * h + (e & 3);
+                const char* src = ldsV + row * ROWB + ((((n32 * DPL) / 8) ^ (row % NC)) * 16) + ((n32 * DPL) % 8) * 2;
+                if constexpr (DPL == 4) {
+                    const uint2 raw = *(const uint2*)src;
+                    vr[e][0] = raw.x;
+                    vr[e][1] = raw.y;
+                } else {
+                    vr[e][0] = *(const uint32_t*)src;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < DPL; ++j) {
+                const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                union {
+                    uint32_t w[4];
+                    bf16x8 v;
+                } vop;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) vop.w[d] = __builtin_amdgcn_perm(vr[2 * d + 1][j / 2], vr[2 * d][j / 2], sel);
+                o[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop.v, pop[0][ks], o[0][j], 0, 0, 0);
+                o[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop.v, pop[1][ks], o[1][j], 0, 0, 0);
+            }
+        }
+
+        wait_vmcnt<0>();
+        __syncthreads();
+    }
+
+    // ---- finalize (Alg. 1: diag(l)^-1 B_o) or store the partial state ------------
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
+        if (!row_ok[nt]) continue;
+        if (u.part_row < 0) {
+            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+            uint16_t* orow = a.out + ((size_t)(u.q_start + tok[nt]) * Hq + head[nt]) * D;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int mrow = 8 * (v / 4) + 4 * h + (v % 4);
+                if constexpr (DPL == 4) {
+                    uint2 w;
+                    w.x = pack_bf16(o[nt][0][v] * inv, o[nt][1][v] * inv);
+                    w.y = pack_bf16(o[nt][2][v] * inv, o[nt][3][v] * inv);
+                    *(uint2*)(orow + DPL * mrow) = w;
+                } else {
+                    *(uint32_t*)(orow + DPL * mrow) = pack_bf16(o[nt][0][v] * inv, o[nt][1][v] * inv);
+                }
+            }
+        } else {
+            const size_t prow = (size_t)u.part_row + (size_t)tok[nt] * Hq + head[nt];
+            float* po = a.part_o + prow * D;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int mrow = 8 * (v / 4) + 4 * h + (v % 4);
+#pragma unroll
+                for (int j = 0; j < DPL; ++j) po[DPL * mrow + j] = o[nt][j][v];
+            }
+            if (h == 0) {
+                a.part_ml[prow * 2] = m_run[nt];
+                a.part_ml[prow * 2 + 1] = l_tot;
+            }
+        }
+    }
+
+    // ---- fused cache update for the tile's new tokens (see the narrow kernel)
+    if (u.flags & 1) {
+        const int c = threadIdx.x % NC;
+        for (int t = threadIdx.x / NC; t < u.n_q; t += 256 / NC) {
+            const int pos = ctx + u.q_pos0 + t;
+            const int page = clamp_page(pt_row[pos >> ps_log2], num_pages);
+            const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * D + c * 8;
+            const size_t dst = ((((size_t)page << ps_log2) + (pos & ps_mask)) * Hkv + g) * D + c * 8;
+            const uint4 kk = *(const uint4*)(a.k_new + src);
+            const uint4 vv = *(const uint4*)(a.v_new + src);
+            *(uint4*)(a.k_pages + dst) = kk;
+            *(uint4*)(a.v_pages + dst) = vv;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Combine: merge the partial states of a tile that was cut into KV ranges.
 // States with different running maxima are rescaled to the common maximum and
@@ -385,6 +665,11 @@ static size_t narrow_lds_bytes(int waves) {
     return (size_t)waves * kNarrowStages * 2 * kNarrowKvTile * D * 2;
 }
 
+template <int D>
+static size_t wide_lds_bytes() {
+    return (size_t)2 * 2 * kWideKvTile * D * 2;
+}
+
 int kernels_init(int device, std::string& err) {
     (void)device;
     hipError_t e;
@@ -393,6 +678,12 @@ int kernels_init(int device, std::string& err) {
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<64, kNarrowStages>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<64>(kMaxWaves));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)wide_lds_bytes<128>());
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)wide_lds_bytes<64>());
     if (e != hipSuccess) {
         err = std::string("hipFuncSetAttribute: ") + hipGetErrorString(e);
         return (int)e;
@@ -414,9 +705,14 @@ int launch_narrow(const KernelArgs& a, int num_units, void* stream) {
 }
 
 int launch_wide(const KernelArgs& a, int num_units, void* stream) {
-    (void)a;
-    (void)stream;
-    return num_units > 0 ? (int)hipErrorNotSupported : 0;
+    if (num_units <= 0) return 0;
+    dim3 grid(num_units, a.num_kv_heads);
+    hipStream_t st = (hipStream_t)stream;
+    if (a.head_dim == 128)
+        hipLaunchKernelGGL((rpa_wide_kernel<128>), grid, dim3(256), wide_lds_bytes<128>(), st, a);
+    else
+        hipLaunchKernelGGL((rpa_wide_kernel<64>), grid, dim3(256), wide_lds_bytes<64>(), st, a);
+    return (int)hipGetLastError();
 }
 
 int launch_combine(const rpa_combine_item* items, int num_items, const float* part_o, const float* part_ml,

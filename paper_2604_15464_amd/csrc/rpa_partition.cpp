@@ -155,7 +155,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         }
         (wide ? any_wide : any_narrow) = true;
         const int32_t ctx = kv[r] - lq;
-        const int32_t tq = wide ? kWideQTokens : tq_narrow;
+        const int32_t tq = wide ? wide_q_tokens(hg) : tq_narrow;
         for (int32_t i0 = 0; i0 < lq; i0 += tq) {
             Tile t{r, i0, std::min(tq, lq - i0), 0, ctx, cu[r], wide};
             t.kv_hi = ctx + i0 + t.n_q;

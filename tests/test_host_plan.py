@@ -30,7 +30,8 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(l, name), name
 
 
-def check_plan(wl, units, items, stats, narrow_tq, wide_tq=64):
+def check_plan(wl, units, items, stats, narrow_tq, wide_tq=None):
+    wide_tq = wide_tq or 256 // (wl.num_q_heads // wl.num_kv_heads)
     cu = wl.cu_q_lens
     # per token: covered KV positions and writers
     cover = {}
