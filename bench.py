@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the ragged paged attention hot path on one MI355X.
+
+One "step" is one call of rpa_update_and_attend (host partition + work-list
+upload + fused cache write + attention + split merge) on a batch that is
+already resident in HBM.  The headline line is the decode workload
+(256 sequences, q_len 1, kv_len ~ U[512, 4096], Llama-3-8B attention shape)
+reported as achieved HBM GB/s; the prefill workload (8 x 2048 causal) is
+reported in the same JSON line under "prefill" as attention TFLOP/s.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Prints exactly one JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix, vendor figure
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_steps(ctx, x, table, wl, steps, warmup):
+    import torch
+
+    def call():
+        ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], table,
+                              cu, kv, wl.sm_scale, out=out)
+
+    cu, kv = wl.cu_q_lens, wl.kv_lens
+    out = torch.empty_like(x["q"])
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        call()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    return dt, prof, out
+
+
+def load_traffic(workload, kernel):
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f)[workload][kernel]["hbm_bytes_per_launch"]
+    except Exception:
+        return None
+
+
+def cpu_baseline(wl, budget_s=15.0):
+    """Time the CPU oracle, as it stands, on a bounded sample of the workload:
+    the first sequences of the batch with their own page pool."""
+    import numpy as np
+    import torch
+    from oracle import rpa_oracle as O
+    from paper_2604_15464_amd import workloads as W
+
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+
+    def sample(n):
+        rng = np.random.default_rng(wl.seed + 7)
+        q, kv = wl.q_lens[:n], wl.kv_lens[:n]
+        pages = int(W.pages_needed(kv, wl.page_size).sum())
+        return W.Workload(f"{wl.name}[:{n}]", wl.seed, wl.num_q_heads, wl.num_kv_heads, wl.head_dim,
+                          wl.page_size, pages, q, kv, W.make_page_table(kv, wl.page_size, pages, rng))
+
+    def run(sub):
+        x = {k: W.bits(v) for k, v in W.materialize(sub, "cpu", poison=False).items()}
+        t0 = time.perf_counter()
+        O.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], sub.page_table,
+                            sub.cu_q_lens, sub.kv_lens, sub.num_seqs, sub.sm_scale)
+        return time.perf_counter() - t0
+
+    probe = sample(min(4, wl.num_seqs))
+    t_probe = run(probe)
+    per_byte = t_probe / probe.algorithmic_bytes()
+    n = wl.num_seqs
+    while n > 4 and sample(n).algorithmic_bytes() * per_byte > budget_s:
+        n //= 2
+    sub = sample(n)
+    t = run(sub)
+    return sub, t, cores
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding in this path).")
+        sys.exit(2)
+    if args.steps < 1 or args.steps > 1024:
+        log("bench.py: --steps must be in 1..1024")
+        sys.exit(2)
+
+    import torch
+    from paper_2604_15464_amd import rpa
+    from paper_2604_15464_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- decode (headline) ----------------------------------------------------
+    wl = W.config(2)
+    x = W.materialize(wl, dev, poison=False)
+    table = torch.from_numpy(wl.page_table).to(dev)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl)
+    dt, prof, _ = time_steps(ctx, x, table, wl, args.steps, args.warmup)
+    info = ctx.plan_info()
+    ctx.close()
+    ms_per_step = dt / args.steps * 1e3
+    nbytes = wl.algorithmic_bytes()
+    value = nbytes / (dt / args.steps) / 1e9
+    narrow_ms = prof["narrow_ms"] / max(1, prof["calls"])
+    achieved = nbytes / (narrow_ms * 1e-3) / 1e9
+    log(f"decode: {ms_per_step * 1e3:.1f} us/step, kernel {narrow_ms * 1e3:.1f} us, combine "
+        f"{prof['combine_ms'] / max(1, prof['calls']) * 1e3:.1f} us, plan {info}")
+    result = {
+        "metric": "decode HBM GB/s",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "decode-only: 256 seqs, q_len 1, kv_len~U[512,4096], Hq32 Hkv8 D128 page16 "
+                               "(Llama-3-8B attention shape), fused KV write + attention",
+                   "algorithmic_bytes_per_step": nbytes, "variant": rpa.VARIANT_NAMES[info["variant"]],
+                   "units": info["num_narrow_units"], "max_splits": info["max_splits"]},
+        "pct_of_peak_hbm": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "roofline": {"kernel": "rpa_narrow_kernel<128>", "bound": "hbm", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": load_traffic(wl.name, "rpa_narrow_kernel"),
+                     "avg_kernel_ms": round(narrow_ms, 5)},
+    }
+    del x, table
+    torch.cuda.empty_cache()
+
+    # ---- prefill (second half of the metric) -------------------------------------
+    if not args.no_prefill:
+        wl3 = W.config(3)
+        x3 = W.materialize(wl3, dev, poison=False)
+        table3 = torch.from_numpy(wl3.page_table).to(dev)
+        ctx3 = rpa.RaggedPagedAttention.for_workload(wl3)
+        steps3 = max(5, min(args.steps, 30))
+        dt3, prof3, _ = time_steps(ctx3, x3, table3, wl3, steps3, max(2, min(args.warmup, 5)))
+        info3 = ctx3.plan_info()
+        ctx3.close()
+        flops = wl3.algorithmic_flops()
+        wide_ms = prof3["wide_ms"] / max(1, prof3["calls"])
+        tf = flops / (dt3 / steps3) / 1e12
+        tf_k = flops / (wide_ms * 1e-3) / 1e12
+        log(f"prefill: {dt3 / steps3 * 1e6:.1f} us/step, kernel {wide_ms * 1e3:.1f} us, plan {info3}")
+        result["prefill"] = {
+            "metric": "prefill attention TFLOP/s", "value": round(tf, 1), "unit": "TFLOP/s",
+            "steps": steps3, "ms_per_step": round(dt3 / steps3 * 1e3, 5),
+            "config": {"workload": "prefill-only: 8 seqs x 2048 causal, Hq32 Hkv8 D128 page16, all K/V new",
+                       "exact_causal_flops_per_step": flops, "units": info3["num_wide_units"]},
+            "pct_of_peak_bf16_mfma": round(100.0 * tf / MFMA_BF16_PEAK_TFLOPS, 2),
+            "roofline": {"kernel": "rpa_wide_kernel<128>", "bound": "mfma", "achieved": round(tf_k, 1),
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(tf_k / MFMA_BF16_PEAK_TFLOPS, 4),
+                         "traffic": load_traffic(wl3.name, "rpa_wide_kernel"),
+                         "avg_kernel_ms": round(wide_ms, 5)},
+        }
+        del x3, table3
+        torch.cuda.empty_cache()
+
+    # ---- CPU oracle baseline ---------------------------------------------------------
+    if not args.no_cpu_baseline:
+        sub, t_cpu, cores = cpu_baseline(wl)
+        result["cpu_baseline"] = {
+            "value": round(sub.algorithmic_bytes() / t_cpu / 1e9, 4), "unit": "GB/s", "cores": cores,
+            "kind": "oracle",
+            "sample": f"fp64 numpy oracle on the first {sub.num_seqs} of the workload's {wl.num_seqs} sequences "
+                      f"(own page pool, {sub.algorithmic_bytes() / 1e6:.0f} MB algorithmic), {t_cpu:.2f} s",
+        }
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

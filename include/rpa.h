@@ -170,6 +170,16 @@ int rpa_plan_info(const rpa_ctx* ctx, rpa_plan_stats* out);
  * defaults.                                                                   */
 int rpa_set_options(rpa_ctx* ctx, const rpa_options* opt);
 
+/* Kernel timing for benchmarks (not part of the paper's method).  While enabled,
+ * every call brackets each of its kernels with HIP events on the call's stream
+ * (at most 1024 calls are kept between two reads).  rpa_profile_read()
+ * synchronises on the last recorded event and adds up, over the calls since the
+ * previous read, the milliseconds spent in the narrow kernel, the wide kernel
+ * and the combine kernel; *calls receives the number of calls covered.        */
+int rpa_profile_enable(rpa_ctx* ctx, int on);
+int rpa_profile_read(rpa_ctx* ctx, float* narrow_ms, float* wide_ms, float* combine_ms,
+                     int32_t* calls);
+
 /* Host-only planning, no GPU needed: the work partition that
  * rpa_update_and_attend would use on a device with `num_cus` compute units
  * (Alg. 1's loops over sequences, Q blocks and KV blocks, flattened into units;

@@ -7,6 +7,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "rpa_internal.h"
 
@@ -27,7 +28,17 @@ struct Staging {
 
 } // namespace
 
+constexpr int kProfCalls = 1024;
+
+struct ProfEvents {
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr}; // narrow start, wide start, combine start, end
+    bool narrow = false, wide = false, combine = false;
+};
+
 struct rpa_ctx {
+    bool prof_on = false;
+    std::vector<ProfEvents> prof;
+    int prof_count = 0;
     rpa_shape shape{};
     rpa_options opt{};
     int device = 0;
@@ -88,7 +99,7 @@ extern "C" int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device) {
     c->partial_row_cap = std::min<int64_t>(
         std::max<int64_t>((int64_t)8 * shape->max_tokens * shape->num_q_heads,
                           (int64_t)12 * c->num_cus * kNarrowRows * shape->num_kv_heads),
-        (int64_t)1 << 22);
+        (int64_t)1 << 20);
     c->blob_bytes = (size_t)c->max_units * sizeof(rpa_work_unit) + (size_t)c->max_items * sizeof(rpa_combine_item);
 
     auto cleanup = [&](const char* what, hipError_t err) {
@@ -129,6 +140,9 @@ extern "C" void rpa_destroy(rpa_ctx* c) {
     }
     if (c->part_o) (void)hipFree(c->part_o);
     if (c->part_ml) (void)hipFree(c->part_ml);
+    for (auto& p : c->prof)
+        for (auto& e : p.ev)
+            if (e) (void)hipEventDestroy(e);
     delete c;
 }
 
@@ -148,6 +162,50 @@ extern "C" int rpa_set_options(rpa_ctx* c, const rpa_options* opt) {
     if (o.variant < RPA_VARIANT_AUTO || o.variant > RPA_VARIANT_MIXED || o.kv_chunk < 0 || o.wide_kv_chunk < 0)
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: bad value");
     c->opt = o;
+    return RPA_OK;
+}
+
+extern "C" int rpa_profile_enable(rpa_ctx* c, int on) {
+    if (!c) return RPA_ERR_INVALID_ARG;
+    if (on && c->prof.empty()) {
+        c->prof.resize(kProfCalls);
+        for (auto& p : c->prof)
+            for (auto& e : p.ev) {
+                hipError_t err = hipEventCreate(&e);
+                if (err != hipSuccess) return hip_fail(c, "hipEventCreate", err);
+            }
+    }
+    c->prof_on = on != 0;
+    c->prof_count = 0;
+    return RPA_OK;
+}
+
+extern "C" int rpa_profile_read(rpa_ctx* c, float* narrow_ms, float* wide_ms, float* combine_ms, int32_t* calls) {
+    if (!c || !narrow_ms || !wide_ms || !combine_ms || !calls) return RPA_ERR_INVALID_ARG;
+    *narrow_ms = *wide_ms = *combine_ms = 0.f;
+    *calls = c->prof_count;
+    for (int i = 0; i < c->prof_count; ++i) {
+        ProfEvents& p = c->prof[i];
+        hipError_t e = hipEventSynchronize(p.ev[3]);
+        if (e != hipSuccess) return hip_fail(c, "hipEventSynchronize", e);
+        float ms = 0.f;
+        if (p.narrow) {
+            e = hipEventElapsedTime(&ms, p.ev[0], p.ev[1]);
+            if (e != hipSuccess) return hip_fail(c, "hipEventElapsedTime", e);
+            *narrow_ms += ms;
+        }
+        if (p.wide) {
+            e = hipEventElapsedTime(&ms, p.ev[1], p.ev[2]);
+            if (e != hipSuccess) return hip_fail(c, "hipEventElapsedTime", e);
+            *wide_ms += ms;
+        }
+        if (p.combine) {
+            e = hipEventElapsedTime(&ms, p.ev[2], p.ev[3]);
+            if (e != hipSuccess) return hip_fail(c, "hipEventElapsedTime", e);
+            *combine_ms += ms;
+        }
+    }
+    c->prof_count = 0;
     return RPA_OK;
 }
 
@@ -251,16 +309,30 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     a.scale_log2 = sm_scale * 1.4426950408889634f;
 
     const rpa_work_unit* dev_units = (const rpa_work_unit*)slot.dev;
+    ProfEvents* pe = (c->prof_on && c->prof_count < kProfCalls) ? &c->prof[c->prof_count] : nullptr;
+    auto mark = [&](int i) {
+        if (pe) (void)hipEventRecord(pe->ev[i], st);
+    };
     int hrc;
     a.units = dev_units;
+    mark(0);
     hrc = launch_narrow(a, (int)n_narrow, stream);
     if (hrc != 0) return hip_fail(c, "narrow kernel launch", (hipError_t)hrc);
+    mark(1);
     a.units = dev_units + n_narrow;
     hrc = launch_wide(a, (int)n_wide, stream);
     if (hrc != 0) return hip_fail(c, "wide kernel launch", (hipError_t)hrc);
+    mark(2);
     hrc = launch_combine((const rpa_combine_item*)((char*)slot.dev + items_off), (int)n_items, c->part_o, c->part_ml,
                          (uint16_t*)out, a.num_q_heads, a.head_dim, stream);
     if (hrc != 0) return hip_fail(c, "combine kernel launch", (hipError_t)hrc);
+    mark(3);
+    if (pe) {
+        pe->narrow = n_narrow > 0;
+        pe->wide = n_wide > 0;
+        pe->combine = n_items > 0;
+        ++c->prof_count;
+    }
     c->last = plan.stats;
     return RPA_OK;
 }

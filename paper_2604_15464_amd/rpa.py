@@ -59,7 +59,7 @@ class RpaError(RuntimeError):
 _lib = None
 
 EXPORTS = ("rpa_create", "rpa_destroy", "rpa_update_and_attend", "rpa_last_error", "rpa_plan_info",
-           "rpa_set_options", "rpa_plan_host")
+           "rpa_set_options", "rpa_plan_host", "rpa_profile_enable", "rpa_profile_read")
 
 
 def lib():
@@ -84,6 +84,11 @@ def lib():
     l.rpa_plan_info.restype = C.c_int
     l.rpa_set_options.argtypes = [C.c_void_p, C.POINTER(Options)]
     l.rpa_set_options.restype = C.c_int
+    l.rpa_profile_enable.argtypes = [C.c_void_p, C.c_int]
+    l.rpa_profile_enable.restype = C.c_int
+    l.rpa_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float),
+                                   C.POINTER(C.c_int32)]
+    l.rpa_profile_read.restype = C.c_int
     l.rpa_plan_host.argtypes = [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(Options), C.c_int,
                                 C.POINTER(WorkUnit), C.c_int32, C.POINTER(CombineItem), C.c_int32,
                                 C.POINTER(PlanStats)]
@@ -171,6 +176,19 @@ class RaggedPagedAttention:
         if rc != RPA_OK:
             raise RpaError(rc, "rpa_plan_info")
         return st.as_dict()
+
+    def profile_enable(self, on=True):
+        rc = self._lib.rpa_profile_enable(self._ctx, 1 if on else 0)
+        if rc != RPA_OK:
+            raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())
+
+    def profile_read(self) -> dict:
+        """Milliseconds per kernel summed over the calls since the last read."""
+        a, b, c_, n = C.c_float(), C.c_float(), C.c_float(), C.c_int32()
+        rc = self._lib.rpa_profile_read(self._ctx, C.byref(a), C.byref(b), C.byref(c_), C.byref(n))
+        if rc != RPA_OK:
+            raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())
+        return {"narrow_ms": a.value, "wide_ms": b.value, "combine_ms": c_.value, "calls": n.value}
 
     def update_and_attend_raw(self, out_ptr, q_ptr, k_new_ptr, v_new_ptr, k_pages_ptr, v_pages_ptr,
                               page_table_ptr, cu_q_lens, kv_lens, num_seqs, sm_scale, stream_ptr):
