@@ -198,3 +198,42 @@ def test_chunked_prefill_carries_cache_across_calls():
     assert np.array_equal(W.bits(x["v_pages"]), vp_ref)
     err = np.abs(to_f64(torch.cat(outs)) - ref)
     assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
+
+
+# ---------------------------------------------------------------------------
+# Full-size configs, in the launch configuration bench.py times (AUTO variant,
+# default chunking).  The cache is compared in full, bit for bit; outputs are
+# compared on a sample of sequences that the oracle computes one by one.
+# ---------------------------------------------------------------------------
+def _full_case(idx, sample):
+    wl = W.config(idx)
+    res = run_case(wl, seqs=sample(wl))
+    check(wl, res, seqs=sample(wl))
+    # every row of the batch must at least be finite
+    t = wl.num_tokens
+    assert torch.isfinite(res["out"][:t].float()).all()
+    return wl, res
+
+
+def test_full_config2_decode():
+    wl, res = _full_case(2, lambda wl: [0, 1, 17, 100, int(np.argmax(wl.kv_lens)), int(np.argmin(wl.kv_lens)), 255])
+    assert res["info"]["variant"] == rpa.VARIANT_DECODE and res["info"]["max_splits"] > 1
+
+
+def test_full_config3_prefill():
+    wl, res = _full_case(3, lambda wl: [0, 5])
+    assert res["info"]["variant"] == rpa.VARIANT_PREFILL
+
+
+def test_full_config4_mixed():
+    def sample(wl):
+        chunks = np.nonzero(wl.q_lens > 1)[0].tolist()
+        dec = np.nonzero(wl.q_lens == 1)[0]
+        return chunks + dec[[0, 7, -1]].tolist() + [int(dec[np.argmax(wl.kv_lens[dec])])]
+    wl, res = _full_case(4, sample)
+    assert res["info"]["variant"] == rpa.VARIANT_MIXED
+
+
+def test_full_config5_long_decode():
+    wl, res = _full_case(5, lambda wl: [0, int(np.argmax(wl.kv_lens)), int(np.argmin(wl.kv_lens))])
+    assert res["info"]["max_splits"] > 8
