@@ -64,8 +64,10 @@ typedef enum {
     RPA_VARIANT_MIXED = 3    /* short-query sequences narrow, the rest wide           */
 } rpa_variant;
 
-/* One unit of work = one workgroup: a query tile of one sequence against a
- * range of that sequence's KV positions.  Exposed for rpa_plan_host().       */
+/* One unit of work: a query tile of one sequence against a range of that
+ * sequence's KV positions.  A wide unit is one workgroup; narrow units are
+ * grouped into bins of equal KV volume, one workgroup per bin.  Exposed for
+ * rpa_plan_host().                                                            */
 typedef struct {
     int32_t seq;        /* sequence index r                                           */
     int32_t q_start;    /* packed token index of the tile's first query token         */
@@ -78,7 +80,8 @@ typedef struct {
     int32_t part_row;   /* first row of this unit's split partial, or -1: write out   */
     int32_t flags;      /* bit 0: this unit writes the tile's new K/V into the pages;
                            bit 1: wide kernel (else narrow)                           */
-    int32_t reserved[2];
+    int32_t bin;        /* narrow units: index of the workgroup that runs the unit     */
+    int32_t reserved;
 } rpa_work_unit;
 
 /* Merge job for one query tile that was split over KV ranges.                */
@@ -95,7 +98,9 @@ typedef struct {
     int32_t num_wide_units;
     int32_t num_combine_items;
     int32_t max_splits;      /* largest number of KV ranges one tile was cut into     */
-    int32_t kv_chunk;        /* target KV positions per unit                          */
+    int32_t kv_chunk;        /* KV positions per narrow workgroup (bin)               */
+    int32_t num_narrow_bins; /* workgroups (x num_kv_heads / narrow_waves) of the narrow kernel */
+    int32_t narrow_waves;    /* waves per narrow workgroup                            */
     int64_t partial_rows;    /* fp32 partial rows used                                */
     int64_t workspace_bytes; /* device workspace owned by the context                 */
 } rpa_plan_stats;
@@ -104,9 +109,16 @@ typedef struct {
  * beyond floating-point summation order.                                      */
 typedef struct {
     int32_t variant;   /* rpa_variant; AUTO selects from the length distribution      */
-    int32_t kv_chunk;  /* KV positions per narrow unit (rounded up to 16); 0 = auto   */
+    int32_t kv_chunk;  /* cap on KV positions per narrow unit (rounded up to 16); 0 = none */
     int32_t wide_kv_chunk; /* KV positions per wide unit (rounded up to 64); 0 = auto */
-    int32_t reserved[5];
+    int32_t narrow_waves;  /* waves (= KV heads) per narrow workgroup: a divisor of
+                              num_kv_heads, at most 8; 0 = auto                       */
+    int32_t units_per_cu;  /* narrow bins per resident workgroup slot (1 = exactly one
+                              wave of workgroups); 0 = default                        */
+    int32_t ablate;        /* measurement only (the paper's ablation method, Sec. 4):
+                              bit 0 = skip the attention math of the narrow kernel (loads
+                              and stores stay); results are then meaningless           */
+    int32_t reserved[2];
 } rpa_options;
 
 typedef struct rpa_ctx rpa_ctx;

@@ -20,9 +20,10 @@ constexpr int kRing = 4; // staging slots: the host may run this many calls ahea
 thread_local std::string g_err; // errors without a context
 
 struct Staging {
-    void* host = nullptr;       // pinned
-    void* dev = nullptr;        // device copy of the same blob
-    hipEvent_t copied = nullptr; // host buffer may be overwritten once this has passed
+    void* host = nullptr;        // pinned
+    void* dev = nullptr;         // device copy of the same blob
+    hipEvent_t copied = nullptr; // upload finished (recorded on the upload stream)
+    hipEvent_t done = nullptr;   // kernels that read `dev` finished (recorded on the caller's stream)
     bool used = false;
 };
 
@@ -49,6 +50,7 @@ struct rpa_ctx {
     size_t blob_bytes = 0;
     Staging ring[kRing];
     int ring_pos = 0;
+    hipStream_t upload = nullptr; // work lists are uploaded here, ahead of the caller's stream
     float* part_o = nullptr;
     float* part_ml = nullptr;
     int64_t workspace_bytes = 0;
@@ -100,7 +102,7 @@ extern "C" int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device) {
         std::max<int64_t>((int64_t)8 * shape->max_tokens * shape->num_q_heads,
                           (int64_t)12 * c->num_cus * kNarrowRows * shape->num_kv_heads),
         (int64_t)1 << 20);
-    c->blob_bytes = (size_t)c->max_units * sizeof(rpa_work_unit) + (size_t)c->max_items * sizeof(rpa_combine_item);
+    c->blob_bytes = (size_t)c->max_units * (sizeof(rpa_work_unit) + sizeof(rpa_combine_item) + sizeof(int32_t)) + 64;
 
     auto cleanup = [&](const char* what, hipError_t err) {
         int r = hip_fail(nullptr, what, err);
@@ -114,8 +116,12 @@ extern "C" int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device) {
         if (e != hipSuccess) return cleanup("hipMalloc", e);
         e = hipEventCreateWithFlags(&c->ring[i].copied, hipEventDisableTiming);
         if (e != hipSuccess) return cleanup("hipEventCreate", e);
+        e = hipEventCreateWithFlags(&c->ring[i].done, hipEventDisableTiming);
+        if (e != hipSuccess) return cleanup("hipEventCreate", e);
         c->workspace_bytes += (int64_t)c->blob_bytes;
     }
+    e = hipStreamCreateWithFlags(&c->upload, hipStreamNonBlocking);
+    if (e != hipSuccess) return cleanup("hipStreamCreate", e);
     const size_t po = (size_t)c->partial_row_cap * shape->head_dim * sizeof(float);
     const size_t pml = (size_t)c->partial_row_cap * 2 * sizeof(float);
     e = hipMalloc((void**)&c->part_o, po);
@@ -135,9 +141,11 @@ extern "C" void rpa_destroy(rpa_ctx* c) {
     if (!c) return;
     for (int i = 0; i < kRing; ++i) {
         if (c->ring[i].copied) (void)hipEventDestroy(c->ring[i].copied);
+        if (c->ring[i].done) (void)hipEventDestroy(c->ring[i].done);
         if (c->ring[i].host) (void)hipHostFree(c->ring[i].host);
         if (c->ring[i].dev) (void)hipFree(c->ring[i].dev);
     }
+    if (c->upload) (void)hipStreamDestroy(c->upload);
     if (c->part_o) (void)hipFree(c->part_o);
     if (c->part_ml) (void)hipFree(c->part_ml);
     for (auto& p : c->prof)
@@ -159,7 +167,9 @@ extern "C" int rpa_set_options(rpa_ctx* c, const rpa_options* opt) {
     if (!c) return RPA_ERR_INVALID_ARG;
     rpa_options o{};
     if (opt) o = *opt;
-    if (o.variant < RPA_VARIANT_AUTO || o.variant > RPA_VARIANT_MIXED || o.kv_chunk < 0 || o.wide_kv_chunk < 0)
+    if (o.variant < RPA_VARIANT_AUTO || o.variant > RPA_VARIANT_MIXED || o.kv_chunk < 0 || o.wide_kv_chunk < 0 ||
+        o.units_per_cu < 0 || o.narrow_waves < 0 || o.narrow_waves > kMaxWaves ||
+        (o.narrow_waves > 0 && c->shape.num_kv_heads % o.narrow_waves != 0))
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: bad value");
     c->opt = o;
     return RPA_OK;
@@ -265,26 +275,30 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     hipError_t e = hipSetDevice(c->device);
     if (e != hipSuccess) return hip_fail(c, "hipSetDevice", e);
     hipStream_t st = (hipStream_t)stream;
+    // The work list goes up on the library's own stream so that it overlaps the
+    // previous call's kernels; the caller's stream only waits for the event.
     Staging& slot = c->ring[c->ring_pos];
     if (slot.used) {
-        e = hipEventSynchronize(slot.copied);
+        e = hipEventSynchronize(slot.done);
         if (e != hipSuccess) return hip_fail(c, "hipEventSynchronize", e);
     }
     char* h = (char*)slot.host;
     const size_t units_bytes = (n_narrow + n_wide) * sizeof(rpa_work_unit);
-    const size_t items_off = (size_t)c->max_units * sizeof(rpa_work_unit);
+    const size_t items_off = (units_bytes + 15) & ~(size_t)15;
+    const size_t bins_off = items_off + n_items * sizeof(rpa_combine_item);
+    const size_t n_bins = n_narrow ? plan.bins.size() - 1 : 0;
+    const size_t total_bytes = bins_off + plan.bins.size() * sizeof(int32_t);
+    if (total_bytes > c->blob_bytes) return fail(c, RPA_ERR_WORKSPACE, "work list larger than the workspace sized at create");
     if (n_narrow) std::memcpy(h, plan.narrow.data(), n_narrow * sizeof(rpa_work_unit));
     if (n_wide) std::memcpy(h + n_narrow * sizeof(rpa_work_unit), plan.wide.data(), n_wide * sizeof(rpa_work_unit));
-    e = hipMemcpyAsync(slot.dev, h, units_bytes, hipMemcpyHostToDevice, st);
+    if (n_items) std::memcpy(h + items_off, plan.items.data(), n_items * sizeof(rpa_combine_item));
+    std::memcpy(h + bins_off, plan.bins.data(), plan.bins.size() * sizeof(int32_t));
+    e = hipMemcpyAsync(slot.dev, h, total_bytes, hipMemcpyHostToDevice, c->upload);
     if (e != hipSuccess) return hip_fail(c, "hipMemcpyAsync", e);
-    if (n_items) {
-        std::memcpy(h + items_off, plan.items.data(), n_items * sizeof(rpa_combine_item));
-        e = hipMemcpyAsync((char*)slot.dev + items_off, h + items_off, n_items * sizeof(rpa_combine_item),
-                           hipMemcpyHostToDevice, st);
-        if (e != hipSuccess) return hip_fail(c, "hipMemcpyAsync", e);
-    }
-    e = hipEventRecord(slot.copied, st);
+    e = hipEventRecord(slot.copied, c->upload);
     if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
+    e = hipStreamWaitEvent(st, slot.copied, 0);
+    if (e != hipSuccess) return hip_fail(c, "hipStreamWaitEvent", e);
     slot.used = true;
     c->ring_pos = (c->ring_pos + 1) % kRing;
 
@@ -307,6 +321,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     a.num_pages = c->shape.num_pages;
     a.wide_tq_log2 = __builtin_ctz((unsigned)wide_q_tokens(a.hg));
     a.scale_log2 = sm_scale * 1.4426950408889634f;
+    a.ablate = c->opt.ablate;
 
     const rpa_work_unit* dev_units = (const rpa_work_unit*)slot.dev;
     ProfEvents* pe = (c->prof_on && c->prof_count < kProfCalls) ? &c->prof[c->prof_count] : nullptr;
@@ -315,8 +330,9 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     };
     int hrc;
     a.units = dev_units;
+    a.bins = (const int32_t*)((const char*)slot.dev + bins_off);
     mark(0);
-    hrc = launch_narrow(a, (int)n_narrow, stream);
+    hrc = launch_narrow(a, (int)n_bins, plan.stats.narrow_waves, stream);
     if (hrc != 0) return hip_fail(c, "narrow kernel launch", (hipError_t)hrc);
     mark(1);
     a.units = dev_units + n_narrow;
@@ -327,6 +343,8 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
                          (uint16_t*)out, a.num_q_heads, a.head_dim, stream);
     if (hrc != 0) return hip_fail(c, "combine kernel launch", (hipError_t)hrc);
     mark(3);
+    e = hipEventRecord(slot.done, st);
+    if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
     if (pe) {
         pe->narrow = n_narrow > 0;
         pe->wide = n_wide > 0;

@@ -16,9 +16,12 @@ constexpr int kNarrowKvTile = 16; // KV positions per narrow pipeline stage
 constexpr int kWideRows = 256;    // query rows per wide tile = (256 / h_g) tokens x h_g heads
 constexpr int kWideKvTile = 64;   // KV positions per wide pipeline stage
 constexpr int kMaxWaves = 8;      // waves per narrow workgroup (one KV head each)
+constexpr int kNarrowStages = 2;   // LDS ring depth of a narrow wave
+constexpr int kLdsBytesPerCu = 160 * 1024;
 
 struct Plan {
-    std::vector<rpa_work_unit> narrow; // launch order
+    std::vector<rpa_work_unit> narrow; // grouped by bin
+    std::vector<int32_t> bins;         // bins[b] .. bins[b+1]: the narrow units of workgroup b
     std::vector<rpa_work_unit> wide;   // launch order
     std::vector<rpa_combine_item> items;
     rpa_plan_stats stats{};
@@ -38,13 +41,17 @@ inline int narrow_q_tokens(int hg) { return (hg >= 1 && hg <= kNarrowRows && kNa
 // Query tokens per wide tile.
 inline int wide_q_tokens(int hg) { return kWideRows / hg; }
 
-// Waves per narrow workgroup: the largest divisor of num_kv_heads not above kMaxWaves.
+// Default waves per narrow workgroup: the largest divisor of num_kv_heads not
+// above 4 (two workgroups of 64 KB LDS per compute unit at head_dim 128).
 inline int narrow_waves(int hkv) {
     int w = 1;
-    for (int d = 1; d <= kMaxWaves; ++d)
+    for (int d = 1; d <= 4; ++d)
         if (hkv % d == 0) w = d;
     return w;
 }
+
+// LDS ring bytes of one narrow wave: stages x (K tile + V tile).
+inline int narrow_lds_per_wave(int head_dim) { return kNarrowStages * 2 * kNarrowKvTile * head_dim * 2; }
 
 struct KernelArgs {
     const uint16_t* q;
@@ -55,16 +62,18 @@ struct KernelArgs {
     uint16_t* out;
     const int32_t* page_table;
     const rpa_work_unit* units;
+    const int32_t* bins; // narrow kernel: unit range of each workgroup
     float* part_o;  // [rows, D] un-normalised partial outputs
     float* part_ml; // [rows, 2] running max (log2 domain) and running sum
     int32_t num_q_heads, num_kv_heads, hg, head_dim;
     int32_t page_size_log2, max_pages_per_seq, num_pages;
     int32_t wide_tq_log2; // log2 of the wide tile's token count
     float scale_log2; // sm_scale * log2(e)
+    int32_t ablate;   // measurement switches (rpa_options.ablate)
 };
 
 // Launchers (rpa_kernels.hip).  Return a hipError_t value as int.
-int launch_narrow(const KernelArgs& a, int num_units, void* stream);
+int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream);
 int launch_wide(const KernelArgs& a, int num_units, void* stream);
 int launch_combine(const rpa_combine_item* items, int num_items, const float* part_o,
                    const float* part_ml, uint16_t* out, int num_q_heads, int head_dim,

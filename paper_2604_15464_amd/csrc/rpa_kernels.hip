@@ -94,25 +94,45 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     const int n = lane & 15;                  // query row of this lane (MFMA column)
     const int quad = lane >> 4;
 
-    const rpa_work_unit u = a.units[blockIdx.x];
     const int hg = a.hg;
     const int Hq = a.num_q_heads, Hkv = a.num_kv_heads;
     const int ps_log2 = a.page_size_log2;
     const int ps_mask = (1 << ps_log2) - 1;
     const int num_pages = a.num_pages;
-    const int ctx = u.ctx;
     const char* const k_pages = (const char*)a.k_pages;
     const char* const v_pages = (const char*)a.v_pages;
     const char* const k_new = (const char*)a.k_new;
     const char* const v_new = (const char*)a.v_new;
-    const const_i32_ptr pt_row = (const_i32_ptr)(uintptr_t)(a.page_table + (size_t)u.seq * a.max_pages_per_seq);
     const uint32_t tokstride = (uint32_t)Hkv * ROWB; // bytes between consecutive tokens
     const uint64_t k_delta = (uint64_t)k_pages - (uint64_t)k_new;
     const uint64_t v_delta = (uint64_t)v_pages - (uint64_t)v_new;
-
-    // ---- query operand: row n = (token n / hg, head g*hg + n % hg) -----------
-    const int tok_n = n / hg;
+    const int tok_n = n / hg; // row n = (token n / hg, head g*hg + n % hg)
     const int hh = n - tok_n * hg;
+    const uint32_t lds_wave = lds_offset(smem) + wave * (NST * STAGEB);
+    const char* lds_wave_ptr = (const char*)smem + wave * (NST * STAGEB);
+
+    // per-lane constants of the gather: load i of a tile brings token
+    // m = i*TPI + lane/NC; the lane fetches the 16-byte chunk that the XOR
+    // swizzle assigns to its LDS slot.
+    const int ld_tok = lane / NC;
+    const int ld_chunk = lane % NC;
+    uint32_t lane_off[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int m = i * TPI + ld_tok;
+        lane_off[i] = (uint32_t)g * ROWB + (uint32_t)((ld_chunk ^ (m % NC)) * 16);
+    }
+
+    // The workgroup walks the units of its bin back to back; the waves never
+    // synchronise with each other.
+    const const_i32_ptr bins = (const_i32_ptr)(uintptr_t)a.bins;
+    const int unit_end = bins[blockIdx.x + 1];
+    for (int ui = bins[blockIdx.x]; ui < unit_end; ++ui) {
+    const rpa_work_unit u = a.units[ui];
+    const int ctx = u.ctx;
+    const const_i32_ptr pt_row = (const_i32_ptr)(uintptr_t)(a.page_table + (size_t)u.seq * a.max_pages_per_seq);
+
+    // ---- query operand ---------------------------------------------------------
     const bool row_ok = tok_n < u.n_q;
     const int limit_n = row_ok ? ctx + u.q_pos0 + tok_n : -1; // last visible KV position
     bf16x8 qreg[KSTEPS];
@@ -129,23 +149,8 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     // the ring's asynchronous loads only.
     wait_vmcnt<0>();
 
-    const uint32_t lds_wave = lds_offset(smem) + wave * (NST * STAGEB);
-    const char* lds_wave_ptr = (const char*)smem + wave * (NST * STAGEB);
-
     const int kv_begin = u.kv_begin, kv_end = u.kv_end;
     const int ntiles = max(0, (kv_end - kv_begin + kNarrowKvTile - 1) / kNarrowKvTile);
-
-    // per-lane constants of the gather: load i of a tile brings token
-    // m = i*TPI + lane/NC; the lane fetches the 16-byte chunk that the XOR
-    // swizzle assigns to its LDS slot.
-    const int ld_tok = lane / NC;
-    const int ld_chunk = lane % NC;
-    uint32_t lane_off[NLD];
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-        const int m = i * TPI + ld_tok;
-        lane_off[i] = (uint32_t)g * ROWB + (uint32_t)((ld_chunk ^ (m % NC)) * 16);
-    }
 
     auto issue_tile = [&](int t) {
         const int pos0 = kv_begin + t * kNarrowKvTile;
@@ -208,6 +213,10 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         const char* ldsK = lds_wave_ptr + (t % NST) * STAGEB;
         const char* ldsV = ldsK + TILEB;
         const int pos0 = kv_begin + t * kNarrowKvTile;
+        if (a.ablate & 1) { // measurement: loads only
+            acc[0][0] += __uint_as_float(*(const uint32_t*)(ldsK + lane * 4)) + __uint_as_float(*(const uint32_t*)(ldsV + lane * 4));
+            continue;
+        }
 
         // ---- S^T = K Q^T (Alg. 1: S <- C_q C_k^T) --------------------------------
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
@@ -315,9 +324,10 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     // ---- finalize (Alg. 1: diag(l)^-1 B_o) or store the partial state ------------
     float l_tot = l_run + __shfl_xor(l_run, 16);
     l_tot += __shfl_xor(l_tot, 32);
-    if (!row_ok) return;
     const int head = g * hg + hh;
-    if (u.part_row < 0) {
+    if (!row_ok) {
+        // nothing to store for a padding row
+    } else if (u.part_row < 0) {
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
         uint16_t* orow = a.out + ((size_t)(u.q_start + tok_n) * Hq + head) * D;
 #pragma unroll
@@ -344,6 +354,9 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
             a.part_ml[prow * 2 + 1] = l_tot;
         }
     }
+    // every store and load of this unit is complete before the next unit's ring starts
+    wait_vmcnt<0>();
+    } // units of the bin
 }
 
 
@@ -635,31 +648,44 @@ __global__ void __launch_bounds__(256) rpa_combine_kernel(const rpa_combine_item
                                                           const float* __restrict__ part_o,
                                                           const float* __restrict__ part_ml,
                                                           uint16_t* __restrict__ out, int Hq, int D) {
+    // one thread = four consecutive dims of one row; blockIdx.y walks row blocks
     const rpa_combine_item it = items[blockIdx.x];
-    const int dim = threadIdx.x % D;
-    const int rstep = blockDim.x / D;
-    for (int row = blockIdx.y * rstep + threadIdx.x / D; row < it.rows; row += rstep * gridDim.y) {
-        float big = -INFINITY;
-        for (int s = 0; s < it.n_splits; ++s)
-            big = fmaxf(big, part_ml[((size_t)it.part_row + (size_t)s * it.rows + row) * 2]);
-        float num = 0.f, den = 0.f;
+    const int lanes_per_row = D / 4;
+    const int rows_per_block = blockDim.x / lanes_per_row;
+    const int dim = (threadIdx.x % lanes_per_row) * 4;
+    for (int row = blockIdx.y * rows_per_block + threadIdx.x / lanes_per_row; row < it.rows;
+         row += rows_per_block * gridDim.y) {
+        const size_t first = (size_t)it.part_row + row;
+        float m_run = -INFINITY, den = 0.f;
+        float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+        // online merge: the loads of different splits are independent
+#pragma unroll 4
         for (int s = 0; s < it.n_splits; ++s) {
-            const size_t prow = (size_t)it.part_row + (size_t)s * it.rows + row;
-            const float m = part_ml[prow * 2];
-            const float w = (m == -INFINITY) ? 0.f : fast_exp2(m - big);
-            num += w * part_o[prow * D + dim];
-            den += w * part_ml[prow * 2 + 1];
+            const size_t prow = first + (size_t)s * it.rows;
+            const float2 ml = *(const float2*)(part_ml + prow * 2);
+            const float4 o = *(const float4*)(part_o + prow * D + dim);
+            const float m_new = fmaxf(m_run, ml.x);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float a_old = fast_exp2(m_run - m_use);
+            const float a_new = fast_exp2(ml.x - m_use);
+            num.x = num.x * a_old + o.x * a_new;
+            num.y = num.y * a_old + o.y * a_new;
+            num.z = num.z * a_old + o.z * a_new;
+            num.w = num.w * a_old + o.w * a_new;
+            den = den * a_old + ml.y * a_new;
+            m_run = m_new;
         }
-        const float r = den > 0.f ? num / den : 0.f;
-        out[((size_t)it.q_start * Hq + row) * D + dim] = (uint16_t)(pack_bf16(r, 0.f) & 0xFFFFu);
+        const float inv = den > 0.f ? 1.f / den : 0.f;
+        uint2 w;
+        w.x = pack_bf16(num.x * inv, num.y * inv);
+        w.y = pack_bf16(num.z * inv, num.w * inv);
+        *(uint2*)(out + ((size_t)it.q_start * Hq + row) * D + dim) = w;
     }
 }
 
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
-constexpr int kNarrowStages = 2;
-
 template <int D>
 static size_t narrow_lds_bytes(int waves) {
     return (size_t)waves * kNarrowStages * 2 * kNarrowKvTile * D * 2;
@@ -691,10 +717,9 @@ int kernels_init(int device, std::string& err) {
     return 0;
 }
 
-int launch_narrow(const KernelArgs& a, int num_units, void* stream) {
-    if (num_units <= 0) return 0;
-    const int waves = narrow_waves(a.num_kv_heads);
-    dim3 grid(num_units, a.num_kv_heads / waves);
+int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream) {
+    if (num_bins <= 0) return 0;
+    dim3 grid(num_bins, a.num_kv_heads / waves);
     dim3 block(64 * waves);
     hipStream_t st = (hipStream_t)stream;
     if (a.head_dim == 128)
@@ -718,7 +743,7 @@ int launch_wide(const KernelArgs& a, int num_units, void* stream) {
 int launch_combine(const rpa_combine_item* items, int num_items, const float* part_o, const float* part_ml,
                    uint16_t* out, int num_q_heads, int head_dim, void* stream) {
     if (num_items <= 0) return 0;
-    dim3 grid(num_items, 4);
+    dim3 grid(num_items, 8);
     hipLaunchKernelGGL(rpa_combine_kernel, grid, dim3(256), 0, (hipStream_t)stream, items, part_o, part_ml, out,
                        num_q_heads, head_dim);
     return (int)hipGetLastError();

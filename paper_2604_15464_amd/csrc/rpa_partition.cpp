@@ -2,9 +2,12 @@
 //
 // Algorithm 1 of the paper walks sequences, Q blocks and KV blocks serially on
 // one core.  Here the same iteration space is flattened into independent units
-// (sequence, Q tile, KV range), one workgroup each, so that 256 compute units
-// stay busy: a tile whose KV range is long is cut into several ranges whose
-// partial softmax states are merged afterwards.  The regime split of Sec. 3.4
+// (sequence, Q tile, KV range) so that 256 compute units stay busy: a tile whose
+// KV range is long is cut into several ranges whose partial softmax states are
+// merged afterwards.  Narrow (bandwidth-bound) units are dealt into bins of
+// equal KV volume, one resident workgroup per bin, by cutting the concatenated
+// KV stream of all narrow tiles at equal intervals; wide (MFMA-bound) units are
+// one workgroup each, longest first.  The regime split of Sec. 3.4
 // (decode-only / prefill-only / mixed) becomes a per-sequence choice between
 // the narrow and the wide kernel.
 #include <algorithm>
@@ -100,7 +103,8 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         return RPA_ERR_BAD_LENGTHS;
     }
     if (opt.variant < RPA_VARIANT_AUTO || opt.variant > RPA_VARIANT_MIXED || opt.kv_chunk < 0 ||
-        opt.wide_kv_chunk < 0) {
+        opt.wide_kv_chunk < 0 || opt.units_per_cu < 0 || opt.narrow_waves < 0 || opt.narrow_waves > kMaxWaves ||
+        (opt.narrow_waves > 0 && s.num_kv_heads % opt.narrow_waves != 0)) {
         err = "bad options";
         return RPA_ERR_INVALID_ARG;
     }
@@ -143,7 +147,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     const int64_t narrow_max_q = 2 * (int64_t)tq_narrow; // up to two narrow tiles
     bool any_narrow = false, any_wide = false;
     std::vector<Tile> tiles;
-    int64_t work_narrow = 0, work_wide = 0, wide_tiles = 0;
+    int64_t work_wide = 0, wide_tiles = 0;
     for (int32_t r = 0; r < n; ++r) {
         const int32_t lq = cu[r + 1] - cu[r];
         if (lq == 0) continue;
@@ -163,21 +167,30 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
             if (wide) {
                 work_wide += t.kv_hi;
                 ++wide_tiles;
-            } else {
-                work_narrow += t.kv_hi;
             }
         }
     }
     plan.stats.variant = any_wide ? (any_narrow ? RPA_VARIANT_MIXED : RPA_VARIANT_PREFILL) : RPA_VARIANT_DECODE;
 
-    // ---- KV range per unit ------------------------------------------------
-    // Narrow units are bandwidth-bound: equal KV bytes per unit, several units
-    // per compute unit so that the tail is short.  Wide units are only split
-    // when there are too few tiles to occupy the chip.
+    // ---- narrow units: equal-volume bins -------------------------------------
+    // The narrow kernel keeps `slots` workgroups resident (LDS-bound); each gets
+    // one bin and walks its pieces back to back, so every workgroup streams the
+    // same number of KV tiles and there is no tail.
     const int cus = std::max(1, num_cus);
-    int64_t chunk_n = opt.kv_chunk > 0 ? round_up(opt.kv_chunk, kNarrowKvTile)
-                                       : round_up(std::max<int64_t>(256, ceil_div(work_narrow, (int64_t)cus * 6)),
-                                                  kNarrowKvTile);
+    const int waves = opt.narrow_waves > 0 ? opt.narrow_waves : narrow_waves(s.num_kv_heads);
+    const int ny = s.num_kv_heads / waves;
+    const int lds_per_wg = waves * narrow_lds_per_wave(s.head_dim);
+    const int wgs_per_cu = std::max(1, std::min(kLdsBytesPerCu / lds_per_wg, 16 / waves));
+    const int64_t slots = (int64_t)cus * wgs_per_cu;
+    const int oversub = opt.units_per_cu > 0 ? opt.units_per_cu : 1;
+    const int64_t want_bins = std::max<int64_t>(1, ceil_div(slots * oversub, ny));
+    int64_t total_tiles = 0; // KV volume of all narrow tiles, in 16-position tiles
+    for (const Tile& t : tiles)
+        if (!t.wide) total_tiles += ceil_div(t.kv_hi, kNarrowKvTile);
+    const int64_t min_bin = 8; // 128 KV positions: below that a bin is not worth a workgroup
+    int64_t per_bin = std::max<int64_t>(min_bin, ceil_div(total_tiles, want_bins));
+    const int64_t max_piece = opt.kv_chunk > 0 ? ceil_div(opt.kv_chunk, kNarrowKvTile) : ((int64_t)1 << 40);
+
     int64_t chunk_w;
     if (opt.wide_kv_chunk > 0) {
         chunk_w = round_up(opt.wide_kv_chunk, kWideKvTile);
@@ -192,14 +205,57 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         plan.narrow.clear();
         plan.wide.clear();
         plan.items.clear();
+        plan.bins.clear();
         int64_t cursor = 0;
         int32_t max_splits = 0;
+        int64_t fill = 0;
+        plan.bins.push_back(0);
         for (const Tile& t : tiles) {
-            if (t.wide)
+            if (t.wide) {
                 emit_units(t, chunk_w, kWideKvTile, s.num_q_heads, cursor, plan.wide, plan.items, max_splits);
-            else
-                emit_units(t, chunk_n, kNarrowKvTile, s.num_q_heads, cursor, plan.narrow, plan.items, max_splits);
+                continue;
+            }
+            const int64_t w = ceil_div(t.kv_hi, kNarrowKvTile);
+            const size_t first = plan.narrow.size();
+            int64_t done = 0;
+            while (done < w) {
+                if (fill >= per_bin) {
+                    plan.bins.push_back((int32_t)plan.narrow.size());
+                    fill = 0;
+                }
+                int64_t take = std::min(std::min(w - done, per_bin - fill), max_piece);
+                // do not leave a sliver of the tile behind
+                if (w - done - take > 0 && w - done - take < 2 && take + (w - done - take) <= max_piece)
+                    take = w - done;
+                rpa_work_unit u{};
+                u.seq = t.seq;
+                u.q_start = t.seq_q0 + t.q_pos0;
+                u.q_pos0 = t.q_pos0;
+                u.n_q = t.n_q;
+                u.kv_begin = (int32_t)(done * kNarrowKvTile);
+                u.kv_end = (int32_t)std::min<int64_t>((done + take) * kNarrowKvTile, t.kv_hi);
+                u.ctx = t.ctx;
+                u.seq_q0 = t.seq_q0;
+                u.part_row = -1;
+                u.flags = 0;
+                u.bin = (int32_t)plan.bins.size() - 1;
+                plan.narrow.push_back(u);
+                done += take;
+                fill += take;
+            }
+            const int64_t n_s = (int64_t)(plan.narrow.size() - first);
+            plan.narrow.back().flags |= 1; // the piece that ends the tile writes its new K/V
+            max_splits = std::max<int32_t>(max_splits, (int32_t)n_s);
+            if (n_s > 1) {
+                const int32_t rows = t.n_q * s.num_q_heads;
+                const int32_t base = (int32_t)cursor;
+                cursor += n_s * rows;
+                plan.items.push_back(rpa_combine_item{base, (int32_t)n_s, rows, t.seq_q0 + t.q_pos0});
+                for (int64_t k = 0; k < n_s; ++k) plan.narrow[first + k].part_row = (int32_t)(base + k * rows);
+            }
         }
+        plan.bins.push_back((int32_t)plan.narrow.size());
+        if (plan.narrow.empty()) plan.bins.assign(1, 0);
         plan.stats.partial_rows = cursor;
         plan.stats.max_splits = max_splits;
         if (cursor <= partial_row_cap) break;
@@ -209,22 +265,22 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
             err = buf;
             return RPA_ERR_WORKSPACE;
         }
-        chunk_n *= 2;
+        per_bin *= 2;
         if (chunk_w < ((int64_t)1 << 30)) chunk_w *= 2;
     }
 
-    // Longest first: the hardware dispatches workgroups in index order, so the
-    // short units fill the gaps at the end.
+    // Wide units longest first: the hardware dispatches workgroups in index order,
+    // so the short units fill the gaps at the end.
     auto span = [](const rpa_work_unit& u) { return (int64_t)(u.kv_end - u.kv_begin) * u.n_q; };
-    std::stable_sort(plan.narrow.begin(), plan.narrow.end(),
-                     [&](const rpa_work_unit& a, const rpa_work_unit& b) { return span(a) > span(b); });
     std::stable_sort(plan.wide.begin(), plan.wide.end(),
                      [&](const rpa_work_unit& a, const rpa_work_unit& b) { return span(a) > span(b); });
 
+    plan.stats.num_narrow_bins = (int32_t)plan.bins.size() - 1;
+    plan.stats.narrow_waves = waves;
+    plan.stats.kv_chunk = (int32_t)std::min<int64_t>(per_bin * kNarrowKvTile, INT32_MAX);
     plan.stats.num_narrow_units = (int32_t)plan.narrow.size();
     plan.stats.num_wide_units = (int32_t)plan.wide.size();
     plan.stats.num_combine_items = (int32_t)plan.items.size();
-    plan.stats.kv_chunk = (int32_t)std::min<int64_t>(chunk_n, INT32_MAX);
     return RPA_OK;
 }
 

@@ -29,7 +29,7 @@ class Shape(C.Structure):
 class WorkUnit(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "seq", "q_start", "q_pos0", "n_q", "kv_begin", "kv_end", "ctx", "seq_q0", "part_row",
-        "flags")] + [("reserved", C.c_int32 * 2)]
+        "flags", "bin", "reserved")]
 
 
 class CombineItem(C.Structure):
@@ -39,7 +39,8 @@ class CombineItem(C.Structure):
 class PlanStats(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "variant", "num_narrow_units", "num_wide_units", "num_combine_items", "max_splits",
-        "kv_chunk")] + [("partial_rows", C.c_int64), ("workspace_bytes", C.c_int64)]
+        "kv_chunk", "num_narrow_bins", "narrow_waves")] + [("partial_rows", C.c_int64),
+                                                             ("workspace_bytes", C.c_int64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -47,7 +48,8 @@ class PlanStats(C.Structure):
 
 class Options(C.Structure):
     _fields_ = [("variant", C.c_int32), ("kv_chunk", C.c_int32), ("wide_kv_chunk", C.c_int32),
-                ("reserved", C.c_int32 * 5)]
+                ("narrow_waves", C.c_int32), ("units_per_cu", C.c_int32), ("ablate", C.c_int32),
+                ("reserved", C.c_int32 * 2)]
 
 
 class RpaError(RuntimeError):
@@ -130,7 +132,8 @@ def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUT
     return u, it, stats.as_dict()
 
 
-UNIT_FIELDS = ("seq", "q_start", "q_pos0", "n_q", "kv_begin", "kv_end", "ctx", "seq_q0", "part_row", "flags")
+UNIT_FIELDS = ("seq", "q_start", "q_pos0", "n_q", "kv_begin", "kv_end", "ctx", "seq_q0", "part_row", "flags",
+               "bin")
 
 
 class RaggedPagedAttention:
@@ -164,8 +167,9 @@ class RaggedPagedAttention:
         except Exception:
             pass
 
-    def set_options(self, variant=VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0):
-        opt = Options(variant, kv_chunk, wide_kv_chunk)
+    def set_options(self, variant=VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, narrow_waves=0, units_per_cu=0,
+                    ablate=0):
+        opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, units_per_cu, ablate)
         rc = self._lib.rpa_set_options(self._ctx, C.byref(opt))
         if rc != RPA_OK:
             raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())

@@ -118,14 +118,19 @@ def test_plan_covers_random_ragged(seed, kv_chunk):
         assert stats["max_splits"] > 1
 
 
-def test_decode_units_balance_bytes():
-    """Equal-KV chunks: no decode unit of config 5 is more than ~2x the mean."""
-    wl = W.config(5)
-    units, _, stats = rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, num_cus=256)
-    span = units[:, F["kv_end"]] - units[:, F["kv_begin"]]
-    assert len(units) >= 4 * 256
-    assert span.max() <= 2 * span.mean()
-    assert (np.diff(span) <= 0).all()          # longest first
+def test_decode_bins_balance_bytes():
+    """Narrow units are dealt into bins of equal KV volume: one workgroup per bin,
+    every bin within a few tiles of the mean, bins contiguous in the unit list."""
+    for idx in (2, 5):
+        wl = W.config(idx)
+        units, _, stats = rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, num_cus=256)
+        bins = units[:, F["bin"]]
+        assert (np.diff(bins) >= 0).all() and bins[0] == 0 and bins[-1] == stats["num_narrow_bins"] - 1
+        tiles = -(-(units[:, F["kv_end"]] - units[:, F["kv_begin"]]) // 16)
+        per_bin = np.bincount(bins, weights=tiles)
+        assert stats["num_narrow_bins"] * (wl.num_kv_heads // stats["narrow_waves"]) <= 2 * 256
+        assert per_bin.max() - per_bin.mean() <= 3
+        assert per_bin.min() >= 0.9 * per_bin.mean() or per_bin.argmin() == len(per_bin) - 1
 
 
 def test_bad_lengths_are_rejected():
