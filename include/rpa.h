@@ -161,7 +161,7 @@ void rpa_destroy(rpa_ctx* ctx);
  *   cu_q_lens  host int32 [num_seqs + 1], cu_q_lens[0] = 0, non-decreasing
  *   kv_lens    host int32 [num_seqs], each includes the sequence's new tokens
  *   num_seqs   0 <= num_seqs <= max_seqs (0: success, nothing enqueued)
- *   sm_scale   softmax scale applied to q . k in fp32
+ *   sm_scale   softmax scale applied to q . k in fp32; finite and > 0
  *   stream     hipStream_t (NULL = the default stream)
  */
 int rpa_update_and_attend(rpa_ctx* ctx, void* out, const void* q, const void* k_new,
@@ -183,8 +183,8 @@ int rpa_plan_info(const rpa_ctx* ctx, rpa_plan_stats* out);
 int rpa_set_options(rpa_ctx* ctx, const rpa_options* opt);
 
 /* Kernel timing for benchmarks (not part of the paper's method).  While enabled,
- * every call brackets each of its kernels with HIP events on the call's stream
- * (at most 1024 calls are kept between two reads).  rpa_profile_read()
+ * every call attaches a start and a stop HIP event to each kernel it launches
+ * on the call's stream (at most 1024 calls are kept between two reads).  rpa_profile_read()
  * synchronises on the last recorded event and adds up, over the calls since the
  * previous read, the milliseconds spent in the narrow kernel, the wide kernel
  * and the combine kernel; *calls receives the number of calls covered.        */

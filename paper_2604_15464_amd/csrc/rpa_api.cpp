@@ -32,7 +32,7 @@ struct Staging {
 constexpr int kProfCalls = 1024;
 
 struct ProfEvents {
-    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr}; // narrow start, wide start, combine start, end
+    hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr}; // start/stop of narrow, wide, combine
     bool narrow = false, wide = false, combine = false;
 };
 
@@ -196,23 +196,16 @@ extern "C" int rpa_profile_read(rpa_ctx* c, float* narrow_ms, float* wide_ms, fl
     *calls = c->prof_count;
     for (int i = 0; i < c->prof_count; ++i) {
         ProfEvents& p = c->prof[i];
-        hipError_t e = hipEventSynchronize(p.ev[3]);
-        if (e != hipSuccess) return hip_fail(c, "hipEventSynchronize", e);
-        float ms = 0.f;
-        if (p.narrow) {
-            e = hipEventElapsedTime(&ms, p.ev[0], p.ev[1]);
+        const bool has[3] = {p.narrow, p.wide, p.combine};
+        float* dst[3] = {narrow_ms, wide_ms, combine_ms};
+        for (int k = 0; k < 3; ++k) {
+            if (!has[k]) continue;
+            hipError_t e = hipEventSynchronize(p.ev[2 * k + 1]);
+            if (e != hipSuccess) return hip_fail(c, "hipEventSynchronize", e);
+            float ms = 0.f;
+            e = hipEventElapsedTime(&ms, p.ev[2 * k], p.ev[2 * k + 1]);
             if (e != hipSuccess) return hip_fail(c, "hipEventElapsedTime", e);
-            *narrow_ms += ms;
-        }
-        if (p.wide) {
-            e = hipEventElapsedTime(&ms, p.ev[1], p.ev[2]);
-            if (e != hipSuccess) return hip_fail(c, "hipEventElapsedTime", e);
-            *wide_ms += ms;
-        }
-        if (p.combine) {
-            e = hipEventElapsedTime(&ms, p.ev[2], p.ev[3]);
-            if (e != hipSuccess) return hip_fail(c, "hipEventElapsedTime", e);
-            *combine_ms += ms;
+            *dst[k] += ms;
         }
     }
     c->prof_count = 0;
@@ -258,7 +251,8 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     const uintptr_t align = (uintptr_t)out | (uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new |
                             (uintptr_t)k_pages | (uintptr_t)v_pages;
     if (align & 15) return fail(c, RPA_ERR_INVALID_ARG, "rpa_update_and_attend: tensors must be 16-byte aligned");
-    if (!std::isfinite(sm_scale)) return fail(c, RPA_ERR_INVALID_ARG, "rpa_update_and_attend: sm_scale not finite");
+    if (!std::isfinite(sm_scale) || !(sm_scale > 0.f))
+        return fail(c, RPA_ERR_INVALID_ARG, "rpa_update_and_attend: sm_scale must be finite and positive");
 
     std::string msg;
     int rc = build_plan(c->shape, cu_q_lens, kv_lens, num_seqs, c->opt, c->num_cus, c->partial_row_cap, c->plan, msg);
@@ -325,24 +319,17 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
 
     const rpa_work_unit* dev_units = (const rpa_work_unit*)slot.dev;
     ProfEvents* pe = (c->prof_on && c->prof_count < kProfCalls) ? &c->prof[c->prof_count] : nullptr;
-    auto mark = [&](int i) {
-        if (pe) (void)hipEventRecord(pe->ev[i], st);
-    };
     int hrc;
     a.units = dev_units;
     a.bins = (const int32_t*)((const char*)slot.dev + bins_off);
-    mark(0);
-    hrc = launch_narrow(a, (int)n_bins, plan.stats.narrow_waves, stream);
+    hrc = launch_narrow(a, (int)n_bins, plan.stats.narrow_waves, stream, pe ? (void**)&pe->ev[0] : nullptr);
     if (hrc != 0) return hip_fail(c, "narrow kernel launch", (hipError_t)hrc);
-    mark(1);
     a.units = dev_units + n_narrow;
-    hrc = launch_wide(a, (int)n_wide, stream);
+    hrc = launch_wide(a, (int)n_wide, stream, pe ? (void**)&pe->ev[2] : nullptr);
     if (hrc != 0) return hip_fail(c, "wide kernel launch", (hipError_t)hrc);
-    mark(2);
     hrc = launch_combine((const rpa_combine_item*)((char*)slot.dev + items_off), (int)n_items, c->part_o, c->part_ml,
-                         (uint16_t*)out, a.num_q_heads, a.head_dim, stream);
+                         (uint16_t*)out, a.num_q_heads, a.head_dim, stream, pe ? (void**)&pe->ev[4] : nullptr);
     if (hrc != 0) return hip_fail(c, "combine kernel launch", (hipError_t)hrc);
-    mark(3);
     e = hipEventRecord(slot.done, st);
     if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
     if (pe) {

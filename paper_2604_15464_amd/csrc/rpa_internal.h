@@ -72,12 +72,14 @@ struct KernelArgs {
     int32_t ablate;   // measurement switches (rpa_options.ablate)
 };
 
-// Launchers (rpa_kernels.hip).  Return a hipError_t value as int.
-int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream);
-int launch_wide(const KernelArgs& a, int num_units, void* stream);
+// Launchers (rpa_kernels.hip).  Return a hipError_t value as int.  `ev` is either
+// null or two hipEvent_t that receive the kernel's own start and stop times
+// (attached to the dispatch, no extra queue packets).
+int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream, void** ev);
+int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev);
 int launch_combine(const rpa_combine_item* items, int num_items, const float* part_o,
                    const float* part_ml, uint16_t* out, int num_q_heads, int head_dim,
-                   void* stream);
+                   void* stream, void** ev);
 int kernels_init(int device, std::string& err);
 
 } // namespace rpa

@@ -9,7 +9,10 @@
 // registers, and the row statistics (running max m, running sum l of Alg. 1)
 // are reduced with two cross-lane steps.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "rpa_internal.h"
 
@@ -230,23 +233,22 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         // ---- mask + online softmax (Alg. 1: m~, P, l~) ------------------------
         float sv[4];
         float mx = -INFINITY;
+        const int rel = min(limit_n, kv_end - 1) - pos0 - 4 * quad;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            const int pos = pos0 + 4 * quad + v;
-            const bool ok = (pos < kv_end) && (pos <= limit_n);
-            sv[v] = ok ? s[v] * a.scale_log2 : -INFINITY;
+            sv[v] = (v <= rel) ? s[v] : -INFINITY; // position pos0 + 4*quad + v; raw score (sm_scale > 0)
             mx = fmaxf(mx, sv[v]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
+        const float m_new = fmaxf(m_run, mx * a.scale_log2);
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = fast_exp2(m_run - m_use);
         float p[4];
         float psum = 0.f;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            p[v] = fast_exp2(sv[v] - m_use);
+            p[v] = fast_exp2(__builtin_fmaf(sv[v], a.scale_log2, -m_use));
             psum += p[v];
         }
         l_run = l_run * alpha + psum;
@@ -363,34 +365,38 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 // ---------------------------------------------------------------------------
 // Wide kernel: query tile of 256 rows = (256 / h_g) tokens x the h_g heads of one
 // KV head (the paper's stacking of a group's heads against one K/V operand,
-// Sec. 3.1.2), four waves of 64 rows each, 32x32x16 MFMA.  K/V tiles of 64
+// Sec. 3.1.2), eight waves of 32 rows each, 32x32x16 MFMA.  K/V tiles of 64
 // positions are staged once per workgroup in LDS by asynchronous 16-byte loads
-// (each wave brings 16 positions) and double-buffered, one barrier per tile.
-// Used for prefill and chunked prefill; MFMA-bound.
+// (each wave brings 8 positions) and double-buffered, one barrier per tile.
+// Two waves share a SIMD, so one wave's softmax (VALU) overlaps the other's
+// MFMAs.  Used for prefill and chunked prefill; MFMA-bound.
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(256) rpa_wide_kernel(KernelArgs a) {
+__global__ void __launch_bounds__(512) rpa_wide_kernel(KernelArgs a) {
     constexpr int ROWB = D * 2;
     constexpr int NC = D / 8;
-    constexpr int TPI = 64 / NC;
+    constexpr int TPI = 64 / NC;   // positions per wave-wide load
     constexpr int KT = kWideKvTile;
     constexpr int TILEB = KT * ROWB;
     constexpr int STAGEB = 2 * TILEB;
-    constexpr int NLD = 16 / TPI;  // loads per wave per K (or V) tile: 16 positions
+    constexpr int WPOS = KT / 8;    // positions each of the 8 waves brings per tile
+    constexpr int NLD = (WPOS + TPI - 1) / TPI;
     constexpr int KSTEPS = D / 16; // 32x32x16 steps over head_dim
-    constexpr int DPL = D / 32;    // output dims per lane and per 32-dim MFMA tile set
+    constexpr int DPL = D / 32;    // output dims per lane per 32-dim MFMA tile set
 
     extern __shared__ uint4 smem[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int g = blockIdx.y;
+    const int Hkv = a.num_kv_heads;
+    const int unit_idx = blockIdx.x / Hkv;
+    const int g = blockIdx.x - unit_idx * Hkv;
     const int n32 = lane & 31;
     const int h = lane >> 5;
 
-    const rpa_work_unit u = a.units[blockIdx.x];
+    const rpa_work_unit u = a.units[unit_idx];
     const int hg = a.hg;
-    const int Hq = a.num_q_heads, Hkv = a.num_kv_heads;
+    const int Hq = a.num_q_heads;
     const int ps_log2 = a.page_size_log2;
     const int ps_mask = (1 << ps_log2) - 1;
     const int num_pages = a.num_pages;
@@ -405,24 +411,29 @@ __global__ void __launch_bounds__(256) rpa_wide_kernel(KernelArgs a) {
     const uint64_t k_delta = (uint64_t)k_pages - (uint64_t)k_new;
     const uint64_t v_delta = (uint64_t)v_pages - (uint64_t)v_new;
 
-    // ---- rows of this lane: rho = 64*wave + 32*nt + lane%32 = head * TQ + token
-    int tok[2], head[2], limit[2];
-    bool row_ok[2];
-    bf16x8 qreg[2][KSTEPS];
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int rho = 64 * wave + 32 * nt + n32;
-        const int hh = rho >> tq_log2;
-        tok[nt] = rho & ((1 << tq_log2) - 1);
-        head[nt] = g * hg + hh;
-        row_ok[nt] = tok[nt] < u.n_q;
-        limit[nt] = row_ok[nt] ? ctx + u.q_pos0 + tok[nt] : -1;
-        const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok[nt] ? tok[nt] : 0)) * Hq + head[nt]) * D;
+    // ---- row of this lane: rho = 32*wave + lane%32 = head_in_group * TQ + token
+    const int rho = 32 * wave + n32;
+    const int hh = rho >> tq_log2;
+    const int tok = rho & ((1 << tq_log2) - 1);
+    const int head = g * hg + hh;
+    const bool row_ok = tok < u.n_q;
+    const int limit = row_ok ? ctx + u.q_pos0 + tok : -1; // last visible KV position
+    // the wave's 32 rows are 32 consecutive tokens of one head (or several heads'
+    // complete token ranges): positions above wave_limit are hidden from all of them
+    const int wave_tok_lo = (32 * wave) & ((1 << tq_log2) - 1);
+    const int wave_tok_hi = (1 << tq_log2) >= 32 ? wave_tok_lo + 31 : (1 << tq_log2) - 1;
+    const int wave_limit = ctx + u.q_pos0 + min(wave_tok_hi, u.n_q - 1);
+    const int wave_min_limit = ((1 << tq_log2) >= 32 ? wave_tok_lo : 0) < u.n_q
+                                   ? ctx + u.q_pos0 + ((1 << tq_log2) >= 32 ? wave_tok_lo : 0)
+                                   : -1;
+    bf16x8 qreg[KSTEPS];
+    {
+        const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok ? tok : 0)) * Hq + head) * D;
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) {
             uint4 raw = make_uint4(0, 0, 0, 0);
-            if (row_ok[nt]) raw = *(const uint4*)(qrow + kk * 16 + h * 8);
-            qreg[nt][kk] = __builtin_bit_cast(bf16x8, raw);
+            if (row_ok) raw = *(const uint4*)(qrow + kk * 16 + h * 8);
+            qreg[kk] = __builtin_bit_cast(bf16x8, raw);
         }
     }
     wait_vmcnt<0>();
@@ -431,23 +442,22 @@ __global__ void __launch_bounds__(256) rpa_wide_kernel(KernelArgs a) {
     const char* lds_ptr = (const char*)smem;
     const int kv_begin = u.kv_begin, kv_end = u.kv_end;
     const int ntiles = max(0, (kv_end - kv_begin + KT - 1) / KT);
-    const int min_limit = ctx + u.q_pos0; // the tile's first token sees the least
 
     const int ld_tok = lane / NC;
     const int ld_chunk = lane % NC;
     uint32_t lane_off[NLD];
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-        const int r = 16 * wave + i * TPI + ld_tok; // row inside the 64-position tile
+        const int r = WPOS * wave + i * TPI + ld_tok; // row inside the 64-position tile
         lane_off[i] = (uint32_t)g * ROWB + (uint32_t)((ld_chunk ^ (r % NC)) * 16);
     }
 
     auto issue_tile = [&](int t) {
-        const int p0w = kv_begin + t * KT + 16 * wave; // this wave's 16 positions
+        const int p0w = kv_begin + t * KT + WPOS * wave; // this wave's positions
         const int slot = t & 1;
         const int pidx = __builtin_amdgcn_readfirstlane(min(p0w, kv_end - 1) >> ps_log2);
-        const int page = clamp_page(pt_row[pidx], num_pages);
-        const uint32_t ldsK = lds_base + slot * STAGEB + (16 * wave) * ROWB;
+        const int page = clamp_page(pt_row[pidx], num_pages); // 8 aligned positions share a page
+        const uint32_t ldsK = lds_base + slot * STAGEB + (WPOS * wave) * ROWB;
         const uint32_t ldsV = ldsK + TILEB;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
@@ -463,104 +473,86 @@ __global__ void __launch_bounds__(256) rpa_wide_kernel(KernelArgs a) {
         }
     };
 
-    f32x16 o[2][DPL];
+    f32x16 o[DPL];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+    for (int j = 0; j < DPL; ++j)
 #pragma unroll
-        for (int j = 0; j < DPL; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[nt][j][v] = 0.f;
-    float m_run[2] = {-INFINITY, -INFINITY};
-    float l_run[2] = {0.f, 0.f};
+        for (int v = 0; v < 16; ++v) o[j][v] = 0.f;
+    float m_run = -INFINITY;
+    float l_run = 0.f;
 
-    if (ntiles > 0) issue_tile(0);
-    wait_vmcnt<0>();
-    __syncthreads();
+    // LDS read offsets inside a tile, one register per distinct swizzle; the
+    // remaining terms of every read are compile-time immediates.
+    //   K operand (row 32*mt + n32, chunk 2*kk + h):  koff[kk] + mt * 32 * ROWB
+    //   V rows of k-step ks, element e:              voff[e] + (32*(ks/2) + 16*(ks%2)) * ROWB
+    uint32_t koff[KSTEPS], voff[8];
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) koff[kk] = n32 * ROWB + (((2 * kk + h) ^ (n32 % NC)) * 16);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int r = 8 * (e >> 2) + 4 * h + (e & 3); // row modulo 16
+        voff[e] = r * ROWB + ((((n32 * DPL) / 8) ^ (r % NC)) * 16) + ((n32 * DPL) % 8) * 2;
+    }
 
-    for (int t = 0; t < ntiles; ++t) {
-        if (t + 1 < ntiles) issue_tile(t + 1);
-        const char* ldsK = lds_ptr + (t & 1) * STAGEB;
-        const char* ldsV = ldsK + TILEB;
-        const int pos0 = kv_begin + t * KT;
-
-        // ---- S^T = K Q^T for both 32-row groups (Alg. 1: S <- C_q C_k^T) -------
-        f32x16 s[2][2]; // [nt][mt]
+    // One 32-position half of a tile: scores, online-softmax update, PV.  Working
+    // in halves keeps the live score registers at 16 per lane.
+    auto compute_half = [&](const char* ldsK, const char* ldsV, int pos0, int mt_, auto masked) {
+        constexpr bool MASKED = decltype(masked)::value;
+        const int mt = mt_;
+        // ---- S^T = K Q^T (Alg. 1: S <- C_q C_k^T) --------------------------------
+        f32x16 s;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                s[0][mt][v] = 0.f;
-                s[1][mt][v] = 0.f;
-            }
-            const int row = 32 * mt + n32;
-#pragma unroll
-            for (int kk = 0; kk < KSTEPS; ++kk) {
-                const int c = 2 * kk + h;
-                const bf16x8 kop = *(const bf16x8*)(ldsK + row * ROWB + ((c ^ (row % NC)) * 16));
-                s[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[0][kk], s[0][mt], 0, 0, 0);
-                s[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[1][kk], s[1][mt], 0, 0, 0);
-            }
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            const bf16x8 kop = *(const bf16x8*)(ldsK + koff[kk] + mt * 32 * ROWB);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[kk], s, 0, 0, 0);
+            if (kk % 4 == 3) __builtin_amdgcn_sched_barrier(0); // bound the operand look-ahead (registers)
         }
-
         // ---- mask + online softmax (Alg. 1: m~, P, l~) ------------------------
-        const bool need_mask = (pos0 + KT > kv_end) || (pos0 + KT - 1 > min_limit);
-        bf16x8 pop[2][4]; // [nt][k-step of 16 positions]
+        // position of element v is pos0 + 32*mt + 4*h + c with the compile-time
+        // c = 8*(v/4) + v%4: visible iff c <= rel.  sm_scale > 0, so the row
+        // maximum is taken on the raw scores and scaled once.
+        float mx = -INFINITY;
+        const int rel = min(limit, kv_end - 1) - pos0 - 32 * mt - 4 * h;
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    float x = s[nt][mt][v] * a.scale_log2;
-                    if (need_mask) {
-                        const int pos = pos0 + 32 * mt + 8 * (v / 4) + 4 * h + (v % 4);
-                        const bool ok = (pos < kv_end) && (pos <= limit[nt]);
-                        x = ok ? x : -INFINITY;
-                    }
-                    s[nt][mt][v] = x;
-                    mx = fmaxf(mx, x);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[nt], mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = fast_exp2(m_run[nt] - m_use);
-            float psum = 0.f;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float pv = fast_exp2(s[nt][mt][v] - m_use);
-                    s[nt][mt][v] = pv;
-                    psum += pv;
-                }
-            l_run[nt] = l_run[nt] * alpha + psum;
-            m_run[nt] = m_new;
-#pragma unroll
-            for (int j = 0; j < DPL; ++j) o[nt][j] *= alpha;
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const int mt = ks >> 1, v0 = 8 * (ks & 1);
-                union {
-                    uint32_t w[4];
-                    bf16x8 v;
-                } pk;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) pk.w[e] = pack_bf16(s[nt][mt][v0 + 2 * e], s[nt][mt][v0 + 2 * e + 1]);
-                pop[nt][ks] = pk.v;
-            }
+        for (int v = 0; v < 16; ++v) {
+            if (MASKED) s[v] = (8 * (v / 4) + (v % 4) <= rel) ? s[v] : -INFINITY;
+            mx = fmaxf(mx, s[v]);
         }
-
-        // ---- O^T += V^T P^T (Alg. 1: C_o <- ... + P C_v) --------------------------
-        // k-step ks covers positions 32*(ks/2) + 8*(2*(ks%2) + e/4) + 4*h + e%4,
-        // e = 0..7, which is the order the packed weights above are in.
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx * a.scale_log2);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = fast_exp2(m_run - m_use);
+        float psum = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+        for (int v = 0; v < 16; ++v) {
+            const float pv = fast_exp2(__builtin_fmaf(s[v], a.scale_log2, -m_use));
+            s[v] = pv;
+            psum += pv;
+        }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) { // skip when no row's maximum moved
+#pragma unroll
+            for (int j = 0; j < DPL; ++j) o[j] *= alpha;
+        }
+        // ---- O^T += V^T P^T (Alg. 1: C_o <- ... + P C_v) --------------------------
+        // k-step kh covers positions 32*mt + 8*(2*kh + e/4) + 4*h + e%4, e = 0..7,
+        // which is the order of the accumulator elements 8*kh .. 8*kh + 7.
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh) {
+            __builtin_amdgcn_sched_barrier(0);
+            union {
+                uint32_t w[4];
+                bf16x8 v;
+            } pk;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pk.w[e] = pack_bf16(s[8 * kh + 2 * e], s[8 * kh + 2 * e + 1]);
             uint32_t vr[8][DPL / 2];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int row = 32 * (ks >> 1) + 8 * (2 * (ks & 1) + (e >> 2)) + 4 * h + (e & 3);
-                const char* src = ldsV + row * ROWB + ((((n32 * DPL) / 8) ^ (row % NC)) * 16) + ((n32 * DPL) % 8) * 2;
+                const char* src = ldsV + voff[e] + (32 * mt + 16 * kh) * ROWB;
                 if constexpr (DPL == 4) {
                     const uint2 raw = *(const uint2*)src;
                     vr[e][0] = raw.x;
@@ -578,46 +570,64 @@ __global__ void __launch_bounds__(256) rpa_wide_kernel(KernelArgs a) {
                 } vop;
 #pragma unroll
                 for (int d = 0; d < 4; ++d) vop.w[d] = __builtin_amdgcn_perm(vr[2 * d + 1][j / 2], vr[2 * d][j / 2], sel);
-                o[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop.v, pop[0][ks], o[0][j], 0, 0, 0);
-                o[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop.v, pop[1][ks], o[1][j], 0, 0, 0);
+                o[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop.v, pk.v, o[j], 0, 0, 0);
             }
         }
+    };
+    auto compute_tile = [&](const char* ldsK, const char* ldsV, int pos0, auto masked) {
+        compute_half(ldsK, ldsV, pos0, 0, masked);
+        __builtin_amdgcn_sched_barrier(0);
+        if (pos0 + 32 <= wave_limit) compute_half(ldsK, ldsV, pos0, 1, masked);
+    };
 
+    if (ntiles > 0) issue_tile(0);
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        if (t + 1 < ntiles) issue_tile(t + 1);
+        const char* ldsK = lds_ptr + (t & 1) * STAGEB;
+        const char* ldsV = ldsK + TILEB;
+        const int pos0 = kv_begin + t * KT;
+        if (pos0 <= wave_limit) { // tiles wholly above the wave's diagonal are skipped
+            if ((pos0 + KT > kv_end) || (pos0 + KT - 1 > wave_min_limit))
+                compute_tile(ldsK, ldsV, pos0, std::true_type{});
+            else
+                compute_tile(ldsK, ldsV, pos0, std::false_type{});
+        }
         wait_vmcnt<0>();
         __syncthreads();
     }
 
     // ---- finalize (Alg. 1: diag(l)^-1 B_o) or store the partial state ------------
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
-        if (!row_ok[nt]) continue;
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (row_ok) {
         if (u.part_row < 0) {
             const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-            uint16_t* orow = a.out + ((size_t)(u.q_start + tok[nt]) * Hq + head[nt]) * D;
+            uint16_t* orow = a.out + ((size_t)(u.q_start + tok) * Hq + head) * D;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int mrow = 8 * (v / 4) + 4 * h + (v % 4);
                 if constexpr (DPL == 4) {
                     uint2 w;
-                    w.x = pack_bf16(o[nt][0][v] * inv, o[nt][1][v] * inv);
-                    w.y = pack_bf16(o[nt][2][v] * inv, o[nt][3][v] * inv);
+                    w.x = pack_bf16(o[0][v] * inv, o[1][v] * inv);
+                    w.y = pack_bf16(o[2][v] * inv, o[3][v] * inv);
                     *(uint2*)(orow + DPL * mrow) = w;
                 } else {
-                    *(uint32_t*)(orow + DPL * mrow) = pack_bf16(o[nt][0][v] * inv, o[nt][1][v] * inv);
+                    *(uint32_t*)(orow + DPL * mrow) = pack_bf16(o[0][v] * inv, o[1][v] * inv);
                 }
             }
         } else {
-            const size_t prow = (size_t)u.part_row + (size_t)tok[nt] * Hq + head[nt];
+            const size_t prow = (size_t)u.part_row + (size_t)tok * Hq + head;
             float* po = a.part_o + prow * D;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int mrow = 8 * (v / 4) + 4 * h + (v % 4);
 #pragma unroll
-                for (int j = 0; j < DPL; ++j) po[DPL * mrow + j] = o[nt][j][v];
+                for (int j = 0; j < DPL; ++j) po[DPL * mrow + j] = o[j][v];
             }
             if (h == 0) {
-                a.part_ml[prow * 2] = m_run[nt];
+                a.part_ml[prow * 2] = m_run;
                 a.part_ml[prow * 2 + 1] = l_tot;
             }
         }
@@ -626,7 +636,7 @@ __global__ void __launch_bounds__(256) rpa_wide_kernel(KernelArgs a) {
     // ---- fused cache update for the tile's new tokens (see the narrow kernel)
     if (u.flags & 1) {
         const int c = threadIdx.x % NC;
-        for (int t = threadIdx.x / NC; t < u.n_q; t += 256 / NC) {
+        for (int t = threadIdx.x / NC; t < u.n_q; t += 512 / NC) {
             const int pos = ctx + u.q_pos0 + t;
             const int page = clamp_page(pt_row[pos >> ps_log2], num_pages);
             const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * D + c * 8;
@@ -717,35 +727,39 @@ int kernels_init(int device, std::string& err) {
     return 0;
 }
 
-int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream) {
+#define RPA_LAUNCH(kernel, grid, block, lds, st, ev, ...)                                              \
+    hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)(lds), st, (ev) ? (hipEvent_t)(ev)[0] : nullptr, \
+                          (ev) ? (hipEvent_t)(ev)[1] : nullptr, 0, __VA_ARGS__)
+
+int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream, void** ev) {
     if (num_bins <= 0) return 0;
     dim3 grid(num_bins, a.num_kv_heads / waves);
     dim3 block(64 * waves);
     hipStream_t st = (hipStream_t)stream;
     if (a.head_dim == 128)
-        hipLaunchKernelGGL((rpa_narrow_kernel<128, kNarrowStages>), grid, block, narrow_lds_bytes<128>(waves), st, a);
+        RPA_LAUNCH((rpa_narrow_kernel<128, kNarrowStages>), grid, block, narrow_lds_bytes<128>(waves), st, ev, a);
     else
-        hipLaunchKernelGGL((rpa_narrow_kernel<64, kNarrowStages>), grid, block, narrow_lds_bytes<64>(waves), st, a);
+        RPA_LAUNCH((rpa_narrow_kernel<64, kNarrowStages>), grid, block, narrow_lds_bytes<64>(waves), st, ev, a);
     return (int)hipGetLastError();
 }
 
-int launch_wide(const KernelArgs& a, int num_units, void* stream) {
+int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev) {
     if (num_units <= 0) return 0;
-    dim3 grid(num_units, a.num_kv_heads);
+    dim3 grid((unsigned)num_units * a.num_kv_heads);
     hipStream_t st = (hipStream_t)stream;
     if (a.head_dim == 128)
-        hipLaunchKernelGGL((rpa_wide_kernel<128>), grid, dim3(256), wide_lds_bytes<128>(), st, a);
+        RPA_LAUNCH((rpa_wide_kernel<128>), grid, dim3(512), wide_lds_bytes<128>(), st, ev, a);
     else
-        hipLaunchKernelGGL((rpa_wide_kernel<64>), grid, dim3(256), wide_lds_bytes<64>(), st, a);
+        RPA_LAUNCH((rpa_wide_kernel<64>), grid, dim3(512), wide_lds_bytes<64>(), st, ev, a);
     return (int)hipGetLastError();
 }
 
 int launch_combine(const rpa_combine_item* items, int num_items, const float* part_o, const float* part_ml,
-                   uint16_t* out, int num_q_heads, int head_dim, void* stream) {
+                   uint16_t* out, int num_q_heads, int head_dim, void* stream, void** ev) {
     if (num_items <= 0) return 0;
     dim3 grid(num_items, 8);
-    hipLaunchKernelGGL(rpa_combine_kernel, grid, dim3(256), 0, (hipStream_t)stream, items, part_o, part_ml, out,
-                       num_q_heads, head_dim);
+    RPA_LAUNCH(rpa_combine_kernel, grid, dim3(256), 0, (hipStream_t)stream, ev, items, part_o, part_ml, out,
+               num_q_heads, head_dim);
     return (int)hipGetLastError();
 }
 
