@@ -17,6 +17,7 @@ constexpr int kWideRows = 256;    // query rows per wide tile = (256 / h_g) toke
 constexpr int kWideKvTile = 64;   // KV positions per wide pipeline stage
 constexpr int kMaxWaves = 8;      // waves per narrow workgroup (one KV head each)
 constexpr int kNarrowStages = 2;   // LDS ring depth of a narrow wave
+constexpr int kWideStages = 3;     // LDS ring depth of a wide workgroup
 constexpr int kLdsBytesPerCu = 160 * 1024;
 
 struct Plan {

@@ -26,6 +26,11 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 // Read-only tables are read through the constant address space so that
 // wave-uniform reads become scalar loads (and stay so next to the inline asm).
 typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+typedef __attribute__((address_space(3))) short4v lds_short4;
+
+// The wide kernel lets softmax weights grow to 2^kRescaleGap before it moves a
+// row's reference maximum and rescales the accumulator.
+constexpr float kRescaleGap = 8.0f;
 
 // ---------------------------------------------------------------------------
 // small device helpers
@@ -365,21 +370,23 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 // ---------------------------------------------------------------------------
 // Wide kernel: query tile of 256 rows = (256 / h_g) tokens x the h_g heads of one
 // KV head (the paper's stacking of a group's heads against one K/V operand,
-// Sec. 3.1.2), eight waves of 32 rows each, 32x32x16 MFMA.  K/V tiles of 64
-// positions are staged once per workgroup in LDS by asynchronous 16-byte loads
-// (each wave brings 8 positions) and double-buffered, one barrier per tile.
-// Two waves share a SIMD, so one wave's softmax (VALU) overlaps the other's
+// Sec. 3.1.2).  8 / NT waves, each owning NT groups of 32 rows; 32x32x16 MFMA.
+// K/V tiles of 64 positions are staged once per workgroup in LDS by asynchronous
+// 16-byte loads (every wave brings its share) in a ring of kWideStages, one
+// barrier per tile.  With NT = 2 a K or V operand read from LDS feeds two
 // MFMAs.  Used for prefill and chunked prefill; MFMA-bound.
 // ---------------------------------------------------------------------------
-template <int D>
-__global__ void __launch_bounds__(512) rpa_wide_kernel(KernelArgs a) {
+template <int D, int NT>
+__global__ void __launch_bounds__(512 / NT) rpa_wide_kernel(KernelArgs a) {
+    constexpr int WAVES = 8 / NT;
     constexpr int ROWB = D * 2;
     constexpr int NC = D / 8;
     constexpr int TPI = 64 / NC;   // positions per wave-wide load
     constexpr int KT = kWideKvTile;
     constexpr int TILEB = KT * ROWB;
     constexpr int STAGEB = 2 * TILEB;
-    constexpr int WPOS = KT / 8;    // positions each of the 8 waves brings per tile
+    constexpr int NST = kWideStages;
+    constexpr int WPOS = KT / WAVES; // positions each wave brings per tile
     constexpr int NLD = (WPOS + TPI - 1) / TPI;
     constexpr int KSTEPS = D / 16; // 32x32x16 steps over head_dim
     constexpr int DPL = D / 32;    // output dims per lane per 32-dim MFMA tile set
@@ -402,6 +409,7 @@ __global__ void __launch_bounds__(512) rpa_wide_kernel(KernelArgs a) {
     const int num_pages = a.num_pages;
     const int ctx = u.ctx;
     const int tq_log2 = a.wide_tq_log2;
+    const int tq_mask = (1 << tq_log2) - 1;
     const char* const k_pages = (const char*)a.k_pages;
     const char* const v_pages = (const char*)a.v_pages;
     const char* const k_new = (const char*)a.k_new;
@@ -411,31 +419,37 @@ __global__ void __launch_bounds__(512) rpa_wide_kernel(KernelArgs a) {
     const uint64_t k_delta = (uint64_t)k_pages - (uint64_t)k_new;
     const uint64_t v_delta = (uint64_t)v_pages - (uint64_t)v_new;
 
-    // ---- row of this lane: rho = 32*wave + lane%32 = head_in_group * TQ + token
-    const int rho = 32 * wave + n32;
-    const int hh = rho >> tq_log2;
-    const int tok = rho & ((1 << tq_log2) - 1);
-    const int head = g * hg + hh;
-    const bool row_ok = tok < u.n_q;
-    const int limit = row_ok ? ctx + u.q_pos0 + tok : -1; // last visible KV position
-    // the wave's 32 rows are 32 consecutive tokens of one head (or several heads'
-    // complete token ranges): positions above wave_limit are hidden from all of them
-    const int wave_tok_lo = (32 * wave) & ((1 << tq_log2) - 1);
-    const int wave_tok_hi = (1 << tq_log2) >= 32 ? wave_tok_lo + 31 : (1 << tq_log2) - 1;
-    const int wave_limit = ctx + u.q_pos0 + min(wave_tok_hi, u.n_q - 1);
-    const int wave_min_limit = ((1 << tq_log2) >= 32 ? wave_tok_lo : 0) < u.n_q
-                                   ? ctx + u.q_pos0 + ((1 << tq_log2) >= 32 ? wave_tok_lo : 0)
-                                   : -1;
-    bf16x8 qreg[KSTEPS];
-    {
-        const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok ? tok : 0)) * Hq + head) * D;
+    // ---- rows of this lane: rho = 32*(NT*wave + nt) + lane%32 = head_in_group * TQ + token
+    int tok[NT], head[NT], limit[NT];
+    bool row_ok[NT];
+    bf16x8 qreg[NT][KSTEPS];
+    int wave_limit = -1;           // positions above it are hidden from every row of the wave
+    int wave_min_limit = 1 << 30;  // positions up to it are visible to every live row of the wave
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int rho = 32 * (NT * wave + nt) + n32;
+        const int hh = rho >> tq_log2;
+        tok[nt] = rho & tq_mask;
+        head[nt] = g * hg + hh;
+        row_ok[nt] = tok[nt] < u.n_q;
+        limit[nt] = row_ok[nt] ? ctx + u.q_pos0 + tok[nt] : -1;
+        // the group's 32 rows are 32 consecutive tokens of one head, or whole token
+        // ranges of several heads when the tile has fewer than 32 tokens
+        const int g_lo = (1 << tq_log2) >= 32 ? ((32 * (NT * wave + nt)) & tq_mask) : 0;
+        const int g_hi = (1 << tq_log2) >= 32 ? g_lo + 31 : tq_mask;
+        if (g_lo < u.n_q) {
+            wave_limit = max(wave_limit, ctx + u.q_pos0 + min(g_hi, u.n_q - 1));
+            wave_min_limit = min(wave_min_limit, ctx + u.q_pos0 + g_lo);
+        }
+        const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok[nt] ? tok[nt] : 0)) * Hq + head[nt]) * D;
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) {
             uint4 raw = make_uint4(0, 0, 0, 0);
-            if (row_ok) raw = *(const uint4*)(qrow + kk * 16 + h * 8);
-            qreg[kk] = __builtin_bit_cast(bf16x8, raw);
+            if (row_ok[nt]) raw = *(const uint4*)(qrow + kk * 16 + h * 8);
+            qreg[nt][kk] = __builtin_bit_cast(bf16x8, raw);
         }
     }
+    if (wave_limit < 0) wave_min_limit = -1;
     wait_vmcnt<0>();
 
     const uint32_t lds_base = lds_offset(smem);
@@ -453,14 +467,16 @@ __global__ void __launch_bounds__(512) rpa_wide_kernel(KernelArgs a) {
     }
 
     auto issue_tile = [&](int t) {
+        if (a.ablate & 64) return; // measurement: no KV traffic
         const int p0w = kv_begin + t * KT + WPOS * wave; // this wave's positions
-        const int slot = t & 1;
-        const int pidx = __builtin_amdgcn_readfirstlane(min(p0w, kv_end - 1) >> ps_log2);
-        const int page = clamp_page(pt_row[pidx], num_pages); // 8 aligned positions share a page
+        const int slot = t % NST;
         const uint32_t ldsK = lds_base + slot * STAGEB + (WPOS * wave) * ROWB;
         const uint32_t ldsV = ldsK + TILEB;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
+            // 8 aligned positions share a page: one scalar page-table read per load
+            const int pidx = __builtin_amdgcn_readfirstlane(min(p0w + (i * TPI / 8) * 8, kv_end - 1) >> ps_log2);
+            const int page = clamp_page(pt_row[pidx], num_pages);
             const int pos = min(p0w + i * TPI + ld_tok, kv_end - 1);
             const bool cached = pos < ctx;
             const size_t tokidx = cached ? (((size_t)page << ps_log2) + (size_t)(pos & ps_mask))
@@ -473,69 +489,115 @@ __global__ void __launch_bounds__(512) rpa_wide_kernel(KernelArgs a) {
         }
     };
 
-    f32x16 o[DPL];
+    f32x16 o[NT][DPL];
+    float m_run[NT], l_run[NT];
 #pragma unroll
-    for (int j = 0; j < DPL; ++j)
+    for (int nt = 0; nt < NT; ++nt) {
+        m_run[nt] = -INFINITY;
+        l_run[nt] = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[j][v] = 0.f;
-    float m_run = -INFINITY;
-    float l_run = 0.f;
+        for (int j = 0; j < DPL; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[nt][j][v] = 0.f;
+    }
 
     // LDS read offsets inside a tile, one register per distinct swizzle; the
     // remaining terms of every read are compile-time immediates.
     //   K operand (row 32*mt + n32, chunk 2*kk + h):  koff[kk] + mt * 32 * ROWB
-    //   V rows of k-step ks, element e:              voff[e] + (32*(ks/2) + 16*(ks%2)) * ROWB
-    uint32_t koff[KSTEPS], voff[8];
+    //   V, dims 32*jb .. 32*jb+31, read rd:           voff[jb][rd] + (32*mt + 16*kh) * ROWB
+    // V is read with the transposing LDS load: in each group of 16 lanes, lane
+    // 4k + r supplies 8 bytes (4 dims) of one position and lane i receives, as
+    // element k, the i-th of the 16 dims that lanes 4k .. 4k+3 supplied.  With
+    // lane 4k + r reading position P + k, dims D0 + 4r .. 4r+3, lane i ends up
+    // with dim D0 + i of positions P .. P+3: a piece of the V^T operand with no
+    // register shuffling.  Read 0 takes positions 4h .. 4h+3 of the 16-position
+    // k-step, read 1 positions 8+4h .. 8+4h+3 (the order the weights are in).
+    uint32_t koff[KSTEPS], voff[DPL][2];
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) koff[kk] = n32 * ROWB + (((2 * kk + h) ^ (n32 % NC)) * 16);
+    {
+        const int j16 = lane & 15, half16 = (lane >> 4) & 1;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int r = 8 * (e >> 2) + 4 * h + (e & 3); // row modulo 16
-        voff[e] = r * ROWB + ((((n32 * DPL) / 8) ^ (r % NC)) * 16) + ((n32 * DPL) % 8) * 2;
+        for (int jb = 0; jb < DPL; ++jb)
+#pragma unroll
+            for (int rd = 0; rd < 2; ++rd) {
+                const int r = 4 * h + (j16 >> 2) + 8 * rd; // position modulo 16
+                const int chunk = 4 * jb + 2 * half16 + ((j16 & 3) >> 1);
+                voff[jb][rd] = r * ROWB + ((chunk ^ (r % NC)) * 16) + (j16 & 1) * 8;
+            }
     }
 
-    // One 32-position half of a tile: scores, online-softmax update, PV.  Working
-    // in halves keeps the live score registers at 16 per lane.
+    // One 32-position half of a tile: scores, online-softmax update, PV.
     auto compute_half = [&](const char* ldsK, const char* ldsV, int pos0, int mt_, auto masked) {
         constexpr bool MASKED = decltype(masked)::value;
         const int mt = mt_;
         // ---- S^T = K Q^T (Alg. 1: S <- C_q C_k^T) --------------------------------
-        f32x16 s;
+        f32x16 s[NT];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[v] = 0.f;
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[nt][v] = 0.f;
+        // all K operands of the half are requested before the first MFMA, so the
+        // LDS latency is paid once per half, not once per MFMA pair
+        bf16x8 kop[KSTEPS];
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) kop[kk] = *(const bf16x8*)(ldsK + koff[kk] + mt * 32 * ROWB);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) {
-            const bf16x8 kop = *(const bf16x8*)(ldsK + koff[kk] + mt * 32 * ROWB);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[kk], s, 0, 0, 0);
-            if (kk % 4 == 3) __builtin_amdgcn_sched_barrier(0); // bound the operand look-ahead (registers)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kk], qreg[nt][kk], s[nt], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
         // ---- mask + online softmax (Alg. 1: m~, P, l~) ------------------------
         // position of element v is pos0 + 32*mt + 4*h + c with the compile-time
         // c = 8*(v/4) + v%4: visible iff c <= rel.  sm_scale > 0, so the row
         // maximum is taken on the raw scores and scaled once.
-        float mx = -INFINITY;
-        const int rel = min(limit, kv_end - 1) - pos0 - 32 * mt - 4 * h;
+        bf16x8 pop[NT][2];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            if (MASKED) s[v] = (8 * (v / 4) + (v % 4) <= rel) ? s[v] : -INFINITY;
-            mx = fmaxf(mx, s[v]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx * a.scale_log2);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run - m_use);
-        float psum = 0.f;
+        for (int nt = 0; nt < NT; ++nt) {
+            float mx = -INFINITY;
+            const int rel = min(limit[nt], kv_end - 1) - pos0 - 32 * mt - 4 * h;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const float pv = fast_exp2(__builtin_fmaf(s[v], a.scale_log2, -m_use));
-            s[v] = pv;
-            psum += pv;
-        }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) { // skip when no row's maximum moved
+            for (int v = 0; v < 16; ++v) {
+                if (MASKED) s[nt][v] = (8 * (v / 4) + (v % 4) <= rel) ? s[nt][v] : -INFINITY;
+                mx = fmaxf(mx, s[nt][v]);
+            }
+            if (a.ablate & 4) mx = 0.f; else
+            mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2;
+            // The reference maximum only moves when the row maximum exceeds it by
+            // more than kRescaleGap (log2 units): weights may reach 2^gap, which fp32
+            // and bf16 hold exactly as well, and the rescale of O becomes rare.  The
+            // result is unchanged: numerator and l share the reference.
+            const float m_new = (mx > m_run[nt] + kRescaleGap) ? mx : m_run[nt];
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = fast_exp2(m_run[nt] - m_use);
+            float psum = 0.f;
+            if (!(a.ablate & 8)) {
 #pragma unroll
-            for (int j = 0; j < DPL; ++j) o[j] *= alpha;
+            for (int v = 0; v < 16; ++v) {
+                const float pv = fast_exp2(__builtin_fmaf(s[nt][v], a.scale_log2, -m_use));
+                s[nt][v] = pv;
+                psum += pv;
+            }
+            }
+            l_run[nt] = l_run[nt] * alpha + psum;
+            m_run[nt] = m_new;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) { // skip when no row's maximum moved
+#pragma unroll
+                for (int j = 0; j < DPL; ++j) o[nt][j] *= alpha;
+            }
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh) {
+                union {
+                    uint32_t w[4];
+                    bf16x8 v;
+                } pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pk.w[e] = pack_bf16(s[nt][8 * kh + 2 * e], s[nt][8 * kh + 2 * e + 1]);
+                pop[nt][kh] = pk.v;
+            }
         }
         // ---- O^T += V^T P^T (Alg. 1: C_o <- ... + P C_v) --------------------------
         // k-step kh covers positions 32*mt + 8*(2*kh + e/4) + 4*h + e%4, e = 0..7,
@@ -543,100 +605,126 @@ __global__ void __launch_bounds__(512) rpa_wide_kernel(KernelArgs a) {
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh) {
             __builtin_amdgcn_sched_barrier(0);
+            if (a.ablate & 16) continue;
+            const char* src = ldsV + (32 * mt + 16 * kh) * ROWB;
             union {
-                uint32_t w[4];
+                short4v p[2];
                 bf16x8 v;
-            } pk;
+            } vop[DPL];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) pk.w[e] = pack_bf16(s[8 * kh + 2 * e], s[8 * kh + 2 * e + 1]);
-            uint32_t vr[8][DPL / 2];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const char* src = ldsV + voff[e] + (32 * mt + 16 * kh) * ROWB;
-                if constexpr (DPL == 4) {
-                    const uint2 raw = *(const uint2*)src;
-                    vr[e][0] = raw.x;
-                    vr[e][1] = raw.y;
-                } else {
-                    vr[e][0] = *(const uint32_t*)src;
-                }
+            for (int jb = 0; jb < DPL; ++jb) {
+                vop[jb].p[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(src + voff[jb][0]));
+                vop[jb].p[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(src + voff[jb][1]));
             }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < DPL; ++j) {
-                const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-                union {
-                    uint32_t w[4];
-                    bf16x8 v;
-                } vop;
+            for (int jb = 0; jb < DPL; ++jb)
 #pragma unroll
-                for (int d = 0; d < 4; ++d) vop.w[d] = __builtin_amdgcn_perm(vr[2 * d + 1][j / 2], vr[2 * d][j / 2], sel);
-                o[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop.v, pk.v, o[j], 0, 0, 0);
-            }
+                for (int nt = 0; nt < NT; ++nt)
+                    o[nt][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[jb].v, pop[nt][kh], o[nt][jb], 0, 0, 0);
         }
     };
+    // The two halves run through one copy of the code (a real loop): unrolled
+    // copies cost the register allocator dozens of registers.
     auto compute_tile = [&](const char* ldsK, const char* ldsV, int pos0, auto masked) {
-        compute_half(ldsK, ldsV, pos0, 0, masked);
-        __builtin_amdgcn_sched_barrier(0);
-        if (pos0 + 32 <= wave_limit) compute_half(ldsK, ldsV, pos0, 1, masked);
+        const int nh = (pos0 + 32 <= wave_limit) ? 2 : 1;
+#pragma unroll 1
+        for (int mt = 0; mt < nh; ++mt) compute_half(ldsK, ldsV, pos0, mt, masked);
     };
 
-    if (ntiles > 0) issue_tile(0);
-    wait_vmcnt<0>();
+    // Ring of NST stages: tile t+NST-1 is requested before tile t is consumed, so
+    // a tile has NST-1 tile times to arrive.  Each wave waits for its own loads
+    // of the next tile, the barrier then makes the whole tile visible.
+    constexpr int LPT = 2 * NLD; // loads per wave per tile
+#pragma unroll
+    for (int s0 = 0; s0 < NST - 1; ++s0)
+        if (s0 < ntiles) issue_tile(s0);
+    if (ntiles > 1 && NST > 2) wait_vmcnt<(NST > 2 ? (NST - 2) * LPT : 0)>();
+    else wait_vmcnt<0>();
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
-        if (t + 1 < ntiles) issue_tile(t + 1);
-        const char* ldsK = lds_ptr + (t & 1) * STAGEB;
+        if (t + NST - 1 < ntiles) issue_tile(t + NST - 1);
+        const char* ldsK = lds_ptr + (t % NST) * STAGEB;
         const char* ldsV = ldsK + TILEB;
         const int pos0 = kv_begin + t * KT;
-        if (pos0 <= wave_limit) { // tiles wholly above the wave's diagonal are skipped
+        if (pos0 <= wave_limit && !(a.ablate & 128)) { // tiles wholly above the wave's diagonal are skipped
             if ((pos0 + KT > kv_end) || (pos0 + KT - 1 > wave_min_limit))
                 compute_tile(ldsK, ldsV, pos0, std::true_type{});
             else
                 compute_tile(ldsK, ldsV, pos0, std::false_type{});
         }
-        wait_vmcnt<0>();
-        __syncthreads();
+        // tile t+1 must have landed; tiles t+2 .. may still be in flight
+        const int behind = min(NST - 2, ntiles - 2 - t);
+        if (NST >= 4 && behind >= 2) wait_vmcnt<(NST >= 4 ? 2 : 0) * LPT>();
+        else if (NST >= 3 && behind == 1) wait_vmcnt<(NST >= 3 ? 1 : 0) * LPT>();
+        else wait_vmcnt<0>();
+        if (!(a.ablate & 32)) __syncthreads();
     }
 
     // ---- finalize (Alg. 1: diag(l)^-1 B_o) or store the partial state ------------
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (row_ok) {
-        if (u.part_row < 0) {
-            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-            uint16_t* orow = a.out + ((size_t)(u.q_start + tok) * Hq + head) * D;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int mrow = 8 * (v / 4) + 4 * h + (v % 4);
-                if constexpr (DPL == 4) {
+    for (int nt = 0; nt < NT; ++nt) {
+        const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
+        if (a.ablate & 256) continue;
+        if (!row_ok[nt] && u.part_row >= 0) continue;
+        if (u.part_row < 0) {
+            // Rows go through this wave's slice of the (now idle) LDS ring so that
+            // the global stores are whole 256-byte rows, 16 lanes per row.  The
+            // loop's last barrier guarantees nobody still reads the ring.
+            constexpr int SROW = ROWB + 16; // padded row: conflict-free 8-byte writes
+            char* stage = (char*)smem + (size_t)(NT * wave + nt) * 32 * SROW;
+            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+            // accumulator element v of block jb is dim 32*jb + 8*(v/4) + 4*h + v%4
+#pragma unroll
+            for (int jb = 0; jb < DPL; ++jb)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
                     uint2 w;
-                    w.x = pack_bf16(o[0][v] * inv, o[1][v] * inv);
-                    w.y = pack_bf16(o[2][v] * inv, o[3][v] * inv);
-                    *(uint2*)(orow + DPL * mrow) = w;
-                } else {
-                    *(uint32_t*)(orow + DPL * mrow) = pack_bf16(o[0][v] * inv, o[1][v] * inv);
+                    w.x = pack_bf16(o[nt][jb][4 * q4] * inv, o[nt][jb][4 * q4 + 1] * inv);
+                    w.y = pack_bf16(o[nt][jb][4 * q4 + 2] * inv, o[nt][jb][4 * q4 + 3] * inv);
+                    *(uint2*)(stage + n32 * SROW + (32 * jb + 8 * q4 + 4 * h) * 2) = w;
                 }
-            }
         } else {
-            const size_t prow = (size_t)u.part_row + (size_t)tok * Hq + head;
+            const size_t prow = (size_t)u.part_row + (size_t)tok[nt] * Hq + head[nt];
             float* po = a.part_o + prow * D;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int mrow = 8 * (v / 4) + 4 * h + (v % 4);
+            for (int jb = 0; jb < DPL; ++jb)
 #pragma unroll
-                for (int j = 0; j < DPL; ++j) po[DPL * mrow + j] = o[j][v];
-            }
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    float4 w = make_float4(o[nt][jb][4 * q4], o[nt][jb][4 * q4 + 1], o[nt][jb][4 * q4 + 2],
+                                           o[nt][jb][4 * q4 + 3]);
+                    *(float4*)(po + 32 * jb + 8 * q4 + 4 * h) = w;
+                }
             if (h == 0) {
-                a.part_ml[prow * 2] = m_run;
+                a.part_ml[prow * 2] = m_run[nt];
                 a.part_ml[prow * 2 + 1] = l_tot;
             }
         }
     }
 
+    if (u.part_row < 0 && !(a.ablate & 256)) {
+        constexpr int SROW = ROWB + 16;
+        constexpr int RPI = 64 / NC; // rows per wave-wide 16-byte store
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const char* stage = (const char*)smem + (size_t)(NT * wave + nt) * 32 * SROW;
+#pragma unroll
+            for (int i = 0; i < 32 / RPI; ++i) {
+                const int r = i * RPI + lane / NC;
+                const int rho = 32 * (NT * wave + nt) + r;
+                const int t_r = rho & tq_mask, h_r = rho >> tq_log2;
+                const uint4 w = *(const uint4*)(stage + r * SROW + (lane % NC) * 16);
+                if (t_r < u.n_q)
+                    *(uint4*)(a.out + ((size_t)(u.q_start + t_r) * Hq + g * hg + h_r) * D + (lane % NC) * 8) = w;
+            }
+        }
+    }
+
     // ---- fused cache update for the tile's new tokens (see the narrow kernel)
-    if (u.flags & 1) {
+    if ((u.flags & 1) && !(a.ablate & 512)) {
         const int c = threadIdx.x % NC;
-        for (int t = threadIdx.x / NC; t < u.n_q; t += 512 / NC) {
+        for (int t = threadIdx.x / NC; t < u.n_q; t += (64 * WAVES) / NC) {
             const int pos = ctx + u.q_pos0 + t;
             const int page = clamp_page(pt_row[pos >> ps_log2], num_pages);
             const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * D + c * 8;
@@ -703,7 +791,7 @@ static size_t narrow_lds_bytes(int waves) {
 
 template <int D>
 static size_t wide_lds_bytes() {
-    return (size_t)2 * 2 * kWideKvTile * D * 2;
+    return (size_t)kWideStages * 2 * kWideKvTile * D * 2;
 }
 
 int kernels_init(int device, std::string& err) {
@@ -715,10 +803,16 @@ int kernels_init(int device, std::string& err) {
         e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<64, kNarrowStages>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<64>(kMaxWaves));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)wide_lds_bytes<128>());
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)wide_lds_bytes<128>());
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)wide_lds_bytes<64>());
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)wide_lds_bytes<64>());
     if (e != hipSuccess) {
         err = std::string("hipFuncSetAttribute: ") + hipGetErrorString(e);
@@ -747,10 +841,14 @@ int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev) {
     if (num_units <= 0) return 0;
     dim3 grid((unsigned)num_units * a.num_kv_heads);
     hipStream_t st = (hipStream_t)stream;
-    if (a.head_dim == 128)
-        RPA_LAUNCH((rpa_wide_kernel<128>), grid, dim3(512), wide_lds_bytes<128>(), st, ev, a);
-    else
-        RPA_LAUNCH((rpa_wide_kernel<64>), grid, dim3(512), wide_lds_bytes<64>(), st, ev, a);
+    const bool two = (a.ablate & 2) != 0; // measurement switch: bit 1 selects the 4-wave, 64-rows-per-wave shape
+    if (a.head_dim == 128) {
+        if (two) RPA_LAUNCH((rpa_wide_kernel<128, 2>), grid, dim3(256), wide_lds_bytes<128>(), st, ev, a);
+        else RPA_LAUNCH((rpa_wide_kernel<128, 1>), grid, dim3(512), wide_lds_bytes<128>(), st, ev, a);
+    } else {
+        if (two) RPA_LAUNCH((rpa_wide_kernel<64, 2>), grid, dim3(256), wide_lds_bytes<64>(), st, ev, a);
+        else RPA_LAUNCH((rpa_wide_kernel<64, 1>), grid, dim3(512), wide_lds_bytes<64>(), st, ev, a);
+    }
     return (int)hipGetLastError();
 }
 
