@@ -24,6 +24,7 @@
 #ifndef RPA_H
 #define RPA_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -115,9 +116,17 @@ typedef struct {
                               num_kv_heads, at most 8; 0 = auto                       */
     int32_t units_per_cu;  /* narrow bins per resident workgroup slot (1 = exactly one
                               wave of workgroups); 0 = default                        */
-    int32_t ablate;        /* measurement only (the paper's ablation method, Sec. 4):
-                              bit 0 = skip the attention math of the narrow kernel (loads
-                              and stores stay); results are then meaningless           */
+    int32_t ablate;        /* measurement only (ablation by leaving a stage out, as in
+                              the paper's kernel analysis, Sec. 4); outputs are then
+                              meaningless, every access stays in bounds.  Bits:
+                                1   narrow kernel: loads and stores only, no math
+                                4   wide kernel: no row maximum (reference fixed at 0)
+                                8   wide kernel: no exponentials / P tile
+                                16  wide kernel: no P.V product
+                                64  wide kernel: no K/V loads and no compute
+                                128 wide kernel: K/V loads only, no compute
+                                256 wide kernel: no output store
+                                512 wide kernel: no cache write                        */
     int32_t reserved[2];
 } rpa_options;
 
@@ -191,6 +200,15 @@ int rpa_set_options(rpa_ctx* ctx, const rpa_options* opt);
 int rpa_profile_enable(rpa_ctx* ctx, int on);
 int rpa_profile_read(rpa_ctx* ctx, float* narrow_ms, float* wide_ms, float* combine_ms,
                      int32_t* calls);
+
+/* Measurement aid (not part of the paper's method): a plain device-to-device
+ * copy of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned, the
+ * ranges must not overlap) by an ordinary streaming kernel on `stream`.  It is
+ * the known-size workload that hardware HBM byte counters and the attention
+ * kernels' bandwidth figures are calibrated against.  If ms is not NULL the
+ * call waits for the kernel and stores its duration in milliseconds.         */
+int rpa_copy_probe(rpa_ctx* ctx, void* dst, const void* src, size_t bytes, void* stream,
+                   float* ms);
 
 /* Host-only planning, no GPU needed: the work partition that
  * rpa_update_and_attend would use on a device with `num_cus` compute units

@@ -212,6 +212,33 @@ extern "C" int rpa_profile_read(rpa_ctx* c, float* narrow_ms, float* wide_ms, fl
     return RPA_OK;
 }
 
+extern "C" int rpa_copy_probe(rpa_ctx* c, void* dst, const void* src, size_t bytes, void* stream, float* ms) {
+    if (!c) return RPA_ERR_INVALID_ARG;
+    if (!dst || !src || bytes % 16 != 0 || ((uintptr_t)dst | (uintptr_t)src) % 16 != 0)
+        return fail(c, RPA_ERR_INVALID_ARG, "rpa_copy_probe: pointers and size must be multiples of 16");
+    const char *d = (const char*)dst, *s = (const char*)src;
+    if (d < s + bytes && s < d + bytes) return fail(c, RPA_ERR_INVALID_ARG, "rpa_copy_probe: ranges overlap");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, "hipSetDevice", e);
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    if (ms) {
+        for (auto& x : ev) {
+            e = hipEventCreate(&x);
+            if (e != hipSuccess) return hip_fail(c, "hipEventCreate", e);
+        }
+    }
+    int rc = launch_copy(dst, src, bytes / 16, c->num_cus, stream, ms ? (void**)ev : nullptr);
+    if (rc == 0 && ms) {
+        e = hipEventSynchronize(ev[1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(ms, ev[0], ev[1]);
+        rc = (int)e;
+    }
+    for (auto& x : ev)
+        if (x) (void)hipEventDestroy(x);
+    if (rc != 0) return hip_fail(c, "rpa_copy_probe", (hipError_t)rc);
+    return RPA_OK;
+}
+
 extern "C" int rpa_plan_host(const rpa_shape* shape, const int32_t* cu_q_lens, const int32_t* kv_lens,
                              int32_t num_seqs, const rpa_options* opt, int num_cus, rpa_work_unit* units,
                              int32_t max_units, rpa_combine_item* items, int32_t max_items,

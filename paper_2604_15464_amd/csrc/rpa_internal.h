@@ -81,6 +81,7 @@ int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev);
 int launch_combine(const rpa_combine_item* items, int num_items, const float* part_o,
                    const float* part_ml, uint16_t* out, int num_q_heads, int head_dim,
                    void* stream, void** ev);
+int launch_copy(void* dst, const void* src, size_t n16, int num_cus, void* stream, void** ev);
 int kernels_init(int device, std::string& err);
 
 } // namespace rpa

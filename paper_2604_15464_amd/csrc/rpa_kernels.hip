@@ -659,7 +659,7 @@ __global__ void __launch_bounds__(512 / NT) rpa_wide_kernel(KernelArgs a) {
         if (NST >= 4 && behind >= 2) wait_vmcnt<(NST >= 4 ? 2 : 0) * LPT>();
         else if (NST >= 3 && behind == 1) wait_vmcnt<(NST >= 3 ? 1 : 0) * LPT>();
         else wait_vmcnt<0>();
-        if (!(a.ablate & 32)) __syncthreads();
+        __syncthreads();
     }
 
     // ---- finalize (Alg. 1: diag(l)^-1 B_o) or store the partial state ------------
@@ -782,6 +782,17 @@ __global__ void __launch_bounds__(256) rpa_combine_kernel(const rpa_combine_item
 }
 
 // ---------------------------------------------------------------------------
+// Plain streaming copy, 16 bytes per lane per step.  Not part of the method: it
+// is the known-size workload against which HBM byte counters and the narrow
+// kernel's bandwidth are calibrated.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rpa_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                       size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 template <int D>
@@ -806,13 +817,7 @@ int kernels_init(int device, std::string& err) {
         e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)wide_lds_bytes<128>());
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)wide_lds_bytes<128>());
-    if (e == hipSuccess)
         e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)wide_lds_bytes<64>());
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)wide_lds_bytes<64>());
     if (e != hipSuccess) {
         err = std::string("hipFuncSetAttribute: ") + hipGetErrorString(e);
@@ -837,18 +842,24 @@ int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream, vo
     return (int)hipGetLastError();
 }
 
+int launch_copy(void* dst, const void* src, size_t n16, int num_cus, void* stream, void** ev) {
+    if (n16 == 0) return 0;
+    const size_t want = (n16 + 255) / 256;
+    const size_t cap = (size_t)num_cus * 8;
+    dim3 grid((unsigned)(want < cap ? want : cap));
+    RPA_LAUNCH(rpa_copy_kernel, grid, dim3(256), 0, (hipStream_t)stream, ev, (uint4*)dst, (const uint4*)src, n16);
+    return (int)hipGetLastError();
+}
+
 int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev) {
     if (num_units <= 0) return 0;
     dim3 grid((unsigned)num_units * a.num_kv_heads);
     hipStream_t st = (hipStream_t)stream;
-    const bool two = (a.ablate & 2) != 0; // measurement switch: bit 1 selects the 4-wave, 64-rows-per-wave shape
-    if (a.head_dim == 128) {
-        if (two) RPA_LAUNCH((rpa_wide_kernel<128, 2>), grid, dim3(256), wide_lds_bytes<128>(), st, ev, a);
-        else RPA_LAUNCH((rpa_wide_kernel<128, 1>), grid, dim3(512), wide_lds_bytes<128>(), st, ev, a);
-    } else {
-        if (two) RPA_LAUNCH((rpa_wide_kernel<64, 2>), grid, dim3(256), wide_lds_bytes<64>(), st, ev, a);
-        else RPA_LAUNCH((rpa_wide_kernel<64, 1>), grid, dim3(512), wide_lds_bytes<64>(), st, ev, a);
-    }
+    // One 32-row group per wave: with two, an operand read would feed two MFMAs,
+    // but the 512-register shape that needs is beyond what the compiler allocates
+    // without spilling.
+    if (a.head_dim == 128) RPA_LAUNCH((rpa_wide_kernel<128, 1>), grid, dim3(512), wide_lds_bytes<128>(), st, ev, a);
+    else RPA_LAUNCH((rpa_wide_kernel<64, 1>), grid, dim3(512), wide_lds_bytes<64>(), st, ev, a);
     return (int)hipGetLastError();
 }
 

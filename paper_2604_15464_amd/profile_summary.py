@@ -1,0 +1,151 @@
+"""Turn rocprofv3 output of a bench.py run into the short text / JSON summaries
+kept under profiles/.
+
+    python -m paper_2604_15464_amd.profile_summary kernels <dir-or-db> <out.txt> "<command>"
+        rocprofv3 --kernel-trace --stats (rocpd database): per-kernel call count,
+        total and average duration, launch shape of this library's kernels.
+
+    python -m paper_2604_15464_amd.profile_summary traffic <fetch-dir> <write-dir> <out.json> <out.txt> "<command>"
+        two rocprofv3 --pmc runs with --output-format csv (FETCH_SIZE, then
+        WRITE_SIZE; both count KiB per dispatch): HBM bytes per launch of each
+        of this library's kernels, each counter scaled by what it reads for the
+        plain copy kernel (rpa_copy_kernel) of known size that
+        `bench.py --copy-bytes` runs in the same process.
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import glob
+import json
+import os
+import sqlite3
+import sys
+
+KERNELS = ("rpa_narrow_kernel", "rpa_wide_kernel", "rpa_combine_kernel", "rpa_copy_kernel")
+
+
+def short_name(name: str) -> str:
+    for k in KERNELS:
+        if k in name:
+            tail = name.split(k, 1)[1]
+            targs = tail.split(">", 1)[0] + ">" if tail.startswith("<") else ""
+            return k + targs
+    return name if len(name) <= 60 else name[:57] + "..."
+
+
+def find(path: str, pattern: str) -> str:
+    if os.path.isfile(path):
+        return path
+    hits = sorted(glob.glob(os.path.join(path, "**", pattern), recursive=True))
+    if not hits:
+        raise SystemExit(f"no {pattern} under {path}")
+    return hits[-1]
+
+
+def kernels(src: str, out: str, command: str) -> None:
+    cur = sqlite3.connect(find(src, "*.db")).cursor()
+    lines = [f"command: {command}", "source: rocprofv3 --kernel-trace --stats (rocpd database, view top_kernels)", "",
+             f"{'kernel':44s} {'calls':>6s} {'total_us':>12s} {'avg_us':>10s} {'pct':>6s}"]
+    for name, calls, total, avg, pct in cur.execute(
+            "select name,total_calls,total_duration,average,percentage from top_kernels"):
+        lines.append(f"{short_name(name):44s} {calls:6d} {total:12.1f} {avg:10.2f} {pct:6.2f}")
+    rows = [r for r in cur.execute("select name,start,end,grid_x,grid_y,workgroup_x,lds_size,vgpr_count,"
+                                   "accum_vgpr_count,scratch_size from kernels order by start")
+            if any(k in r[0] for k in KERNELS)]
+    # per-kernel average over the second half of its launches (steady state, after warm-up)
+    by = collections.defaultdict(list)
+    for r in rows:
+        by[short_name(r[0])].append(r)
+    lines += ["", "this library's kernels: average over the last half of the launches of each, and launch shape"]
+    for name, rs in by.items():
+        tail = rs[len(rs) // 2:]
+        avg = sum(r[2] - r[1] for r in tail) / len(tail) / 1e3
+        r = rs[-1]
+        lines.append(f"  {name:32s} n={len(rs):4d} steady_avg_us={avg:9.2f} grid_threads=({r[3]},{r[4]}) wg={r[5]} "
+                     f"lds={r[6]} vgpr={r[7]} agpr={r[8]} scratch={r[9]}")
+    text = "\n".join(lines) + "\n"
+    with open(out, "w") as f:
+        f.write(text)
+    print(text)
+
+
+def read_counter(path: str, counter: str) -> dict:
+    """kernel (without template arguments) -> per-dispatch (value, grid size) of
+    `counter`, in dispatch order."""
+    vals = collections.defaultdict(list)
+    with open(find(path, "*counter_collection.csv"), newline="") as f:
+        for r in csv.DictReader(f):
+            if r["Counter_Name"] != counter:
+                continue
+            name = r["Kernel_Name"]
+            if not any(k in name for k in KERNELS):
+                continue
+            base = next(k for k in KERNELS if k in name)
+            vals[base].append((int(r["Dispatch_Id"]), float(r["Counter_Value"]), int(r["Grid_Size"])))
+    return {k: [(v, g) for _, v, g in sorted(rows)] for k, rows in vals.items()}
+
+
+def traffic(fetch_dir: str, write_dir: str, out_json: str, out_txt: str, command: str) -> None:
+    with open(find(fetch_dir, "bench*.json")) as f:
+        bench = json.loads(f.read().strip().splitlines()[-1])
+    copy_bytes = int(bench["stream_copy"]["bytes"])
+    fetch = read_counter(fetch_dir, "FETCH_SIZE")
+    write = read_counter(write_dir, "WRITE_SIZE")
+
+    def steady(rows):
+        tail = rows[len(rows) // 2:]
+        return sum(v for v, _ in tail) / len(tail)
+
+    kib = 1024.0
+    cf = copy_bytes / (steady(fetch["rpa_copy_kernel"]) * kib)
+    cw = copy_bytes / (steady(write["rpa_copy_kernel"]) * kib)
+    workloads = {
+        bench["config"]["name"]: {"rpa_narrow_kernel": bench["config"]["algorithmic_bytes_per_step"]},
+    }
+    if "prefill" in bench:
+        workloads[bench["prefill"]["config"]["name"]] = {
+            "rpa_wide_kernel": bench["prefill"]["config"]["algorithmic_bytes_per_step"]}
+    out = {"command": command,
+           "calibration": {"copy_bytes": copy_bytes, "fetch_scale": cf, "write_scale": cw,
+                           "note": "scale = known bytes of the plain copy kernel / (counter * 1024)"}}
+    lines = [f"command: {command}",
+             "source: two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), csv output",
+             f"calibration: rpa_copy_kernel moves {copy_bytes} B each way; FETCH_SIZE reads "
+             f"{steady(fetch['rpa_copy_kernel']):.0f} KiB -> scale {cf:.4f}; WRITE_SIZE reads "
+             f"{steady(write['rpa_copy_kernel']):.0f} KiB -> scale {cw:.4f}", "",
+             f"{'workload':16s} {'kernel':28s} {'fetch_B':>14s} {'write_B':>14s} {'hbm_B/launch':>14s} "
+             f"{'algorithmic_B':>14s} {'ratio':>6s}"]
+    for wname, ks in workloads.items():
+        out[wname] = {}
+        for kname, alg in ks.items():
+            # the decode workload launches only the narrow kernel and the prefill
+            # workload only the wide one, so every dispatch of a kernel belongs to one workload
+            grids = collections.Counter(g for _, g in fetch[kname])
+            fb = steady(fetch[kname]) * kib * cf
+            wb = steady(write[kname]) * kib * cw
+            out[wname][kname] = {"hbm_bytes_per_launch": round(fb + wb), "fetch_bytes": round(fb),
+                                               "write_bytes": round(wb), "algorithmic_bytes": alg,
+                                               "launches": len(fetch[kname]), "grids": dict(grids)}
+            lines.append(f"{wname:16s} {kname:28s} {fb:14.0f} {wb:14.0f} {fb + wb:14.0f} {alg:14d} "
+                         f"{(fb + wb) / alg:6.3f}")
+    with open(out_json, "w") as f:
+        json.dump(out, f, indent=1)
+        f.write("\n")
+    text = "\n".join(lines) + "\n"
+    with open(out_txt, "w") as f:
+        f.write(text)
+    print(text)
+
+
+def main(argv):
+    if len(argv) >= 5 and argv[1] == "kernels":
+        kernels(argv[2], argv[3], argv[4])
+    elif len(argv) >= 7 and argv[1] == "traffic":
+        traffic(argv[2], argv[3], argv[4], argv[5], argv[6])
+    else:
+        raise SystemExit(__doc__)
+
+
+if __name__ == "__main__":
+    main(sys.argv)

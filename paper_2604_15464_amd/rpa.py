@@ -61,7 +61,7 @@ class RpaError(RuntimeError):
 _lib = None
 
 EXPORTS = ("rpa_create", "rpa_destroy", "rpa_update_and_attend", "rpa_last_error", "rpa_plan_info",
-           "rpa_set_options", "rpa_plan_host", "rpa_profile_enable", "rpa_profile_read")
+           "rpa_set_options", "rpa_plan_host", "rpa_profile_enable", "rpa_profile_read", "rpa_copy_probe")
 
 
 def lib():
@@ -95,6 +95,8 @@ def lib():
                                 C.POINTER(WorkUnit), C.c_int32, C.POINTER(CombineItem), C.c_int32,
                                 C.POINTER(PlanStats)]
     l.rpa_plan_host.restype = C.c_int
+    l.rpa_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
+    l.rpa_copy_probe.restype = C.c_int
     _lib = l
     return l
 
@@ -193,6 +195,22 @@ class RaggedPagedAttention:
         if rc != RPA_OK:
             raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())
         return {"narrow_ms": a.value, "wide_ms": b.value, "combine_ms": c_.value, "calls": n.value}
+
+    def copy_probe(self, dst, src, timed=True):
+        """Plain streaming copy src -> dst (contiguous cuda tensors of equal byte
+        size); returns the kernel's milliseconds when timed."""
+        import torch
+
+        nbytes = src.numel() * src.element_size()
+        if dst.numel() * dst.element_size() != nbytes or not (src.is_contiguous() and dst.is_contiguous()):
+            raise ValueError("copy_probe: contiguous tensors of equal byte size expected")
+        ms = C.c_float()
+        rc = self._lib.rpa_copy_probe(self._ctx, dst.data_ptr(), src.data_ptr(), nbytes,
+                                      torch.cuda.current_stream(src.device).cuda_stream,
+                                      C.byref(ms) if timed else None)
+        if rc != RPA_OK:
+            raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())
+        return ms.value if timed else None
 
     def update_and_attend_raw(self, out_ptr, q_ptr, k_new_ptr, v_new_ptr, k_pages_ptr, v_pages_ptr,
                               page_table_ptr, cu_q_lens, kv_lens, num_seqs, sm_scale, stream_ptr):

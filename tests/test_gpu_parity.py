@@ -21,7 +21,7 @@ def to_f64(t):
 
 
 def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=True, pad_tokens=0,
-             pad_seqs=0, seqs=None, calls=1):
+             pad_seqs=0, seqs=None, calls=1, narrow_waves=0, units_per_cu=0):
     """Run the HIP path and the oracle on the workload; returns a dict of results."""
     dev = torch.device("cuda:0")
     max_tokens = wl.num_tokens + pad_tokens
@@ -32,7 +32,8 @@ def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=T
     table[:wl.num_seqs] = wl.page_table
     table_dev = torch.from_numpy(table).to(dev)
     ctx = rpa.RaggedPagedAttention.for_workload(wl, max_tokens=max(1, max_tokens), max_seqs=max(1, max_seqs))
-    ctx.set_options(variant=variant, kv_chunk=kv_chunk, wide_kv_chunk=wide_kv_chunk)
+    ctx.set_options(variant=variant, kv_chunk=kv_chunk, wide_kv_chunk=wide_kv_chunk, narrow_waves=narrow_waves,
+                    units_per_cu=units_per_cu)
     out = torch.full_like(x["q"], float("nan"))
     sentinel = out.clone()
     for _ in range(calls):
@@ -166,6 +167,58 @@ def test_empty_batch_and_errors():
     torch.cuda.synchronize()
     assert torch.equal(before_k.view(torch.int16), x["k_pages"].view(torch.int16))
     assert torch.equal(out.view(torch.int16), keep.view(torch.int16))
+    ctx.close()
+
+
+@pytest.mark.parametrize("narrow_waves,units_per_cu", [(1, 0), (2, 0), (4, 3), (8, 1), (0, 4)])
+def test_launch_shape_options(narrow_waves, units_per_cu):
+    """Waves per narrow workgroup and bins per resident slot change the launch
+    shape only: same cache bytes, outputs within the same tolerance."""
+    wl = W.ragged(31, num_seqs=24, hq=32, hkv=8, d=128, ps=16, max_q=40, max_ctx=900, p_decode=0.6)
+    res = run_case(wl, narrow_waves=narrow_waves, units_per_cu=units_per_cu)
+    check(wl, res)
+    if narrow_waves:
+        assert res["info"]["narrow_waves"] == narrow_waves
+
+
+def test_rejected_arguments_leave_everything_untouched():
+    wl = W.config(1)
+    dev = torch.device("cuda:0")
+    x = W.materialize(wl, dev)
+    table = torch.from_numpy(wl.page_table).to(dev)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl)
+    before_k = x["k_pages"].clone()
+    out = torch.full_like(x["q"], float("nan"))
+    keep = out.clone()
+    for bad_scale in (0.0, -0.125, float("nan"), float("inf")):
+        with pytest.raises(rpa.RpaError) as e:
+            ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], table,
+                                  wl.cu_q_lens, wl.kv_lens, bad_scale, out=out)
+        assert e.value.code == rpa.ERR_INVALID_ARG
+    with pytest.raises(rpa.RpaError):
+        ctx.set_options(narrow_waves=3)  # not a divisor of num_kv_heads
+    torch.cuda.synchronize()
+    assert torch.equal(before_k.view(torch.int16), x["k_pages"].view(torch.int16))
+    assert torch.equal(out.view(torch.int16), keep.view(torch.int16))
+    # the context still works after the rejected calls
+    ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], table,
+                          wl.cu_q_lens, wl.kv_lens, wl.sm_scale, out=out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out[:wl.num_tokens].float()).all()
+    ctx.close()
+
+
+def test_copy_probe_copies_and_checks_arguments():
+    wl = W.config(1)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl)
+    src = torch.arange(0, (1 << 20) + 48, dtype=torch.int32, device="cuda:0")
+    dst = torch.zeros_like(src)
+    ms = ctx.copy_probe(dst, src)
+    assert ms > 0 and torch.equal(dst, src)
+    with pytest.raises(rpa.RpaError):
+        ctx.copy_probe(dst[:3], src[:3])            # 12 bytes: not a multiple of 16
+    with pytest.raises(rpa.RpaError):
+        ctx.copy_probe(src[4:1028], src[:1024])     # overlapping ranges
     ctx.close()
 
 
