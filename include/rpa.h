@@ -104,6 +104,8 @@ typedef struct {
     int32_t narrow_waves;    /* waves per narrow workgroup                            */
     int64_t partial_rows;    /* fp32 partial rows used                                */
     int64_t workspace_bytes; /* device workspace owned by the context                 */
+    int32_t wide_rows;       /* query rows (tokens x heads of a group) per wide tile  */
+    int32_t reserved;
 } rpa_plan_stats;
 
 /* Tuning knobs; all-zero = defaults.  They change speed only, never results
@@ -127,7 +129,10 @@ typedef struct {
                                 128 wide kernel: K/V loads only, no compute
                                 256 wide kernel: no output store
                                 512 wide kernel: no cache write                        */
-    int32_t reserved[2];
+    int32_t wide_rows;     /* query rows per wide tile: 256 (eight waves, one workgroup
+                              per CU) or 128 (four waves, two workgroups per CU);
+                              0 = default                                              */
+    int32_t reserved;
 } rpa_options;
 
 typedef struct rpa_ctx rpa_ctx;

@@ -169,7 +169,8 @@ extern "C" int rpa_set_options(rpa_ctx* c, const rpa_options* opt) {
     if (opt) o = *opt;
     if (o.variant < RPA_VARIANT_AUTO || o.variant > RPA_VARIANT_MIXED || o.kv_chunk < 0 || o.wide_kv_chunk < 0 ||
         o.units_per_cu < 0 || o.narrow_waves < 0 || o.narrow_waves > kMaxWaves ||
-        (o.narrow_waves > 0 && c->shape.num_kv_heads % o.narrow_waves != 0))
+        (o.narrow_waves > 0 && c->shape.num_kv_heads % o.narrow_waves != 0) ||
+        (o.wide_rows != 0 && o.wide_rows != 128 && o.wide_rows != 256))
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: bad value");
     c->opt = o;
     return RPA_OK;
@@ -340,7 +341,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     a.page_size_log2 = __builtin_ctz((unsigned)c->shape.page_size);
     a.max_pages_per_seq = c->shape.max_pages_per_seq;
     a.num_pages = c->shape.num_pages;
-    a.wide_tq_log2 = __builtin_ctz((unsigned)wide_q_tokens(a.hg));
+    a.wide_tq_log2 = __builtin_ctz((unsigned)wide_q_tokens(a.hg, plan.stats.wide_rows));
     a.scale_log2 = sm_scale * 1.4426950408889634f;
     a.ablate = c->opt.ablate;
 
@@ -354,8 +355,11 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     a.units = dev_units + n_narrow;
     hrc = launch_wide(a, (int)n_wide, stream, pe ? (void**)&pe->ev[2] : nullptr);
     if (hrc != 0) return hip_fail(c, "wide kernel launch", (hipError_t)hrc);
+    int max_rows = 0;
+    for (const rpa_combine_item& it : plan.items) max_rows = std::max(max_rows, (int)it.rows);
     hrc = launch_combine((const rpa_combine_item*)((char*)slot.dev + items_off), (int)n_items, c->part_o, c->part_ml,
-                         (uint16_t*)out, a.num_q_heads, a.head_dim, stream, pe ? (void**)&pe->ev[4] : nullptr);
+                         (uint16_t*)out, a.num_q_heads, a.head_dim, max_rows, stream,
+                         pe ? (void**)&pe->ev[4] : nullptr);
     if (hrc != 0) return hip_fail(c, "combine kernel launch", (hipError_t)hrc);
     e = hipEventRecord(slot.done, st);
     if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);

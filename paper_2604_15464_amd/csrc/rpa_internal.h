@@ -13,11 +13,12 @@ namespace rpa {
 // Tile geometry the kernels are compiled for.
 constexpr int kNarrowRows = 16;   // query rows (tokens x heads of one group) per narrow tile
 constexpr int kNarrowKvTile = 16; // KV positions per narrow pipeline stage
-constexpr int kWideRows = 256;    // query rows per wide tile = (256 / h_g) tokens x h_g heads
+constexpr int kWideRows = 128;    // default query rows per wide tile = (128 / h_g) tokens x h_g heads
 constexpr int kWideKvTile = 64;   // KV positions per wide pipeline stage
 constexpr int kMaxWaves = 8;      // waves per narrow workgroup (one KV head each)
 constexpr int kNarrowStages = 2;   // LDS ring depth of a narrow wave
-constexpr int kWideStages = 3;     // LDS ring depth of a wide workgroup
+constexpr int kWideStages = 3;     // LDS ring depth of a 256-row wide workgroup
+constexpr int kWideStagesHalf = 2; // ... of a 128-row one (64 KB: two workgroups per CU)
 constexpr int kLdsBytesPerCu = 160 * 1024;
 
 struct Plan {
@@ -40,7 +41,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu_q_lens, const int32_t* kv_l
 inline int narrow_q_tokens(int hg) { return (hg >= 1 && hg <= kNarrowRows && kNarrowRows % hg == 0) ? kNarrowRows / hg : 0; }
 
 // Query tokens per wide tile.
-inline int wide_q_tokens(int hg) { return kWideRows / hg; }
+inline int wide_q_tokens(int hg, int rows) { return rows / hg; }
 
 // Default waves per narrow workgroup: the largest divisor of num_kv_heads not
 // above 4 (two workgroups of 64 KB LDS per compute unit at head_dim 128).
@@ -79,7 +80,7 @@ struct KernelArgs {
 int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream, void** ev);
 int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev);
 int launch_combine(const rpa_combine_item* items, int num_items, const float* part_o,
-                   const float* part_ml, uint16_t* out, int num_q_heads, int head_dim,
+                   const float* part_ml, uint16_t* out, int num_q_heads, int head_dim, int max_rows,
                    void* stream, void** ev);
 int launch_copy(void* dst, const void* src, size_t n16, int num_cus, void* stream, void** ev);
 int kernels_init(int device, std::string& err);

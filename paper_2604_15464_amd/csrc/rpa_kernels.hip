@@ -12,6 +12,7 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "rpa_internal.h"
@@ -376,16 +377,16 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 // barrier per tile.  With NT = 2 a K or V operand read from LDS feeds two
 // MFMAs.  Used for prefill and chunked prefill; MFMA-bound.
 // ---------------------------------------------------------------------------
-template <int D, int NT>
-__global__ void __launch_bounds__(512 / NT) rpa_wide_kernel(KernelArgs a) {
-    constexpr int WAVES = 8 / NT;
+template <int D, int WAVES, int NST>
+__global__ void __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2)))
+rpa_wide_kernel(KernelArgs a) {
+    constexpr int NT = 1; // 32-row groups per wave
     constexpr int ROWB = D * 2;
     constexpr int NC = D / 8;
     constexpr int TPI = 64 / NC;   // positions per wave-wide load
     constexpr int KT = kWideKvTile;
     constexpr int TILEB = KT * ROWB;
     constexpr int STAGEB = 2 * TILEB;
-    constexpr int NST = kWideStages;
     constexpr int WPOS = KT / WAVES; // positions each wave brings per tile
     constexpr int NLD = (WPOS + TPI - 1) / TPI;
     constexpr int KSTEPS = D / 16; // 32x32x16 steps over head_dim
@@ -801,8 +802,8 @@ static size_t narrow_lds_bytes(int waves) {
 }
 
 template <int D>
-static size_t wide_lds_bytes() {
-    return (size_t)kWideStages * 2 * kWideKvTile * D * 2;
+static size_t wide_lds_bytes(int stages) {
+    return (size_t)stages * 2 * kWideKvTile * D * 2;
 }
 
 int kernels_init(int device, std::string& err) {
@@ -814,11 +815,17 @@ int kernels_init(int device, std::string& err) {
         e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<64, kNarrowStages>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<64>(kMaxWaves));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)wide_lds_bytes<128>());
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 8, kWideStages>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<128>(kWideStages));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)wide_lds_bytes<64>());
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 8, kWideStages>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<64>(kWideStages));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 4, kWideStagesHalf>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<128>(kWideStagesHalf));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 4, kWideStagesHalf>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<64>(kWideStagesHalf));
     if (e != hipSuccess) {
         err = std::string("hipFuncSetAttribute: ") + hipGetErrorString(e);
         return (int)e;
@@ -858,15 +865,33 @@ int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev) {
     // One 32-row group per wave: with two, an operand read would feed two MFMAs,
     // but the 512-register shape that needs is beyond what the compiler allocates
     // without spilling.
-    if (a.head_dim == 128) RPA_LAUNCH((rpa_wide_kernel<128, 1>), grid, dim3(512), wide_lds_bytes<128>(), st, ev, a);
-    else RPA_LAUNCH((rpa_wide_kernel<64, 1>), grid, dim3(512), wide_lds_bytes<64>(), st, ev, a);
+    const bool half = (a.hg << a.wide_tq_log2) == 128; // 128-row tiles: four waves, two workgroups per CU
+    if (a.head_dim == 128) {
+        if (half)
+            RPA_LAUNCH((rpa_wide_kernel<128, 4, kWideStagesHalf>), grid, dim3(256),
+                       wide_lds_bytes<128>(kWideStagesHalf), st, ev, a);
+        else
+            RPA_LAUNCH((rpa_wide_kernel<128, 8, kWideStages>), grid, dim3(512), wide_lds_bytes<128>(kWideStages), st,
+                       ev, a);
+    } else {
+        if (half)
+            RPA_LAUNCH((rpa_wide_kernel<64, 4, kWideStagesHalf>), grid, dim3(256),
+                       wide_lds_bytes<64>(kWideStagesHalf), st, ev, a);
+        else
+            RPA_LAUNCH((rpa_wide_kernel<64, 8, kWideStages>), grid, dim3(512), wide_lds_bytes<64>(kWideStages), st,
+                       ev, a);
+    }
     return (int)hipGetLastError();
 }
 
 int launch_combine(const rpa_combine_item* items, int num_items, const float* part_o, const float* part_ml,
-                   uint16_t* out, int num_q_heads, int head_dim, void* stream, void** ev) {
+                   uint16_t* out, int num_q_heads, int head_dim, int max_rows, void* stream, void** ev) {
     if (num_items <= 0) return 0;
-    dim3 grid(num_items, 8);
+    // enough row blocks that the largest item is covered in one pass: the merge is
+    // a chain of dependent loads per row, so it wants threads, not iterations
+    const int rows_per_block = 256 / (head_dim / 4);
+    const int ny = std::min(512, std::max(1, (max_rows + rows_per_block - 1) / rows_per_block));
+    dim3 grid(num_items, ny);
     RPA_LAUNCH(rpa_combine_kernel, grid, dim3(256), 0, (hipStream_t)stream, ev, items, part_o, part_ml, out,
                num_q_heads, head_dim);
     return (int)hipGetLastError();

@@ -104,7 +104,8 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     }
     if (opt.variant < RPA_VARIANT_AUTO || opt.variant > RPA_VARIANT_MIXED || opt.kv_chunk < 0 ||
         opt.wide_kv_chunk < 0 || opt.units_per_cu < 0 || opt.narrow_waves < 0 || opt.narrow_waves > kMaxWaves ||
-        (opt.narrow_waves > 0 && s.num_kv_heads % opt.narrow_waves != 0)) {
+        (opt.narrow_waves > 0 && s.num_kv_heads % opt.narrow_waves != 0) ||
+        (opt.wide_rows != 0 && opt.wide_rows != 128 && opt.wide_rows != 256)) {
         err = "bad options";
         return RPA_ERR_INVALID_ARG;
     }
@@ -145,6 +146,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
 
     // ---- regime per sequence (Sec. 3.4) ---------------------------------
     const int64_t narrow_max_q = 2 * (int64_t)tq_narrow; // up to two narrow tiles
+    const int wide_rows = opt.wide_rows > 0 ? opt.wide_rows : kWideRows;
     bool any_narrow = false, any_wide = false;
     std::vector<Tile> tiles;
     int64_t work_wide = 0, wide_tiles = 0;
@@ -159,7 +161,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         }
         (wide ? any_wide : any_narrow) = true;
         const int32_t ctx = kv[r] - lq;
-        const int32_t tq = wide ? wide_q_tokens(hg) : tq_narrow;
+        const int32_t tq = wide ? wide_q_tokens(hg, wide_rows) : tq_narrow;
         for (int32_t i0 = 0; i0 < lq; i0 += tq) {
             Tile t{r, i0, std::min(tq, lq - i0), 0, ctx, cu[r], wide};
             t.kv_hi = ctx + i0 + t.n_q;
@@ -277,6 +279,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
 
     plan.stats.num_narrow_bins = (int32_t)plan.bins.size() - 1;
     plan.stats.narrow_waves = waves;
+    plan.stats.wide_rows = wide_rows;
     plan.stats.kv_chunk = (int32_t)std::min<int64_t>(per_bin * kNarrowKvTile, INT32_MAX);
     plan.stats.num_narrow_units = (int32_t)plan.narrow.size();
     plan.stats.num_wide_units = (int32_t)plan.wide.size();

@@ -21,7 +21,7 @@ def to_f64(t):
 
 
 def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=True, pad_tokens=0,
-             pad_seqs=0, seqs=None, calls=1, narrow_waves=0, units_per_cu=0):
+             pad_seqs=0, seqs=None, calls=1, narrow_waves=0, units_per_cu=0, wide_rows=0):
     """Run the HIP path and the oracle on the workload; returns a dict of results."""
     dev = torch.device("cuda:0")
     max_tokens = wl.num_tokens + pad_tokens
@@ -33,7 +33,7 @@ def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=T
     table_dev = torch.from_numpy(table).to(dev)
     ctx = rpa.RaggedPagedAttention.for_workload(wl, max_tokens=max(1, max_tokens), max_seqs=max(1, max_seqs))
     ctx.set_options(variant=variant, kv_chunk=kv_chunk, wide_kv_chunk=wide_kv_chunk, narrow_waves=narrow_waves,
-                    units_per_cu=units_per_cu)
+                    units_per_cu=units_per_cu, wide_rows=wide_rows)
     out = torch.full_like(x["q"], float("nan"))
     sentinel = out.clone()
     for _ in range(calls):
@@ -179,6 +179,18 @@ def test_launch_shape_options(narrow_waves, units_per_cu):
     check(wl, res)
     if narrow_waves:
         assert res["info"]["narrow_waves"] == narrow_waves
+
+
+@pytest.mark.parametrize("wide_rows", [128, 256])
+@pytest.mark.parametrize("shape", [(4, 2, 64), (32, 8, 128), (16, 1, 128), (8, 8, 64)])
+def test_wide_tile_rows(wide_rows, shape):
+    """Both wide tile heights (eight waves x 32 rows, four waves x 32 rows) on
+    prefill-heavy ragged batches, forced through the wide kernel, with splits."""
+    hq, hkv, d = shape
+    wl = W.ragged(77 + hq, num_seqs=6, hq=hq, hkv=hkv, d=d, ps=16, max_q=300, max_ctx=500, p_decode=0.1)
+    res = run_case(wl, variant=rpa.VARIANT_PREFILL, wide_rows=wide_rows, wide_kv_chunk=192)
+    check(wl, res)
+    assert res["info"]["wide_rows"] == wide_rows
 
 
 def test_rejected_arguments_leave_everything_untouched():

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def check_plan(wl, units, items, stats, narrow_tq, wide_tq=None):
-    wide_tq = wide_tq or 256 // (wl.num_q_heads // wl.num_kv_heads)
+    wide_tq = wide_tq or stats["wide_rows"] // (wl.num_q_heads // wl.num_kv_heads)
     cu = wl.cu_q_lens
     # per token: covered KV positions and writers
     cover = {}
