@@ -132,7 +132,9 @@ typedef struct {
     int32_t wide_rows;     /* query rows per wide tile: 256 (eight waves, one workgroup
                               per CU) or 128 (four waves, two workgroups per CU);
                               0 = default                                              */
-    int32_t reserved;
+    int32_t wide_order;    /* launch order of the wide units: 1 (and 0 = default)
+                              longest tile first overall; 2 = by sequence, heaviest
+                              sequence first, longest tile first inside a sequence    */
 } rpa_options;
 
 typedef struct rpa_ctx rpa_ctx;

@@ -69,6 +69,17 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// max over the two 32-lane halves of a wave, in every lane, with the register
+// swap v_permlane32_swap (no LDS round trip as a cross-half shuffle would take).
+// Written as asm: with both operands equal the compiler's model of the builtin
+// folds the second result into the first.  The leading s_nop covers the hazard
+// of a VALU write directly before the swap.
+__device__ __forceinline__ float max_across_halves(float x) {
+    float lo = x, hi = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+    return fmaxf(lo, hi);
+}
+
 __device__ __forceinline__ int clamp_page(int page, int num_pages) {
     return min(max(page, 0), num_pages - 1);
 }
@@ -551,6 +562,24 @@ rpa_wide_kernel(KernelArgs a) {
                 s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kk], qreg[nt][kk], s[nt], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
+        // The V^T fragments of the half's first 16 positions are requested now and
+        // arrive under the softmax; those of the second 16 are requested after it,
+        // ahead of the first PV MFMAs.
+        union VOp {
+            short4v p[2];
+            bf16x8 v;
+        };
+        VOp vop[2][DPL];
+        auto load_v = [&](int kh) {
+            const char* src = ldsV + (32 * mt + 16 * kh) * ROWB;
+#pragma unroll
+            for (int jb = 0; jb < DPL; ++jb) {
+                vop[kh][jb].p[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(src + voff[jb][0]));
+                vop[kh][jb].p[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(src + voff[jb][1]));
+            }
+        };
+        if (!(a.ablate & 16)) load_v(0);
+        __builtin_amdgcn_sched_barrier(0);
         // ---- mask + online softmax (Alg. 1: m~, P, l~) ------------------------
         // position of element v is pos0 + 32*mt + 4*h + c with the compile-time
         // c = 8*(v/4) + v%4: visible iff c <= rel.  sm_scale > 0, so the row
@@ -566,7 +595,7 @@ rpa_wide_kernel(KernelArgs a) {
                 mx = fmaxf(mx, s[nt][v]);
             }
             if (a.ablate & 4) mx = 0.f; else
-            mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2;
+            mx = max_across_halves(mx) * a.scale_log2;
             // The reference maximum only moves when the row maximum exceeds it by
             // more than kRescaleGap (log2 units): weights may reach 2^gap, which fp32
             // and bf16 hold exactly as well, and the rescale of O becomes rare.  The
@@ -603,26 +632,18 @@ rpa_wide_kernel(KernelArgs a) {
         // ---- O^T += V^T P^T (Alg. 1: C_o <- ... + P C_v) --------------------------
         // k-step kh covers positions 32*mt + 8*(2*kh + e/4) + 4*h + e%4, e = 0..7,
         // which is the order of the accumulator elements 8*kh .. 8*kh + 7.
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh) {
+        if (!(a.ablate & 16)) {
             __builtin_amdgcn_sched_barrier(0);
-            if (a.ablate & 16) continue;
-            const char* src = ldsV + (32 * mt + 16 * kh) * ROWB;
-            union {
-                short4v p[2];
-                bf16x8 v;
-            } vop[DPL];
-#pragma unroll
-            for (int jb = 0; jb < DPL; ++jb) {
-                vop[jb].p[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(src + voff[jb][0]));
-                vop[jb].p[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(src + voff[jb][1]));
-            }
+            load_v(1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int jb = 0; jb < DPL; ++jb)
+            for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    o[nt][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[jb].v, pop[nt][kh], o[nt][jb], 0, 0, 0);
+                for (int jb = 0; jb < DPL; ++jb)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        o[nt][jb] =
+                            __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[kh][jb].v, pop[nt][kh], o[nt][jb], 0, 0, 0);
         }
     };
     // The two halves run through one copy of the code (a real loop): unrolled

@@ -105,7 +105,8 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     if (opt.variant < RPA_VARIANT_AUTO || opt.variant > RPA_VARIANT_MIXED || opt.kv_chunk < 0 ||
         opt.wide_kv_chunk < 0 || opt.units_per_cu < 0 || opt.narrow_waves < 0 || opt.narrow_waves > kMaxWaves ||
         (opt.narrow_waves > 0 && s.num_kv_heads % opt.narrow_waves != 0) ||
-        (opt.wide_rows != 0 && opt.wide_rows != 128 && opt.wide_rows != 256)) {
+        (opt.wide_rows != 0 && opt.wide_rows != 128 && opt.wide_rows != 256) || opt.wide_order < 0 ||
+        opt.wide_order > 2) {
         err = "bad options";
         return RPA_ERR_INVALID_ARG;
     }
@@ -274,8 +275,21 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     // Wide units longest first: the hardware dispatches workgroups in index order,
     // so the short units fill the gaps at the end.
     auto span = [](const rpa_work_unit& u) { return (int64_t)(u.kv_end - u.kv_begin) * u.n_q; };
-    std::stable_sort(plan.wide.begin(), plan.wide.end(),
-                     [&](const rpa_work_unit& a, const rpa_work_unit& b) { return span(a) > span(b); });
+    if (opt.wide_order != 2) {
+        std::stable_sort(plan.wide.begin(), plan.wide.end(),
+                         [&](const rpa_work_unit& a, const rpa_work_unit& b) { return span(a) > span(b); });
+    } else {
+        // Sequence-major: the tiles of one sequence run at about the same time, so
+        // its K/V stay in L2 while they are re-read; heaviest sequence first and,
+        // inside a sequence, longest tile first.
+        std::vector<int64_t> seq_work(n, 0);
+        for (const rpa_work_unit& u : plan.wide) seq_work[u.seq] += span(u);
+        std::stable_sort(plan.wide.begin(), plan.wide.end(), [&](const rpa_work_unit& a, const rpa_work_unit& b) {
+            if (a.seq != b.seq)
+                return seq_work[a.seq] != seq_work[b.seq] ? seq_work[a.seq] > seq_work[b.seq] : a.seq < b.seq;
+            return span(a) > span(b);
+        });
+    }
 
     plan.stats.num_narrow_bins = (int32_t)plan.bins.size() - 1;
     plan.stats.narrow_waves = waves;

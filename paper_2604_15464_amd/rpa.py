@@ -50,7 +50,7 @@ class PlanStats(C.Structure):
 class Options(C.Structure):
     _fields_ = [("variant", C.c_int32), ("kv_chunk", C.c_int32), ("wide_kv_chunk", C.c_int32),
                 ("narrow_waves", C.c_int32), ("units_per_cu", C.c_int32), ("ablate", C.c_int32),
-                ("wide_rows", C.c_int32), ("reserved", C.c_int32)]
+                ("wide_rows", C.c_int32), ("wide_order", C.c_int32)]
 
 
 class RpaError(RuntimeError):
@@ -171,8 +171,8 @@ class RaggedPagedAttention:
             pass
 
     def set_options(self, variant=VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, narrow_waves=0, units_per_cu=0,
-                    ablate=0, wide_rows=0):
-        opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, units_per_cu, ablate, wide_rows)
+                    ablate=0, wide_rows=0, wide_order=0):
+        opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, units_per_cu, ablate, wide_rows, wide_order)
         rc = self._lib.rpa_set_options(self._ctx, C.byref(opt))
         if rc != RPA_OK:
             raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())
