@@ -131,7 +131,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--copy-bytes", type=int, default=1 << 30,
@@ -205,8 +205,8 @@ def main():
         x3 = W.materialize(wl3, dev, poison=False)
         table3 = torch.from_numpy(wl3.page_table).to(dev)
         ctx3 = rpa.RaggedPagedAttention.for_workload(wl3)
-        steps3 = max(5, min(args.steps, 30))
-        dt3, prof3, _ = time_steps(ctx3, x3, table3, wl3, steps3, max(2, min(args.warmup, 5)))
+        steps3 = args.steps
+        dt3, prof3, _ = time_steps(ctx3, x3, table3, wl3, steps3, args.warmup)
         info3 = ctx3.plan_info()
         ctx3.close()
         flops = wl3.algorithmic_flops()

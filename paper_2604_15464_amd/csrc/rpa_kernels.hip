@@ -469,13 +469,22 @@ rpa_wide_kernel(KernelArgs a) {
     const int kv_begin = u.kv_begin, kv_end = u.kv_end;
     const int ntiles = max(0, (kv_end - kv_begin + KT - 1) / KT);
 
+    // LDS swizzle: 16-byte chunk c of tile row r sits at chunk position c ^ swz(r).
+    // swz permutes the bits of r so that both kinds of operand read touch every
+    // bank once: a K read (ds_read_b128) takes one chunk from 16 consecutive rows,
+    // a transposing V read takes four adjacent chunks from four consecutive rows.
+    // LDS banks repeat every 256 bytes, i.e. every row at D = 128 and every second
+    // row at D = 64, where the row's parity already separates two rows.
+    auto swz = [](int r) {
+        return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
+    };
     const int ld_tok = lane / NC;
     const int ld_chunk = lane % NC;
     uint32_t lane_off[NLD];
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
         const int r = WPOS * wave + i * TPI + ld_tok; // row inside the 64-position tile
-        lane_off[i] = (uint32_t)g * ROWB + (uint32_t)((ld_chunk ^ (r % NC)) * 16);
+        lane_off[i] = (uint32_t)g * ROWB + (uint32_t)((ld_chunk ^ swz(r)) * 16);
     }
 
     auto issue_tile = [&](int t) {
@@ -526,7 +535,7 @@ rpa_wide_kernel(KernelArgs a) {
     // k-step, read 1 positions 8+4h .. 8+4h+3 (the order the weights are in).
     uint32_t koff[KSTEPS], voff[DPL][2];
 #pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk) koff[kk] = n32 * ROWB + (((2 * kk + h) ^ (n32 % NC)) * 16);
+    for (int kk = 0; kk < KSTEPS; ++kk) koff[kk] = n32 * ROWB + (((2 * kk + h) ^ swz(n32)) * 16);
     {
         const int j16 = lane & 15, half16 = (lane >> 4) & 1;
 #pragma unroll
@@ -535,7 +544,7 @@ rpa_wide_kernel(KernelArgs a) {
             for (int rd = 0; rd < 2; ++rd) {
                 const int r = 4 * h + (j16 >> 2) + 8 * rd; // position modulo 16
                 const int chunk = 4 * jb + 2 * half16 + ((j16 & 3) >> 1);
-                voff[jb][rd] = r * ROWB + ((chunk ^ (r % NC)) * 16) + (j16 & 1) * 8;
+                voff[jb][rd] = r * ROWB + ((chunk ^ swz(r)) * 16) + (j16 & 1) * 8;
             }
     }
 

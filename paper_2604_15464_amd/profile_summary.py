@@ -11,6 +11,10 @@ kept under profiles/.
         of this library's kernels, each counter scaled by what it reads for the
         plain copy kernel (rpa_copy_kernel) of known size that
         `bench.py --copy-bytes` runs in the same process.
+
+    python -m paper_2604_15464_amd.profile_summary counters <pmc-dir> <out.txt> "<command>"
+        any other rocprofv3 --pmc run (csv): steady-state mean of every counter
+        for each of this library's kernels.
 """
 from __future__ import annotations
 
@@ -138,9 +142,31 @@ def traffic(fetch_dir: str, write_dir: str, out_json: str, out_txt: str, command
     print(text)
 
 
+def counters(src: str, out: str, command: str) -> None:
+    vals = collections.defaultdict(lambda: collections.defaultdict(list))
+    with open(find(src, "*counter_collection.csv"), newline="") as f:
+        for r in csv.DictReader(f):
+            name = r["Kernel_Name"]
+            if any(k in name for k in KERNELS):
+                vals[short_name(name)][r["Counter_Name"]].append((int(r["Dispatch_Id"]), float(r["Counter_Value"])))
+    lines = [f"command: {command}", "source: rocprofv3 --pmc, csv output; mean over the last half of each kernel's dispatches", ""]
+    for kname, cs in vals.items():
+        lines.append(kname)
+        for cname in sorted(cs):
+            rows = [v for _, v in sorted(cs[cname])]
+            tail = rows[len(rows) // 2:]
+            lines.append(f"  {cname:36s} n={len(rows):3d} mean={sum(tail) / len(tail):18.1f}")
+    text = "\n".join(lines) + "\n"
+    with open(out, "w") as f:
+        f.write(text)
+    print(text)
+
+
 def main(argv):
     if len(argv) >= 5 and argv[1] == "kernels":
         kernels(argv[2], argv[3], argv[4])
+    elif len(argv) >= 5 and argv[1] == "counters":
+        counters(argv[2], argv[3], argv[4])
     elif len(argv) >= 7 and argv[1] == "traffic":
         traffic(argv[2], argv[3], argv[4], argv[5], argv[6])
     else:
