@@ -549,8 +549,7 @@ rpa_wide_kernel(KernelArgs a) {
     }
 
     // One 32-position half of a tile: scores, online-softmax update, PV.
-    auto compute_half = [&](const char* ldsK, const char* ldsV, int pos0, int mt_, auto masked) {
-        constexpr bool MASKED = decltype(masked)::value;
+    auto compute_half = [&](const char* ldsK, const char* ldsV, int pos0, int mt_) {
         const int mt = mt_;
         // ---- S^T = K Q^T (Alg. 1: S <- C_q C_k^T) --------------------------------
         f32x16 s[NT];
@@ -597,12 +596,18 @@ rpa_wide_kernel(KernelArgs a) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             float mx = -INFINITY;
-            const int rel = min(limit[nt], kv_end - 1) - pos0 - 32 * mt - 4 * h;
+            // Only a half that reaches past some row's diagonal or past the end of
+            // the range is masked, under a wave-uniform branch: one copy of the
+            // whole half serves both cases, so the accumulators never change
+            // registers between a masked and an unmasked variant.
+            const int half_last = pos0 + 32 * mt + 31;
+            if (half_last > wave_min_limit || half_last >= kv_end) {
+                const int rel = min(limit[nt], kv_end - 1) - pos0 - 32 * mt - 4 * h;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                if (MASKED) s[nt][v] = (8 * (v / 4) + (v % 4) <= rel) ? s[nt][v] : -INFINITY;
-                mx = fmaxf(mx, s[nt][v]);
+                for (int v = 0; v < 16; ++v) s[nt][v] = (8 * (v / 4) + (v % 4) <= rel) ? s[nt][v] : -INFINITY;
             }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nt][v]);
             if (a.ablate & 4) mx = 0.f; else
             mx = max_across_halves(mx) * a.scale_log2;
             // The reference maximum only moves when the row maximum exceeds it by
@@ -657,10 +662,10 @@ rpa_wide_kernel(KernelArgs a) {
     };
     // The two halves run through one copy of the code (a real loop): unrolled
     // copies cost the register allocator dozens of registers.
-    auto compute_tile = [&](const char* ldsK, const char* ldsV, int pos0, auto masked) {
+    auto compute_tile = [&](const char* ldsK, const char* ldsV, int pos0) {
         const int nh = (pos0 + 32 <= wave_limit) ? 2 : 1;
 #pragma unroll 1
-        for (int mt = 0; mt < nh; ++mt) compute_half(ldsK, ldsV, pos0, mt, masked);
+        for (int mt = 0; mt < nh; ++mt) compute_half(ldsK, ldsV, pos0, mt);
     };
 
     // Ring of NST stages: tile t+NST-1 is requested before tile t is consumed, so
@@ -679,12 +684,8 @@ rpa_wide_kernel(KernelArgs a) {
         const char* ldsK = lds_ptr + (t % NST) * STAGEB;
         const char* ldsV = ldsK + TILEB;
         const int pos0 = kv_begin + t * KT;
-        if (pos0 <= wave_limit && !(a.ablate & 128)) { // tiles wholly above the wave's diagonal are skipped
-            if ((pos0 + KT > kv_end) || (pos0 + KT - 1 > wave_min_limit))
-                compute_tile(ldsK, ldsV, pos0, std::true_type{});
-            else
-                compute_tile(ldsK, ldsV, pos0, std::false_type{});
-        }
+        // tiles wholly above the wave's diagonal are skipped
+        if (pos0 <= wave_limit && !(a.ablate & 128)) compute_tile(ldsK, ldsV, pos0);
         // tile t+1 must have landed; tiles t+2 .. may still be in flight
         const int behind = min(NST - 2, ntiles - 2 - t);
         if (NST >= 4 && behind >= 2) wait_vmcnt<(NST >= 4 ? 2 : 0) * LPT>();
