@@ -147,7 +147,20 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
 
     // ---- regime per sequence (Sec. 3.4) ---------------------------------
     const int64_t narrow_max_q = 2 * (int64_t)tq_narrow; // up to two narrow tiles
-    const int wide_rows = opt.wide_rows > 0 ? opt.wide_rows : kWideRows;
+    // Wide tile height: 256 rows (half the K/V staging traffic per row, no stall
+    // on the loads) when that still gives every CU several workgroups, else 128
+    // rows (twice as many, independent workgroups).
+    int wide_rows = opt.wide_rows;
+    if (wide_rows == 0) {
+        int64_t tiles256 = 0;
+        const int32_t tq256 = wide_q_tokens(hg, 256);
+        for (int32_t r = 0; r < n; ++r) {
+            const int32_t lq = cu[r + 1] - cu[r];
+            const bool wide = opt.variant == RPA_VARIANT_PREFILL || (opt.variant != RPA_VARIANT_DECODE && lq > narrow_max_q);
+            if (lq > 0 && wide) tiles256 += ceil_div(lq, tq256);
+        }
+        wide_rows = tiles256 * s.num_kv_heads >= 4 * (int64_t)std::max(1, num_cus) ? 256 : kWideRows;
+    }
     bool any_narrow = false, any_wide = false;
     std::vector<Tile> tiles;
     int64_t work_wide = 0, wide_tiles = 0;
