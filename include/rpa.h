@@ -122,10 +122,7 @@ typedef struct {
                               the paper's kernel analysis, Sec. 4); outputs are then
                               meaningless, every access stays in bounds.  Bits:
                                 1   narrow kernel: loads and stores only, no math
-                                4   wide kernel: no row maximum (reference fixed at 0)
-                                8   wide kernel: no exponentials / P tile
-                                16  wide kernel: no P.V product
-                                64  wide kernel: no K/V loads and no compute
+                                64  wide kernel: no K/V loads (compute runs on stale LDS)
                                 128 wide kernel: K/V loads only, no compute
                                 256 wide kernel: no output store
                                 512 wide kernel: no cache write                        */

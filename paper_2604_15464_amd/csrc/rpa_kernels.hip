@@ -586,7 +586,7 @@ rpa_wide_kernel(KernelArgs a) {
                 vop[kh][jb].p[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(src + voff[jb][1]));
             }
         };
-        if (!(a.ablate & 16)) load_v(0);
+        load_v(0);
         __builtin_amdgcn_sched_barrier(0);
         // ---- mask + online softmax (Alg. 1: m~, P, l~) ------------------------
         // position of element v is pos0 + 32*mt + 4*h + c with the compile-time
@@ -608,7 +608,6 @@ rpa_wide_kernel(KernelArgs a) {
             }
 #pragma unroll
             for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nt][v]);
-            if (a.ablate & 4) mx = 0.f; else
             mx = max_across_halves(mx) * a.scale_log2;
             // The reference maximum only moves when the row maximum exceeds it by
             // more than kRescaleGap (log2 units): weights may reach 2^gap, which fp32
@@ -618,13 +617,11 @@ rpa_wide_kernel(KernelArgs a) {
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
             const float alpha = fast_exp2(m_run[nt] - m_use);
             float psum = 0.f;
-            if (!(a.ablate & 8)) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const float pv = fast_exp2(__builtin_fmaf(s[nt][v], a.scale_log2, -m_use));
                 s[nt][v] = pv;
                 psum += pv;
-            }
             }
             l_run[nt] = l_run[nt] * alpha + psum;
             m_run[nt] = m_new;
@@ -646,7 +643,7 @@ rpa_wide_kernel(KernelArgs a) {
         // ---- O^T += V^T P^T (Alg. 1: C_o <- ... + P C_v) --------------------------
         // k-step kh covers positions 32*mt + 8*(2*kh + e/4) + 4*h + e%4, e = 0..7,
         // which is the order of the accumulator elements 8*kh .. 8*kh + 7.
-        if (!(a.ablate & 16)) {
+        {
             __builtin_amdgcn_sched_barrier(0);
             load_v(1);
             __builtin_amdgcn_sched_barrier(0);
@@ -660,12 +657,18 @@ rpa_wide_kernel(KernelArgs a) {
                             __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[kh][jb].v, pop[nt][kh], o[nt][jb], 0, 0, 0);
         }
     };
-    // The two halves run through one copy of the code (a real loop): unrolled
-    // copies cost the register allocator dozens of registers.
+    // The eight-wave shape runs the two halves through one copy of the code (a real
+    // loop), the four-wave shape through two copies (the LDS offsets of a half are
+    // then immediates); which is faster was measured, not derived.
     auto compute_tile = [&](const char* ldsK, const char* ldsV, int pos0) {
         const int nh = (pos0 + 32 <= wave_limit) ? 2 : 1;
+        if constexpr (WAVES == 4) {
+            compute_half(ldsK, ldsV, pos0, 0);
+            if (nh == 2) compute_half(ldsK, ldsV, pos0, 1);
+        } else {
 #pragma unroll 1
-        for (int mt = 0; mt < nh; ++mt) compute_half(ldsK, ldsV, pos0, mt);
+            for (int mt = 0; mt < nh; ++mt) compute_half(ldsK, ldsV, pos0, mt);
+        }
     };
 
     // Ring of NST stages: tile t+NST-1 is requested before tile t is consumed, so
