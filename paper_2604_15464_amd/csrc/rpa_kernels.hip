@@ -347,27 +347,31 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     if (!row_ok) {
         // nothing to store for a padding row
     } else if (u.part_row < 0) {
+        // accumulator elements acc[0 .. MT-1][v] of a lane are MT consecutive dims
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
         uint16_t* orow = a.out + ((size_t)(u.q_start + tok_n) * Hq + head) * D;
 #pragma unroll
-        for (int j = 0; j < MT; ++j)
+        for (int v = 0; v < 4; ++v) {
+            const int mrow = 4 * quad + v;
+            const int d0 = 8 * (mrow % NC) + MT * (mrow / NC);
+            uint32_t w[MT / 2];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int mrow = 4 * quad + v;
-                const int dim = 8 * (mrow % NC) + j + MT * (mrow / NC);
-                orow[dim] = (uint16_t)(pack_bf16(acc[j][v] * inv, 0.f) & 0xFFFFu);
-            }
+            for (int jj = 0; jj < MT / 2; ++jj) w[jj] = pack_bf16(acc[2 * jj][v] * inv, acc[2 * jj + 1][v] * inv);
+            if constexpr (MT == 8) *(uint4*)(orow + d0) = make_uint4(w[0], w[1], w[2], w[3]);
+            else *(uint2*)(orow + d0) = make_uint2(w[0], w[1]);
+        }
     } else {
         const size_t prow = (size_t)u.part_row + (size_t)tok_n * Hq + head;
         float* po = a.part_o + prow * D;
 #pragma unroll
-        for (int j = 0; j < MT; ++j)
+        for (int v = 0; v < 4; ++v) {
+            const int mrow = 4 * quad + v;
+            const int d0 = 8 * (mrow % NC) + MT * (mrow / NC);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int mrow = 4 * quad + v;
-                const int dim = 8 * (mrow % NC) + j + MT * (mrow / NC);
-                po[dim] = acc[j][v];
-            }
+            for (int c4 = 0; c4 < MT / 4; ++c4)
+                *(float4*)(po + d0 + 4 * c4) =
+                    make_float4(acc[4 * c4][v], acc[4 * c4 + 1][v], acc[4 * c4 + 2][v], acc[4 * c4 + 3][v]);
+        }
         if (quad == 0) {
             a.part_ml[prow * 2] = m_run;
             a.part_ml[prow * 2 + 1] = l_tot;
