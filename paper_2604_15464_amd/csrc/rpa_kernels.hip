@@ -457,16 +457,8 @@ rpa_wide_kernel(KernelArgs a) {
             wave_limit = max(wave_limit, ctx + u.q_pos0 + min(g_hi, u.n_q - 1));
             wave_min_limit = min(wave_min_limit, ctx + u.q_pos0 + g_lo);
         }
-        const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok[nt] ? tok[nt] : 0)) * Hq + head[nt]) * D;
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (row_ok[nt]) raw = *(const uint4*)(qrow + kk * 16 + h * 8);
-            qreg[nt][kk] = __builtin_bit_cast(bf16x8, raw);
-        }
     }
     if (wave_limit < 0) wave_min_limit = -1;
-    wait_vmcnt<0>();
 
     const uint32_t lds_base = lds_offset(smem);
     const char* lds_ptr = (const char*)smem;
@@ -682,8 +674,19 @@ rpa_wide_kernel(KernelArgs a) {
 #pragma unroll
     for (int s0 = 0; s0 < NST - 1; ++s0)
         if (s0 < ntiles) issue_tile(s0);
-    if (ntiles > 1 && NST > 2) wait_vmcnt<(NST > 2 ? (NST - 2) * LPT : 0)>();
-    else wait_vmcnt<0>();
+    // The Q rows are fetched behind the first tiles so that the two latencies
+    // overlap; loads complete in order, hence waiting for Q waits for those tiles.
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok[nt] ? tok[nt] : 0)) * Hq + head[nt]) * D;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (row_ok[nt]) raw = *(const uint4*)(qrow + kk * 16 + h * 8);
+            qreg[nt][kk] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    wait_vmcnt<0>();
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
