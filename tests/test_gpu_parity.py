@@ -117,6 +117,17 @@ def test_group_sizes(hq, hkv):
         check(wl, res)
 
 
+@pytest.mark.parametrize("ps", [16, 32, 64, 128, 256])
+@pytest.mark.parametrize("d", [64, 128])
+def test_page_sizes(ps, d):
+    """Every supported page size (the paper's own is 256), both head dims, both
+    kernels, with KV splits and a page pool larger than needed."""
+    wl = W.ragged(700 + ps + d, num_seqs=6, hq=8, hkv=2, d=d, ps=ps, max_q=90, max_ctx=700, spare_pages=5)
+    for variant in (rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL):
+        res = run_case(wl, variant=variant, kv_chunk=96, wide_kv_chunk=128)
+        check(wl, res)
+
+
 @pytest.mark.parametrize("idx,scale", [(2, 0.125), (3, 0.125), (4, 0.0625), (5, 0.03125)])
 def test_shrunken_configs(idx, scale):
     wl = W.config(idx, scale=scale)
