@@ -20,7 +20,9 @@ Readings where the paper is silent (each also listed in the design notes):
     promoted to fp64 (Alg. 1 writes S = C_q C_k^T without a scale);
   * "mask S if needed" (Alg. 1) is the causal mask aligned to the end of the
     sequence: query i (0-based in its sequence) sees positions
-    j <= kv_len - q_len + i;
+    j <= kv_len - q_len + i; with causal=False (the paper's non-causal prefill
+    measurements, Sec. 4.2) every query sees all kv_len positions, its own
+    sequence's later tokens included;
   * kv_len counts this call's new tokens (Sec. 4.1: the context length
     "accounts for KV data fetched from both the KV cache and newly projected
     KV");
@@ -110,7 +112,7 @@ def gather_sequence(pages, table_row, l_kv):
 # --------------------------------------------------------------------------
 # step 3: dense causal GQA softmax attention of one sequence, fp64, two-pass
 # --------------------------------------------------------------------------
-def attend_sequence(q, k, v, sm_scale, heads=None):
+def attend_sequence(q, k, v, sm_scale, heads=None, causal=True):
     """q fp64 [l_q, Hq, D]; k, v fp64 [l_kv, Hkv, D] -> fp64 [l_q, Hq, D].
 
     The last l_q positions of k/v are the queries' own tokens."""
@@ -122,7 +124,7 @@ def attend_sequence(q, k, v, sm_scale, heads=None):
     out = np.zeros((l_q, hq, d), dtype=np.float64)
     i = np.arange(l_q)[:, None]
     j = np.arange(l_kv)[None, :]
-    hidden = j > (ctx + i)
+    hidden = (j > (ctx + i)) if causal else np.zeros((l_q, l_kv), dtype=bool)
     for h in (range(hq) if heads is None else heads):
         g = h // hg
         s = scale * (q[:, h, :] @ k[:, g, :].T)
@@ -137,7 +139,7 @@ def attend_sequence(q, k, v, sm_scale, heads=None):
 # the whole call
 # --------------------------------------------------------------------------
 def update_and_attend(q, k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens,
-                      num_seqs, sm_scale, seqs=None, heads=None):
+                      num_seqs, sm_scale, seqs=None, heads=None, causal=True):
     """The oracle of the library call.
 
     All tensor arguments are numpy uint16 arrays of bf16 bit patterns.
@@ -160,7 +162,7 @@ def update_and_attend(q, k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, 
         kk = bf16_to_f64(gather_sequence(k_pages, page_table[r], l_kv))
         vv = bf16_to_f64(gather_sequence(v_pages, page_table[r], l_kv))
         qq = bf16_to_f64(q[q0:q0 + l_q])
-        res = attend_sequence(qq, kk, vv, sm_scale, heads=heads)
+        res = attend_sequence(qq, kk, vv, sm_scale, heads=heads, causal=causal)
         if heads is None:
             out[q0:q0 + l_q] = res
         else:
@@ -202,7 +204,7 @@ def merge_partials(parts):
 # --------------------------------------------------------------------------
 # structurally different brute force, for pinning the above on tiny inputs
 # --------------------------------------------------------------------------
-def dense_bruteforce(q, k, v, sm_scale):
+def dense_bruteforce(q, k, v, sm_scale, causal=True):
     """Pure-Python triple loop over contiguous lists.
 
     q: [l_q][Hq][D], k/v: [l_kv][Hkv][D] nested lists (or arrays) of floats;
@@ -214,7 +216,7 @@ def dense_bruteforce(q, k, v, sm_scale):
     scale = float(np.float32(sm_scale))
     out = [[[0.0] * d for _ in range(hq)] for _ in range(l_q)]
     for i in range(l_q):
-        last = ctx + i
+        last = ctx + i if causal else l_kv - 1
         for h in range(hq):
             g = h // hg
             scores = []

@@ -14,9 +14,13 @@ import test_oracle_pins as pins
 SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "rpa_oracle.py")
 
 MUTATIONS = {
-    "mask_excludes_own_token": ("hidden = j > (ctx + i)", "hidden = j >= (ctx + i)"),
-    "mask_one_too_many": ("hidden = j > (ctx + i)", "hidden = j > (ctx + i + 1)"),
-    "mask_aligned_to_start": ("hidden = j > (ctx + i)", "hidden = j > i"),
+    "mask_excludes_own_token": ("hidden = (j > (ctx + i))", "hidden = (j >= (ctx + i))"),
+    "mask_one_too_many": ("hidden = (j > (ctx + i))", "hidden = (j > (ctx + i + 1))"),
+    "mask_aligned_to_start": ("hidden = (j > (ctx + i))", "hidden = (j > i)"),
+    "noncausal_flag_ignored": ("if causal else np.zeros((l_q, l_kv), dtype=bool)", "if True else None"),
+    "noncausal_hides_new_tokens": ("if causal else np.zeros((l_q, l_kv), dtype=bool)",
+                                   "if causal else (j >= ctx) & (j > ctx + i)"),
+    "causal_flag_not_forwarded": ("heads=heads, causal=causal)", "heads=heads)"),
     "no_mask": ("s[hidden] = -np.inf", "pass"),
     "wrong_gqa_map": ("g = h // hg\n        s = scale", "g = h % hkv\n        s = scale"),
     "missing_scale": ("s = scale * (q[:, h, :] @ k[:, g, :].T)", "s = (q[:, h, :] @ k[:, g, :].T)"),

@@ -408,3 +408,65 @@ def test_config_shapes():
         used = c.page_table[c.page_table >= 0]
         assert len(np.unique(used)) == len(used)
         assert used.max() < c.num_pages
+
+
+# ---- non-causal reading (causal=False: every query sees all kv_len positions) ----
+def test_noncausal_bruteforce_matches():
+    wl = W.ragged(21, num_seqs=4, hq=4, hkv=2, d=8, ps=16, max_q=9, max_ctx=21)
+    x = host_inputs(wl)
+    out, kp, vp = run_oracle(wl, x, causal=False)
+    out_c, kp_c, vp_c = run_oracle(wl, x)
+    # the mask does not change what is written into the cache
+    assert np.array_equal(kp, kp_c) and np.array_equal(vp, vp_c)
+    for r in range(wl.num_seqs):
+        lq = int(wl.q_lens[r])
+        if lq == 0:
+            continue
+        q, k, v = contiguous_kv(wl, x, r)
+        q0 = int(wl.cu_q_lens[r])
+        for i in range(lq):
+            # the brute force sees the whole sequence for every row ...
+            ref = O.dense_bruteforce(q[i:i + 1].tolist(), k.tolist(), v.tolist(), wl.sm_scale, causal=False)
+            assert np.allclose(out[q0 + i], np.asarray(ref[0]), rtol=0, atol=1e-12)
+        # ... and the last row sees the same keys under either mask
+        assert np.allclose(out[q0 + lq - 1], out_c[q0 + lq - 1], rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("lq,ctx", [(1, 40), (33, 0), (17, 29)])
+def test_noncausal_matches_torch_sdpa_float64(lq, ctx):
+    hq, hkv, d, ps = 8, 2, 32, 16
+    wl = W.Workload("s", 9, hq, hkv, d, ps, 6, [lq], [lq + ctx],
+                    W.make_page_table([lq + ctx], ps, 6, np.random.default_rng(4)))
+    x = host_inputs(wl)
+    out, _, _ = run_oracle(wl, x, causal=False)
+    q, k, v = contiguous_kv(wl, x, 0)
+    tq = torch.from_numpy(q).permute(1, 0, 2)
+    tk = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(hq // hkv, dim=0)
+    tv = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(hq // hkv, dim=0)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq[None], tk[None], tv[None], scale=wl.sm_scale)[0]
+    assert np.allclose(out[:lq], ref.permute(1, 0, 2).numpy(), rtol=0, atol=1e-12)
+
+
+def test_noncausal_closed_forms():
+    hq, hkv, d, ps = 2, 1, 8, 16
+    lq, ctx = 6, 11
+    wl = W.Workload("e", 13, hq, hkv, d, ps, 4, [lq], [lq + ctx],
+                    W.make_page_table([lq + ctx], ps, 4, np.random.default_rng(6)))
+    x = host_inputs(wl)
+    # equal keys: every row is the mean of ALL values, later tokens included
+    row = f32_to_bf16_bits(np.random.default_rng(7).standard_normal(d))
+    x["k_pages"][:] = row
+    x["k_new"][:] = row
+    out, _, _ = run_oracle(wl, x, causal=False)
+    _, _, v = contiguous_kv(wl, x, 0)
+    for i in range(lq):
+        assert np.allclose(out[i, 0], v[:, 0].mean(axis=0), atol=1e-13)
+    # equal queries: rows of one head are identical (nothing depends on the row index)
+    x = host_inputs(wl)
+    x["q"][:lq] = x["q"][0]
+    out, _, _ = run_oracle(wl, x, causal=False)
+    for i in range(1, lq):
+        assert np.allclose(out[i], out[0], atol=1e-13)
+    # while under the causal mask they differ (later rows see more keys)
+    out_c, _, _ = run_oracle(wl, x)
+    assert not np.allclose(out_c[0], out_c[lq - 1], atol=1e-6)
