@@ -53,6 +53,10 @@ typedef struct {
     int32_t max_seqs;          /* n: rows of page_table                              */
     int32_t max_pages_per_seq; /* row stride of page_table                           */
     int32_t num_pages;         /* pages in each of k_pages and v_pages               */
+    int32_t non_causal;        /* 0: causal mask aligned to the end of the sequence
+                                  (the default; Alg. 1 "mask S if needed"); 1: no mask,
+                                  every query token sees all kv_len positions (the
+                                  paper's non-causal prefill measurements, Sec. 4.2)  */
 } rpa_shape;
 
 /* Kernel variants (Sec. 3.4 "Distribution-aware Compilation": decode-only,

@@ -344,6 +344,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     a.wide_tq_log2 = __builtin_ctz((unsigned)wide_q_tokens(a.hg, plan.stats.wide_rows));
     a.scale_log2 = sm_scale * 1.4426950408889634f;
     a.ablate = c->opt.ablate;
+    a.causal = c->shape.non_causal ? 0 : 1;
 
     const rpa_work_unit* dev_units = (const rpa_work_unit*)slot.dev;
     ProfEvents* pe = (c->prof_on && c->prof_count < kProfCalls) ? &c->prof[c->prof_count] : nullptr;

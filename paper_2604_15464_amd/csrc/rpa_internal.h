@@ -72,6 +72,7 @@ struct KernelArgs {
     int32_t wide_tq_log2; // log2 of the wide tile's token count
     float scale_log2; // sm_scale * log2(e)
     int32_t ablate;   // measurement switches (rpa_options.ablate)
+    int32_t causal;   // 0: no mask beyond the end of the sequence
 };
 
 // Launchers (rpa_kernels.hip).  Return a hipError_t value as int.  `ev` is either

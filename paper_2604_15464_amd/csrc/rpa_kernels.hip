@@ -174,7 +174,8 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 
     // ---- query operand ---------------------------------------------------------
     const bool row_ok = tok_n < u.n_q;
-    const int limit_n = row_ok ? ctx + u.q_pos0 + tok_n : -1; // last visible KV position
+    // last visible KV position of the row (without the causal mask: no limit but kv_end)
+    const int limit_n = row_ok ? (a.causal ? ctx + u.q_pos0 + tok_n : 0x3fffffff) : -1;
     bf16x8 qreg[KSTEPS];
     {
         const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok ? tok_n : 0)) * Hq + g * hg + hh) * D;
@@ -468,14 +469,14 @@ rpa_wide_kernel(KernelArgs a) {
         tok[nt] = rho & tq_mask;
         head[nt] = g * hg + hh;
         row_ok[nt] = tok[nt] < u.n_q;
-        limit[nt] = row_ok[nt] ? ctx + u.q_pos0 + tok[nt] : -1;
+        limit[nt] = row_ok[nt] ? (a.causal ? ctx + u.q_pos0 + tok[nt] : 0x3fffffff) : -1;
         // the group's 32 rows are 32 consecutive tokens of one head, or whole token
         // ranges of several heads when the tile has fewer than 32 tokens
         const int g_lo = (1 << tq_log2) >= 32 ? ((32 * (NT * wave + nt)) & tq_mask) : 0;
         const int g_hi = (1 << tq_log2) >= 32 ? g_lo + 31 : tq_mask;
         if (g_lo < u.n_q) {
-            wave_limit = max(wave_limit, ctx + u.q_pos0 + min(g_hi, u.n_q - 1));
-            wave_min_limit = min(wave_min_limit, ctx + u.q_pos0 + g_lo);
+            wave_limit = max(wave_limit, a.causal ? ctx + u.q_pos0 + min(g_hi, u.n_q - 1) : 0x3fffffff);
+            wave_min_limit = min(wave_min_limit, a.causal ? ctx + u.q_pos0 + g_lo : 0x3fffffff);
         }
     }
     if (wave_limit < 0) wave_min_limit = -1;

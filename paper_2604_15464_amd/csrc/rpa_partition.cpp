@@ -178,7 +178,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         const int32_t tq = wide ? wide_q_tokens(hg, wide_rows) : tq_narrow;
         for (int32_t i0 = 0; i0 < lq; i0 += tq) {
             Tile t{r, i0, std::min(tq, lq - i0), 0, ctx, cu[r], wide};
-            t.kv_hi = ctx + i0 + t.n_q;
+            t.kv_hi = s.non_causal ? kv[r] : ctx + i0 + t.n_q; // last position any row of the tile sees, + 1
             tiles.push_back(t);
             if (wide) {
                 work_wide += t.kv_hi;

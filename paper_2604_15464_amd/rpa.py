@@ -23,7 +23,7 @@ VARIANT_NAMES = {0: "auto", 1: "decode", 2: "prefill", 3: "mixed"}
 class Shape(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "num_q_heads", "num_kv_heads", "head_dim", "page_size", "max_tokens", "max_seqs",
-        "max_pages_per_seq", "num_pages")]
+        "max_pages_per_seq", "num_pages", "non_causal")]
 
 
 class WorkUnit(C.Structure):
@@ -108,9 +108,9 @@ def _i32(a):
 
 
 def make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs, max_pages_per_seq,
-               num_pages) -> Shape:
+               num_pages, causal=True) -> Shape:
     return Shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs, max_pages_per_seq,
-                 num_pages)
+                 num_pages, 0 if causal else 1)
 
 
 def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUTO, kv_chunk=0,
@@ -143,10 +143,10 @@ class RaggedPagedAttention:
     """One context = one static shape on one GPU."""
 
     def __init__(self, num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs,
-                 max_pages_per_seq, num_pages, device=0):
+                 max_pages_per_seq, num_pages, device=0, causal=True):
         self._lib = lib()
         self.shape = make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs,
-                                max_pages_per_seq, num_pages)
+                                max_pages_per_seq, num_pages, causal)
         self._ctx = C.c_void_p()
         rc = self._lib.rpa_create(C.byref(self._ctx), C.byref(self.shape), int(device))
         if rc != RPA_OK:
@@ -154,10 +154,10 @@ class RaggedPagedAttention:
         self.device = int(device)
 
     @classmethod
-    def for_workload(cls, wl, max_tokens=None, max_seqs=None, device=0):
+    def for_workload(cls, wl, max_tokens=None, max_seqs=None, device=0, causal=True):
         return cls(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size,
                    max(1, max_tokens or wl.num_tokens), max(1, max_seqs or wl.num_seqs),
-                   wl.max_pages_per_seq, wl.num_pages, device)
+                   wl.max_pages_per_seq, wl.num_pages, device, causal)
 
     def close(self):
         if getattr(self, "_ctx", None) is not None and self._ctx.value:

@@ -7,7 +7,8 @@ Sec. 4.2 causal prefill table): uniform lengths, Llama-3-8B attention shape
 Decode: n = 128 sequences, q_len 1, identical context length 512 ... 32768;
 reports the step latency and the algorithmic GB/s (the paper's byte formula
 with decimal units).  Prefill: one sequence of 512 ... 32768 tokens, causal,
-no cached context; reports latency and TFLOP/s with exact causal FLOPs.
+no cached context; reports latency and TFLOP/s with exact causal FLOPs,
+then the same lengths without the causal mask (4*s*s*Hq*D FLOPs).
 One JSON line per point on stdout, a table on stderr.  Synthetic N(0,1) data.
 """
 from __future__ import annotations
@@ -34,13 +35,13 @@ def uniform_workload(name, n, q_len, kv_len, page_size=256, seed=11):
                       W.make_page_table(kv, page_size, pages, rng))
 
 
-def time_workload(wl, steps, warmup):
+def time_workload(wl, steps, warmup, causal=True):
     import torch
 
     dev = torch.device("cuda:0")
     x = W.materialize(wl, dev, poison=False)
     table = torch.from_numpy(wl.page_table).to(dev)
-    ctx = rpa.RaggedPagedAttention.for_workload(wl)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl, causal=causal)
     out = torch.empty_like(x["q"])
 
     def call():
@@ -100,6 +101,19 @@ def main():
             tf = wl.algorithmic_flops() / dt / 1e12
             rec = {"sweep": "prefill_causal", "n": 1, "seq_len": s, "page_size": 256, "latency_us": round(dt * 1e6, 1),
                    "TFLOPs": round(tf, 1), "pct_of_2500": round(tf / 25.0, 2),
+                   "wide_kernel_us": round(k["wide_ms"] * 1e3, 1), "combine_kernel_us": round(k["combine_ms"] * 1e3, 1),
+                   "units": info["num_wide_units"], "wide_rows": info["wide_rows"], "max_splits": info["max_splits"]}
+            rows.append(rec)
+            print(json.dumps(rec), flush=True)
+    if args.prefill or both:
+        for s in LENGTHS:
+            if s > args.max_len:
+                break
+            wl = uniform_workload(f"prefill_1x{s}", 1, s, s)
+            dt, k, info = time_workload(wl, args.steps, args.warmup, causal=False)
+            tf = 4.0 * wl.num_q_heads * wl.head_dim * s * s / dt / 1e12  # every (query, key) pair is visible
+            rec = {"sweep": "prefill_noncausal", "n": 1, "seq_len": s, "page_size": 256,
+                   "latency_us": round(dt * 1e6, 1), "TFLOPs": round(tf, 1), "pct_of_2500": round(tf / 25.0, 2),
                    "wide_kernel_us": round(k["wide_ms"] * 1e3, 1), "combine_kernel_us": round(k["combine_ms"] * 1e3, 1),
                    "units": info["num_wide_units"], "wide_rows": info["wide_rows"], "max_splits": info["max_splits"]}
             rows.append(rec)

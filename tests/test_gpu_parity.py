@@ -21,7 +21,7 @@ def to_f64(t):
 
 
 def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=True, pad_tokens=0,
-             pad_seqs=0, seqs=None, calls=1, narrow_waves=0, units_per_cu=0, wide_rows=0):
+             pad_seqs=0, seqs=None, calls=1, narrow_waves=0, units_per_cu=0, wide_rows=0, causal=True):
     """Run the HIP path and the oracle on the workload; returns a dict of results."""
     dev = torch.device("cuda:0")
     max_tokens = wl.num_tokens + pad_tokens
@@ -31,7 +31,8 @@ def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=T
     table = np.full((max(1, max_seqs), wl.max_pages_per_seq), -1, dtype=np.int32)
     table[:wl.num_seqs] = wl.page_table
     table_dev = torch.from_numpy(table).to(dev)
-    ctx = rpa.RaggedPagedAttention.for_workload(wl, max_tokens=max(1, max_tokens), max_seqs=max(1, max_seqs))
+    ctx = rpa.RaggedPagedAttention.for_workload(wl, max_tokens=max(1, max_tokens), max_seqs=max(1, max_seqs),
+                                                causal=causal)
     ctx.set_options(variant=variant, kv_chunk=kv_chunk, wide_kv_chunk=wide_kv_chunk, narrow_waves=narrow_waves,
                     units_per_cu=units_per_cu, wide_rows=wide_rows)
     out = torch.full_like(x["q"], float("nan"))
@@ -44,7 +45,7 @@ def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=T
     ctx.close()
     ref, kp, vp = O.update_and_attend(host["q"], host["k_new"], host["v_new"], host["k_pages"],
                                       host["v_pages"], wl.page_table, wl.cu_q_lens, wl.kv_lens,
-                                      wl.num_seqs, wl.sm_scale, seqs=seqs)
+                                      wl.num_seqs, wl.sm_scale, seqs=seqs, causal=causal)
     return {"out": out, "ref": ref, "kp": W.bits(x["k_pages"]), "vp": W.bits(x["v_pages"]), "kp_ref": kp,
             "vp_ref": vp, "info": info, "sentinel": sentinel, "x": x}
 
@@ -115,6 +116,26 @@ def test_group_sizes(hq, hkv):
     for variant in (rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL):
         res = run_case(wl, variant=variant, kv_chunk=64, wide_kv_chunk=64)
         check(wl, res)
+
+
+@pytest.mark.parametrize("variant", [rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL])
+@pytest.mark.parametrize("shape", [(4, 2, 64), (32, 8, 128), (8, 8, 128)])
+@pytest.mark.parametrize("wide_rows", [128, 256])
+def test_without_causal_mask(variant, shape, wide_rows):
+    """causal=False: every query token sees its whole sequence, later new tokens
+    included; cache update unchanged.  Both kernels, split and unsplit."""
+    hq, hkv, d = shape
+    wl = W.ragged(900 + hq + d, num_seqs=7, hq=hq, hkv=hkv, d=d, ps=16, max_q=150, max_ctx=400)
+    for chunk in (0, 64):
+        res = run_case(wl, variant=variant, kv_chunk=chunk, wide_kv_chunk=chunk, wide_rows=wide_rows, causal=False)
+        check(wl, res)
+
+
+def test_full_prefill_without_causal_mask():
+    """Config 3 at full size without the mask (sampled sequences)."""
+    wl = W.config(3)
+    res = run_case(wl, poison=False, seqs=[0, 5], causal=False)
+    check(wl, res, seqs=[0, 5])
 
 
 @pytest.mark.parametrize("ps", [16, 32, 64, 128, 256])

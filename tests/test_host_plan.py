@@ -14,10 +14,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 F = {n: i for i, n in enumerate(rpa.UNIT_FIELDS)}
 
 
-def shape_of(wl, max_tokens=None, max_seqs=None):
+def shape_of(wl, max_tokens=None, max_seqs=None, causal=True):
     return rpa.make_shape(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size,
                           max_tokens or max(1, wl.num_tokens), max_seqs or max(1, wl.num_seqs),
-                          wl.max_pages_per_seq, wl.num_pages)
+                          wl.max_pages_per_seq, wl.num_pages, causal)
 
 
 def test_library_exports_every_declared_symbol():
@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(l, name), name
 
 
-def check_plan(wl, units, items, stats, narrow_tq, wide_tq=None):
+def check_plan(wl, units, items, stats, narrow_tq, wide_tq=None, causal=True):
     wide_tq = wide_tq or stats["wide_rows"] // (wl.num_q_heads // wl.num_kv_heads)
     cu = wl.cu_q_lens
     # per token: covered KV positions and writers
@@ -46,7 +46,7 @@ def check_plan(wl, units, items, stats, narrow_tq, wide_tq=None):
         assert ctx == wl.kv_lens[seq] - wl.q_lens[seq]
         assert 1 <= n_q <= (wide_tq if wide else narrow_tq)
         assert q_pos0 + n_q <= wl.q_lens[seq]
-        assert 0 <= b < e <= ctx + q_pos0 + n_q
+        assert 0 <= b < e <= (ctx + q_pos0 + n_q if causal else wl.kv_lens[seq])
         assert b % (64 if wide else 16) == 0
         tile_units.setdefault((seq, q_pos0), []).append((b, e, part, flags, n_q))
         if flags & 1:
@@ -56,7 +56,7 @@ def check_plan(wl, units, items, stats, narrow_tq, wide_tq=None):
     for (seq, q_pos0), lst in tile_units.items():
         lst.sort()
         n_q = lst[0][4]
-        kv_hi = wl.kv_lens[seq] - wl.q_lens[seq] + q_pos0 + n_q
+        kv_hi = wl.kv_lens[seq] - wl.q_lens[seq] + q_pos0 + n_q if causal else wl.kv_lens[seq]
         # ranges tile [0, kv_hi) without gap or overlap
         assert lst[0][0] == 0 and lst[-1][1] == kv_hi
         for (b0, e0, *_), (b1, *_rest) in zip(lst[:-1], lst[1:]):
@@ -96,6 +96,15 @@ def test_plan_covers_configs(idx, variant):
         assert stats["num_wide_units"] == 0 and stats["variant"] == rpa.VARIANT_DECODE
     if variant == rpa.VARIANT_PREFILL:
         assert stats["num_narrow_units"] == 0 and stats["variant"] == rpa.VARIANT_PREFILL
+
+
+@pytest.mark.parametrize("idx", [1, 3, 4])
+@pytest.mark.parametrize("variant", [rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL])
+def test_plan_without_causal_mask_covers_whole_sequences(idx, variant):
+    wl = W.config(idx) if idx == 1 else W.config(idx, scale=0.25)
+    units, items, stats = rpa.plan_host(shape_of(wl, causal=False), wl.cu_q_lens, wl.kv_lens, variant=variant,
+                                        kv_chunk=64, wide_kv_chunk=64)
+    check_plan(wl, units, items, stats, narrow_tq=16 // (wl.num_q_heads // wl.num_kv_heads), causal=False)
 
 
 def test_auto_variant_follows_distribution():
