@@ -132,7 +132,8 @@ typedef struct {
                                 512 wide kernel: no cache write                        */
     int32_t wide_rows;     /* query rows per wide tile: 256 (eight waves, one workgroup
                               per CU) or 128 (four waves, two workgroups per CU);
-                              0 = default                                              */
+                              0 = chosen per call: 256 if that leaves every CU at
+                              least four workgroups, else 128                          */
     int32_t wide_order;    /* launch order of the wide units: 1 (and 0 = default)
                               longest tile first overall; 2 = by sequence, heaviest
                               sequence first, longest tile first inside a sequence    */

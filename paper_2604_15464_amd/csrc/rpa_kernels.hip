@@ -405,13 +405,15 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 
 
 // ---------------------------------------------------------------------------
-// Wide kernel: query tile of 256 rows = (256 / h_g) tokens x the h_g heads of one
-// KV head (the paper's stacking of a group's heads against one K/V operand,
-// Sec. 3.1.2).  8 / NT waves, each owning NT groups of 32 rows; 32x32x16 MFMA.
-// K/V tiles of 64 positions are staged once per workgroup in LDS by asynchronous
-// 16-byte loads (every wave brings its share) in a ring of kWideStages, one
-// barrier per tile.  With NT = 2 a K or V operand read from LDS feeds two
-// MFMAs.  Used for prefill and chunked prefill; MFMA-bound.
+// Wide kernel: query tile of 32 * WAVES rows = (32 * WAVES / h_g) tokens x the h_g
+// heads of one KV head (the paper's stacking of a group's heads against one K/V
+// operand, Sec. 3.1.2).  Every wave owns 32 rows; 32x32x16 MFMA.  Two shapes are
+// built: 8 waves (256 rows, one workgroup per CU, ring of 3 stages) and 4 waves
+// (128 rows, two independent workgroups per CU, ring of 2 stages).  K/V tiles of
+// 64 positions are staged once per workgroup in LDS by asynchronous 16-byte
+// loads (every wave brings its share), one barrier per tile.  Used for prefill
+// and chunked prefill; bound by the MFMA and vector pipes together (they do not
+// overlap on this part).
 // ---------------------------------------------------------------------------
 template <int D, int WAVES, int NST>
 __global__ void __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2)))
