@@ -47,7 +47,7 @@ typedef enum {
 typedef struct {
     int32_t num_q_heads;       /* h_q                                                */
     int32_t num_kv_heads;      /* h_kv; num_q_heads must be a multiple of it        */
-    int32_t head_dim;          /* d_k: 64 or 128                                     */
+    int32_t head_dim;          /* d_k: 64, 128 or 256                                */
     int32_t page_size;         /* tokens per cache page: a power of two >= 16        */
     int32_t max_tokens;        /* s: rows of q / k_new / v_new / out                 */
     int32_t max_seqs;          /* n: rows of page_table                              */
@@ -119,7 +119,8 @@ typedef struct {
     int32_t kv_chunk;  /* cap on KV positions per narrow unit (rounded up to 16); 0 = none */
     int32_t wide_kv_chunk; /* KV positions per wide unit (rounded up to 64); 0 = auto */
     int32_t narrow_waves;  /* waves (= KV heads) per narrow workgroup: a divisor of
-                              num_kv_heads, at most 8; 0 = auto                       */
+                              num_kv_heads, at most 8 (4 at head_dim 256: every wave
+                              keeps head_dim * 128 bytes of LDS); 0 = auto            */
     int32_t units_per_cu;  /* narrow bins per resident workgroup slot (1 = exactly one
                               wave of workgroups); 0 = default                        */
     int32_t ablate;        /* measurement only (ablation by leaving a stage out, as in
@@ -133,7 +134,8 @@ typedef struct {
     int32_t wide_rows;     /* query rows per wide tile: 256 (eight waves, one workgroup
                               per CU) or 128 (four waves, two workgroups per CU);
                               0 = chosen per call: 256 if that leaves every CU at
-                              least four workgroups, else 128                          */
+                              least four workgroups, else 128.  head_dim 256 has the
+                              128-row shape only (one workgroup per CU) and rejects 256 */
     int32_t wide_order;    /* launch order of the wide units: 1 (and 0 = default)
                               longest tile first overall; 2 = by sequence, heaviest
                               sequence first, longest tile first inside a sequence    */

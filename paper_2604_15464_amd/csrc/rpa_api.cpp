@@ -170,7 +170,8 @@ extern "C" int rpa_set_options(rpa_ctx* c, const rpa_options* opt) {
     if (o.variant < RPA_VARIANT_AUTO || o.variant > RPA_VARIANT_MIXED || o.kv_chunk < 0 || o.wide_kv_chunk < 0 ||
         o.units_per_cu < 0 || o.narrow_waves < 0 || o.narrow_waves > kMaxWaves ||
         (o.narrow_waves > 0 && c->shape.num_kv_heads % o.narrow_waves != 0) ||
-        (o.wide_rows != 0 && o.wide_rows != 128 && o.wide_rows != 256) || o.wide_order < 0 || o.wide_order > 2)
+        (o.wide_rows != 0 && o.wide_rows != 128 && o.wide_rows != 256) || o.wide_order < 0 || o.wide_order > 2 ||
+        !options_fit_shape(c->shape, o))
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: bad value");
     c->opt = o;
     return RPA_OK;

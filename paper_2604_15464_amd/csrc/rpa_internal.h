@@ -43,17 +43,26 @@ inline int narrow_q_tokens(int hg) { return (hg >= 1 && hg <= kNarrowRows && kNa
 // Query tokens per wide tile.
 inline int wide_q_tokens(int hg, int rows) { return rows / hg; }
 
+// LDS ring bytes of one narrow wave: stages x (K tile + V tile).
+inline int narrow_lds_per_wave(int head_dim) { return kNarrowStages * 2 * kNarrowKvTile * head_dim * 2; }
+
 // Default waves per narrow workgroup: the largest divisor of num_kv_heads not
-// above 4 (two workgroups of 64 KB LDS per compute unit at head_dim 128).
-inline int narrow_waves(int hkv) {
+// above 4 (two workgroups of 64 KB LDS per compute unit at head_dim 128, one
+// of 128 KB at head_dim 256).
+inline int narrow_waves(int hkv, int head_dim) {
     int w = 1;
     for (int d = 1; d <= 4; ++d)
-        if (hkv % d == 0) w = d;
+        if (hkv % d == 0 && d * narrow_lds_per_wave(head_dim) <= kLdsBytesPerCu) w = d;
     return w;
 }
 
-// LDS ring bytes of one narrow wave: stages x (K tile + V tile).
-inline int narrow_lds_per_wave(int head_dim) { return kNarrowStages * 2 * kNarrowKvTile * head_dim * 2; }
+// Launch-shape options the kernels have no build for at this shape: a narrow
+// workgroup whose rings exceed the LDS, 256-row wide tiles at head_dim 256.
+inline bool options_fit_shape(const rpa_shape& s, const rpa_options& o) {
+    if (o.narrow_waves > 0 && o.narrow_waves * narrow_lds_per_wave(s.head_dim) > kLdsBytesPerCu) return false;
+    if (s.head_dim > 128 && o.wide_rows == 256) return false;
+    return true;
+}
 
 struct KernelArgs {
     const uint16_t* q;

@@ -124,6 +124,8 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     constexpr int LOADS_PER_STAGE = 2 * NLD;
     constexpr int KSTEPS = D / 32;              // MFMA 16x16x32 steps over head_dim
     constexpr int MT = D / 16;                  // 16-dim output tiles
+    constexpr int VG = D > 128 ? D / 128 : 1;   // 128-dim groups of a V row (16 chunks each)
+    constexpr int JW = MT / VG;                 // output tiles per group
 
     extern __shared__ uint4 smem[];
 
@@ -303,42 +305,46 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 
         // ---- O^T += V^T P^T (Alg. 1: C_o <- ... + P C_v) --------------------------
         // lane (m = lane%16, quad) reads 16 bytes (8 dims) of its four tokens and
-        // transposes them in registers into eight 4-token operands.
-        uint32_t vr[4][4];
-        const int ch = n % NC;
+        // transposes them in registers into eight 4-token operands; a row wider
+        // than 128 dims is taken in groups of 16 chunks.
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-            const int tok = 4 * quad + tt;
-            const uint4 raw = *(const uint4*)(ldsV + tok * ROWB + ((ch ^ (tok % NC)) * 16));
-            vr[tt][0] = raw.x;
-            vr[tt][1] = raw.y;
-            vr[tt][2] = raw.z;
-            vr[tt][3] = raw.w;
-        }
-        short4v vop[8];
+        for (int vg = 0; vg < VG; ++vg) {
+            uint32_t vr[4][4];
+            const int ch = 16 * vg + n % NC;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-            union {
-                uint32_t w[2];
-                short4v v;
-            } o;
-            o.w[0] = __builtin_amdgcn_perm(vr[1][j / 2], vr[0][j / 2], sel);
-            o.w[1] = __builtin_amdgcn_perm(vr[3][j / 2], vr[2][j / 2], sel);
-            vop[j] = o.v;
-        }
-        if constexpr (D == 128) {
+            for (int tt = 0; tt < 4; ++tt) {
+                const int tok = 4 * quad + tt;
+                const uint4 raw = *(const uint4*)(ldsV + tok * ROWB + ((ch ^ (tok % NC)) * 16));
+                vr[tt][0] = raw.x;
+                vr[tt][1] = raw.y;
+                vr[tt][2] = raw.z;
+                vr[tt][3] = raw.w;
+            }
+            short4v vop[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[j], pop.v, acc[j], 0, 0, 0);
-        } else {
-            const bool upper = n >= NC; // lanes 8..15 serve dims j+4 of their chunk
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                union {
+                    uint32_t w[2];
+                    short4v v;
+                } o;
+                o.w[0] = __builtin_amdgcn_perm(vr[1][j / 2], vr[0][j / 2], sel);
+                o.w[1] = __builtin_amdgcn_perm(vr[3][j / 2], vr[2][j / 2], sel);
+                vop[j] = o.v;
+            }
+            if constexpr (D >= 128) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                short4v pick;
+                for (int j = 0; j < 8; ++j)
+                    acc[8 * vg + j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[j], pop.v, acc[8 * vg + j], 0, 0, 0);
+            } else {
+                const bool upper = n >= NC; // lanes 8..15 serve dims j+4 of their chunk
 #pragma unroll
-                for (int e = 0; e < 4; ++e) pick[e] = upper ? vop[j + 4][e] : vop[j][e];
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pick, pop.v, acc[j], 0, 0, 0);
+                for (int j = 0; j < 4; ++j) {
+                    short4v pick;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) pick[e] = upper ? vop[j + 4][e] : vop[j][e];
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pick, pop.v, acc[j], 0, 0, 0);
+                }
             }
         }
     }
@@ -368,31 +374,37 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     if (!row_ok) {
         // nothing to store for a padding row
     } else if (u.part_row < 0) {
-        // accumulator elements acc[0 .. MT-1][v] of a lane are MT consecutive dims
+        // accumulator elements acc[JW*vg .. JW*vg + JW-1][v] of a lane are JW consecutive dims
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
         uint16_t* orow = a.out + ((size_t)(u.q_start + tok_n) * Hq + head) * D;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int mrow = 4 * quad + v;
-            const int d0 = 8 * (mrow % NC) + MT * (mrow / NC);
-            uint32_t w[MT / 2];
+        for (int v = 0; v < 4; ++v)
 #pragma unroll
-            for (int jj = 0; jj < MT / 2; ++jj) w[jj] = pack_bf16(acc[2 * jj][v] * inv, acc[2 * jj + 1][v] * inv);
-            if constexpr (MT == 8) *(uint4*)(orow + d0) = make_uint4(w[0], w[1], w[2], w[3]);
-            else *(uint2*)(orow + d0) = make_uint2(w[0], w[1]);
-        }
+            for (int vg = 0; vg < VG; ++vg) {
+                const int mrow = 4 * quad + v;
+                const int d0 = 128 * vg + 8 * (mrow % NC) + JW * (mrow / NC);
+                uint32_t w[JW / 2];
+#pragma unroll
+                for (int jj = 0; jj < JW / 2; ++jj)
+                    w[jj] = pack_bf16(acc[JW * vg + 2 * jj][v] * inv, acc[JW * vg + 2 * jj + 1][v] * inv);
+                if constexpr (JW == 8) *(uint4*)(orow + d0) = make_uint4(w[0], w[1], w[2], w[3]);
+                else *(uint2*)(orow + d0) = make_uint2(w[0], w[1]);
+            }
     } else {
         const size_t prow = (size_t)u.part_row + (size_t)tok_n * Hq + head;
         float* po = a.part_o + prow * D;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int mrow = 4 * quad + v;
-            const int d0 = 8 * (mrow % NC) + MT * (mrow / NC);
+        for (int v = 0; v < 4; ++v)
 #pragma unroll
-            for (int c4 = 0; c4 < MT / 4; ++c4)
-                *(float4*)(po + d0 + 4 * c4) =
-                    make_float4(acc[4 * c4][v], acc[4 * c4 + 1][v], acc[4 * c4 + 2][v], acc[4 * c4 + 3][v]);
-        }
+            for (int vg = 0; vg < VG; ++vg) {
+                const int mrow = 4 * quad + v;
+                const int d0 = 128 * vg + 8 * (mrow % NC) + JW * (mrow / NC);
+#pragma unroll
+                for (int c4 = 0; c4 < JW / 4; ++c4)
+                    *(float4*)(po + d0 + 4 * c4) =
+                        make_float4(acc[JW * vg + 4 * c4][v], acc[JW * vg + 4 * c4 + 1][v], acc[JW * vg + 4 * c4 + 2][v],
+                                    acc[JW * vg + 4 * c4 + 3][v]);
+            }
         if (quad == 0) {
             a.part_ml[prow * 2] = m_run;
             a.part_ml[prow * 2 + 1] = l_tot;
@@ -416,7 +428,7 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 // overlap on this part).
 // ---------------------------------------------------------------------------
 template <int D, int WAVES, int NST>
-__global__ void __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ void __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(D > 128 ? 1 : 2)))
 rpa_wide_kernel(KernelArgs a) {
     constexpr int NT = 1; // 32-row groups per wave
     constexpr int ROWB = D * 2;
@@ -492,10 +504,11 @@ rpa_wide_kernel(KernelArgs a) {
     // swz permutes the bits of r so that both kinds of operand read touch every
     // bank once: a K read (ds_read_b128) takes one chunk from 16 consecutive rows,
     // a transposing V read takes four adjacent chunks from four consecutive rows.
-    // LDS banks repeat every 256 bytes, i.e. every row at D = 128 and every second
+    // LDS banks repeat every 256 bytes, i.e. every row at D = 128 (every half row at
+    // D = 256, where the swizzle leaves the chunk's top bit alone) and every second
     // row at D = 64, where the row's parity already separates two rows.
     auto swz = [](int r) {
-        return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
+        return D >= 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
     };
     const int ld_tok = lane / NC;
     const int ld_chunk = lane % NC;
@@ -568,7 +581,7 @@ rpa_wide_kernel(KernelArgs a) {
     }
 
     // One 32-position half of a tile: scores, online-softmax update, PV.
-    auto compute_half = [&](const char* ldsK, const char* ldsV, int pos0, int mt_) {
+    auto compute_half = [&](const char* ldsK, const char* ldsV, int pos0, int mt_) __attribute__((always_inline)) {
         const int mt = mt_;
         // ---- S^T = K Q^T (Alg. 1: S <- C_q C_k^T) --------------------------------
         f32x16 s[NT];
@@ -578,17 +591,22 @@ rpa_wide_kernel(KernelArgs a) {
             for (int v = 0; v < 16; ++v) s[nt][v] = 0.f;
         // all K operands of the half are requested before the first MFMA, so the
         // LDS latency is paid once per half, not once per MFMA pair
-        bf16x8 kop[KSTEPS];
+        // (in batches of eight: 32 registers)
+        constexpr int KB = KSTEPS < 8 ? KSTEPS : 8;
 #pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) kop[kk] = *(const bf16x8*)(ldsK + koff[kk] + mt * 32 * ROWB);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int k0 = 0; k0 < KSTEPS; k0 += KB) {
+            bf16x8 kop[KB];
 #pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
+            for (int kk = 0; kk < KB; ++kk) kop[kk] = *(const bf16x8*)(ldsK + koff[k0 + kk] + mt * 32 * ROWB);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kk], qreg[nt][kk], s[nt], 0, 0, 0);
+            for (int kk = 0; kk < KB; ++kk) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kk], qreg[nt][k0 + kk], s[nt], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
         // The V^T fragments of the half's first 16 positions are requested now and
         // arrive under the softmax; those of the second 16 are requested after it,
         // ahead of the first PV MFMAs.
@@ -645,8 +663,25 @@ rpa_wide_kernel(KernelArgs a) {
             l_run[nt] = l_run[nt] * alpha + psum;
             m_run[nt] = m_new;
             if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) { // skip when no row's maximum moved
+                if constexpr (D > 128) {
+                    // The accumulator lives in AGPRs at this size.  The multiply goes
+                    // through explicit register moves so that the compiler keeps it
+                    // there on every path instead of copying all of it to VGPRs and
+                    // back around the MFMAs of every half for the sake of this rare one.
 #pragma unroll
-                for (int j = 0; j < DPL; ++j) o[nt][j] *= alpha;
+                    for (int j = 0; j < DPL; ++j)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            float t, r;
+                            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(o[nt][j][v]));
+                            t *= alpha;
+                            asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(r) : "v"(t));
+                            o[nt][j][v] = r;
+                        }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < DPL; ++j) o[nt][j] *= alpha;
+                }
             }
 #pragma unroll
             for (int kh = 0; kh < 2; ++kh) {
@@ -890,6 +925,13 @@ int kernels_init(int device, std::string& err) {
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 4, kWideStagesHalf>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<64>(kWideStagesHalf));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<256, kNarrowStages>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)narrow_lds_bytes<256>(kLdsBytesPerCu / narrow_lds_per_wave(256)));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<256, 4, kWideStagesHalf>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<256>(kWideStagesHalf));
     if (e != hipSuccess) {
         err = std::string("hipFuncSetAttribute: ") + hipGetErrorString(e);
         return (int)e;
@@ -906,7 +948,9 @@ int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream, vo
     dim3 grid(num_bins, a.num_kv_heads / waves);
     dim3 block(64 * waves);
     hipStream_t st = (hipStream_t)stream;
-    if (a.head_dim == 128)
+    if (a.head_dim == 256)
+        RPA_LAUNCH((rpa_narrow_kernel<256, kNarrowStages>), grid, block, narrow_lds_bytes<256>(waves), st, ev, a);
+    else if (a.head_dim == 128)
         RPA_LAUNCH((rpa_narrow_kernel<128, kNarrowStages>), grid, block, narrow_lds_bytes<128>(waves), st, ev, a);
     else
         RPA_LAUNCH((rpa_narrow_kernel<64, kNarrowStages>), grid, block, narrow_lds_bytes<64>(waves), st, ev, a);
@@ -930,7 +974,13 @@ int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev) {
     // but the 512-register shape that needs is beyond what the compiler allocates
     // without spilling.
     const bool half = (a.hg << a.wide_tq_log2) == 128; // 128-row tiles: four waves, two workgroups per CU
-    if (a.head_dim == 128) {
+    if (a.head_dim == 256) {
+        // one shape only: 128 rows, four waves with the whole register file each, and
+        // a ring of two 64 KB stages (one workgroup per CU)
+        if (!half) return (int)hipErrorInvalidValue;
+        RPA_LAUNCH((rpa_wide_kernel<256, 4, kWideStagesHalf>), grid, dim3(256), wide_lds_bytes<256>(kWideStagesHalf),
+                   st, ev, a);
+    } else if (a.head_dim == 128) {
         if (half)
             RPA_LAUNCH((rpa_wide_kernel<128, 4, kWideStagesHalf>), grid, dim3(256),
                        wide_lds_bytes<128>(kWideStagesHalf), st, ev, a);

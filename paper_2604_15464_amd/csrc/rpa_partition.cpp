@@ -27,8 +27,8 @@ int check_shape(const rpa_shape& s, std::string& err) {
         err = "shape fields must all be positive";
         return RPA_ERR_INVALID_ARG;
     }
-    if (s.head_dim != 64 && s.head_dim != 128) {
-        snprintf(buf, sizeof buf, "head_dim %d unsupported (64 or 128)", s.head_dim);
+    if (s.head_dim != 64 && s.head_dim != 128 && s.head_dim != 256) {
+        snprintf(buf, sizeof buf, "head_dim %d unsupported (64, 128 or 256)", s.head_dim);
         err = buf;
         return RPA_ERR_UNSUPPORTED;
     }
@@ -106,7 +106,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         opt.wide_kv_chunk < 0 || opt.units_per_cu < 0 || opt.narrow_waves < 0 || opt.narrow_waves > kMaxWaves ||
         (opt.narrow_waves > 0 && s.num_kv_heads % opt.narrow_waves != 0) ||
         (opt.wide_rows != 0 && opt.wide_rows != 128 && opt.wide_rows != 256) || opt.wide_order < 0 ||
-        opt.wide_order > 2) {
+        opt.wide_order > 2 || !options_fit_shape(s, opt)) {
         err = "bad options";
         return RPA_ERR_INVALID_ARG;
     }
@@ -151,7 +151,9 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     // on the loads) when that still gives every CU several workgroups, else 128
     // rows (twice as many, independent workgroups).
     int wide_rows = opt.wide_rows;
-    if (wide_rows == 0) {
+    if (s.head_dim > 128) {
+        wide_rows = kWideRows; // the only shape built for this head_dim
+    } else if (wide_rows == 0) {
         int64_t tiles256 = 0;
         const int32_t tq256 = wide_q_tokens(hg, 256);
         for (int32_t r = 0; r < n; ++r) {
@@ -193,7 +195,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     // one bin and walks its pieces back to back, so every workgroup streams the
     // same number of KV tiles and there is no tail.
     const int cus = std::max(1, num_cus);
-    const int waves = opt.narrow_waves > 0 ? opt.narrow_waves : narrow_waves(s.num_kv_heads);
+    const int waves = opt.narrow_waves > 0 ? opt.narrow_waves : narrow_waves(s.num_kv_heads, s.head_dim);
     const int ny = s.num_kv_heads / waves;
     const int lds_per_wg = waves * narrow_lds_per_wave(s.head_dim);
     const int wgs_per_cu = std::max(1, std::min(kLdsBytesPerCu / lds_per_wg, 16 / waves));

@@ -114,7 +114,7 @@ def make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_s
 
 
 def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUTO, kv_chunk=0,
-              wide_kv_chunk=0, max_units=1 << 20):
+              wide_kv_chunk=0, max_units=1 << 20, narrow_waves=0, wide_rows=0):
     """Host-only work partition (no GPU needed).  Returns (units, items, stats)
     with units/items as numpy structured views."""
     l = lib()
@@ -124,7 +124,7 @@ def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUT
     units = (WorkUnit * max_units)()
     items = (CombineItem * max_units)()
     stats = PlanStats()
-    opt = Options(variant, kv_chunk, wide_kv_chunk)
+    opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, 0, 0, wide_rows, 0)
     rc = l.rpa_plan_host(C.byref(shape), cu_p, kv_p, n, C.byref(opt), num_cus, units, max_units, items,
                          max_units, C.byref(stats))
     if rc != RPA_OK:

@@ -1,8 +1,9 @@
 """Length sweeps in the shape of the paper's own tables (Sec. 4.1 decode table,
 Sec. 4.2 causal prefill table): uniform lengths, Llama-3-8B attention shape
-(32 query heads, 8 KV heads, head_dim 128), page size 256.
+(32 query heads, 8 KV heads, head_dim 128 or, with --head-dim 256, the paper's
+second head size), page size 256.
 
-    python -m paper_2604_15464_amd.sweep [--decode] [--prefill] [--steps K] [--max-len L]
+    python -m paper_2604_15464_amd.sweep [--decode] [--prefill] [--steps K] [--max-len L] [--head-dim D]
 
 Decode: n = 128 sequences, q_len 1, identical context length 512 ... 32768;
 reports the step latency and the algorithmic GB/s (the paper's byte formula
@@ -24,15 +25,6 @@ from . import rpa
 from . import workloads as W
 
 LENGTHS = (512, 1024, 2048, 4096, 8192, 16384, 32768)
-
-
-def uniform_workload(name, n, q_len, kv_len, page_size=256, seed=11):
-    rng = np.random.default_rng(seed)
-    q = np.full(n, q_len, dtype=np.int64)
-    kv = np.full(n, kv_len, dtype=np.int64)
-    pages = int(W.pages_needed(kv, page_size).sum())
-    return W.Workload(name, seed, 32, 8, 128, page_size, pages, q, kv,
-                      W.make_page_table(kv, page_size, pages, rng))
 
 
 def time_workload(wl, steps, warmup, causal=True):
@@ -76,17 +68,20 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--max-len", type=int, default=32768)
+    ap.add_argument("--head-dim", type=int, default=128, choices=(128, 256))
     args = ap.parse_args()
+    d = args.head_dim
     both = not (args.decode or args.prefill)
     rows = []
     if args.decode or both:
         for c in LENGTHS:
             if c > args.max_len:
                 break
-            wl = uniform_workload(f"decode_128x{c}", 128, 1, c + 1)
+            wl = W.uniform(128, 1, c + 1, d=d)
             dt, k, info = time_workload(wl, args.steps, args.warmup)
             gbps = wl.algorithmic_bytes() / dt / 1e9
-            rec = {"sweep": "decode", "n": 128, "context": c, "page_size": 256, "latency_us": round(dt * 1e6, 1),
+            rec = {"sweep": "decode", "head_dim": d, "n": 128, "context": c, "page_size": 256,
+                   "latency_us": round(dt * 1e6, 1),
                    "GBps": round(gbps, 1), "pct_of_8TBps": round(gbps / 80.0, 2),
                    "narrow_kernel_us": round(k["narrow_ms"] * 1e3, 1), "combine_kernel_us": round(k["combine_ms"] * 1e3, 1),
                    "units": info["num_narrow_units"], "bins": info["num_narrow_bins"]}
@@ -96,10 +91,11 @@ def main():
         for s in LENGTHS:
             if s > args.max_len:
                 break
-            wl = uniform_workload(f"prefill_1x{s}", 1, s, s)
+            wl = W.uniform(1, s, s, d=d)
             dt, k, info = time_workload(wl, args.steps, args.warmup)
             tf = wl.algorithmic_flops() / dt / 1e12
-            rec = {"sweep": "prefill_causal", "n": 1, "seq_len": s, "page_size": 256, "latency_us": round(dt * 1e6, 1),
+            rec = {"sweep": "prefill_causal", "head_dim": d, "n": 1, "seq_len": s, "page_size": 256,
+                   "latency_us": round(dt * 1e6, 1),
                    "TFLOPs": round(tf, 1), "pct_of_2500": round(tf / 25.0, 2),
                    "wide_kernel_us": round(k["wide_ms"] * 1e3, 1), "combine_kernel_us": round(k["combine_ms"] * 1e3, 1),
                    "units": info["num_wide_units"], "wide_rows": info["wide_rows"], "max_splits": info["max_splits"]}
@@ -109,10 +105,10 @@ def main():
         for s in LENGTHS:
             if s > args.max_len:
                 break
-            wl = uniform_workload(f"prefill_1x{s}", 1, s, s)
+            wl = W.uniform(1, s, s, d=d)
             dt, k, info = time_workload(wl, args.steps, args.warmup, causal=False)
             tf = 4.0 * wl.num_q_heads * wl.head_dim * s * s / dt / 1e12  # every (query, key) pair is visible
-            rec = {"sweep": "prefill_noncausal", "n": 1, "seq_len": s, "page_size": 256,
+            rec = {"sweep": "prefill_noncausal", "head_dim": d, "n": 1, "seq_len": s, "page_size": 256,
                    "latency_us": round(dt * 1e6, 1), "TFLOPs": round(tf, 1), "pct_of_2500": round(tf / 25.0, 2),
                    "wide_kernel_us": round(k["wide_ms"] * 1e3, 1), "combine_kernel_us": round(k["combine_ms"] * 1e3, 1),
                    "units": info["num_wide_units"], "wide_rows": info["wide_rows"], "max_splits": info["max_splits"]}

@@ -193,6 +193,17 @@ def ragged(seed: int, num_seqs: int = 5, hq: int = 4, hkv: int = 2, d: int = 64,
                    num_pages=need + spare_pages)
 
 
+def uniform(n: int, q_len: int, kv_len: int, hq: int = 32, hkv: int = 8, d: int = 128, ps: int = 256,
+            seed: int = 11) -> Workload:
+    """n sequences of identical lengths: the shape of the paper's own latency
+    tables (Sec. 4.1 decode: n = 128, q_len 1; Sec. 4.2 prefill: n = 1, q_len =
+    kv_len; head_dim 128 and 256, page size 256)."""
+    rng = np.random.default_rng(seed)
+    q = np.full(n, q_len, dtype=np.int64)
+    kv = np.full(n, kv_len, dtype=np.int64)
+    return _finish(f"uniform_{n}x{q_len}q_{kv_len}kv_d{d}", seed, hq, hkv, d, ps, q, kv, rng)
+
+
 def live_slot_mask(wl: Workload) -> np.ndarray:
     """bool [num_pages, page_size]: slots holding pre-existing cache content
     (positions < ctx of some sequence).  All other slots are dead before the

@@ -139,9 +139,9 @@ def test_full_prefill_without_causal_mask():
 
 
 @pytest.mark.parametrize("ps", [16, 32, 64, 128, 256])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [64, 128, 256])
 def test_page_sizes(ps, d):
-    """Every supported page size (the paper's own is 256), both head dims, both
+    """Every supported page size (the paper's own is 256), every head dim, both
     kernels, with KV splits and a page pool larger than needed."""
     wl = W.ragged(700 + ps + d, num_seqs=6, hq=8, hkv=2, d=d, ps=ps, max_q=90, max_ctx=700, spare_pages=5)
     for variant in (rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL):
@@ -295,6 +295,73 @@ def test_chunked_prefill_carries_cache_across_calls():
     assert np.array_equal(W.bits(x["v_pages"]), vp_ref)
     err = np.abs(to_f64(torch.cat(outs)) - ref)
     assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
+
+
+# ---------------------------------------------------------------------------
+# head_dim 256, the second head size of the paper's evaluation (Sec. 4).
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(4))
+@pytest.mark.parametrize("variant", [rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL])
+def test_head_dim_256_ragged(seed, variant):
+    wl = W.ragged(1200 + seed, num_seqs=6, hq=32, hkv=8, d=256, ps=(16, 64, 256, 32)[seed], max_q=150,
+                  max_ctx=500)
+    for chunk in (0, 64):
+        res = run_case(wl, variant=variant, kv_chunk=chunk, wide_kv_chunk=chunk, pad_tokens=3, pad_seqs=2)
+        check(wl, res)
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 8), (16, 2), (16, 1), (4, 2), (5, 5), (32, 2)])
+def test_head_dim_256_group_sizes(hq, hkv):
+    wl = W.ragged(1300 + hq + hkv, num_seqs=5, hq=hq, hkv=hkv, d=256, ps=16, max_q=80, max_ctx=300)
+    for variant in (rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL):
+        res = run_case(wl, variant=variant)
+        check(wl, res)
+
+
+@pytest.mark.parametrize("variant", [rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL])
+def test_head_dim_256_without_causal_mask(variant):
+    wl = W.ragged(1400, num_seqs=7, hq=8, hkv=2, d=256, ps=16, max_q=150, max_ctx=400)
+    for chunk in (0, 64):
+        res = run_case(wl, variant=variant, kv_chunk=chunk, wide_kv_chunk=chunk, causal=False)
+        check(wl, res)
+
+
+@pytest.mark.parametrize("narrow_waves", [1, 2, 4])
+def test_head_dim_256_narrow_waves(narrow_waves):
+    wl = W.ragged(1500, num_seqs=12, hq=32, hkv=8, d=256, ps=16, max_q=30, max_ctx=600, p_decode=0.7)
+    res = run_case(wl, narrow_waves=narrow_waves, units_per_cu=2)
+    check(wl, res)
+    assert res["info"]["narrow_waves"] == narrow_waves
+
+
+def test_head_dim_256_rejects_shapes_it_has_no_kernel_for():
+    wl = W.ragged(1500, num_seqs=4, hq=32, hkv=8, d=256, ps=16)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl)
+    for kw in ({"narrow_waves": 8}, {"wide_rows": 256}):
+        with pytest.raises(rpa.RpaError) as e:
+            ctx.set_options(**kw)
+        assert e.value.code == rpa.ERR_INVALID_ARG
+    ctx.set_options(narrow_waves=4, wide_rows=128)
+    ctx.close()
+
+
+def test_head_dim_256_uniform_decode_full_size():
+    """A point of the paper's decode table (128 sequences, context 4096, page
+    size 256) at head_dim 256; cache in full, outputs on sampled sequences."""
+    wl = W.uniform(128, 1, 4097, d=256)
+    res = run_case(wl, poison=False, seqs=[0, 63, 127])
+    check(wl, res, seqs=[0, 63, 127])
+    assert res["info"]["variant"] == rpa.VARIANT_DECODE
+    assert torch.isfinite(res["out"][:wl.num_tokens].float()).all()
+
+
+def test_head_dim_256_uniform_prefill_full_size():
+    """Four prefills of 2048 tokens at head_dim 256, one sequence checked."""
+    wl = W.uniform(4, 2048, 2048, d=256)
+    res = run_case(wl, poison=False, seqs=[2])
+    check(wl, res, seqs=[2])
+    assert res["info"]["variant"] == rpa.VARIANT_PREFILL and res["info"]["wide_rows"] == 128
+    assert torch.isfinite(res["out"][:wl.num_tokens].float()).all()
 
 
 # ---------------------------------------------------------------------------

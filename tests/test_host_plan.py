@@ -107,6 +107,22 @@ def test_plan_without_causal_mask_covers_whole_sequences(idx, variant):
     check_plan(wl, units, items, stats, narrow_tq=16 // (wl.num_q_heads // wl.num_kv_heads), causal=False)
 
 
+@pytest.mark.parametrize("variant", [rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL])
+def test_plan_head_dim_256(variant):
+    """head_dim 256: 128-row wide tiles only, at most four waves per narrow
+    workgroup (LDS), and the options that ask for more are rejected."""
+    wl = W.ragged(1200, num_seqs=9, hq=32, hkv=8, d=256, ps=16, max_q=150, max_ctx=400)
+    units, items, stats = rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, variant=variant, num_cus=256)
+    check_plan(wl, units, items, stats, narrow_tq=4)
+    assert stats["wide_rows"] == 128 and stats["narrow_waves"] == 4
+    big = W.uniform(8, 4096, 4096, d=256)          # enough tiles for the 256-row shape at head_dim 128
+    assert rpa.plan_host(shape_of(big), big.cu_q_lens, big.kv_lens, num_cus=256)[2]["wide_rows"] == 128
+    for kw in ({"wide_rows": 256}, {"narrow_waves": 8}):
+        with pytest.raises(rpa.RpaError) as e:
+            rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, **kw)
+        assert e.value.code == rpa.ERR_INVALID_ARG
+
+
 def test_auto_variant_follows_distribution():
     s2 = rpa.plan_host(shape_of(W.config(2)), W.config(2).cu_q_lens, W.config(2).kv_lens)[2]
     assert s2["variant"] == rpa.VARIANT_DECODE

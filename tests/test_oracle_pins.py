@@ -190,9 +190,10 @@ def test_chunked_prefill_composition():
 
 
 # ---- P5: library special case ----------------------------------------------
+@pytest.mark.parametrize("d", [32, 256])
 @pytest.mark.parametrize("lq,ctx", [(1, 40), (33, 0), (17, 29)])
-def test_matches_torch_sdpa_float64(lq, ctx):
-    hq, hkv, d, ps = 8, 2, 32, 16
+def test_matches_torch_sdpa_float64(lq, ctx, d):
+    hq, hkv, ps = 8, 2, 16
     wl = W.Workload("s", 9, hq, hkv, d, ps, 6, [lq], [lq + ctx],
                     W.make_page_table([lq + ctx], ps, 6, np.random.default_rng(4)))
     x = host_inputs(wl)
