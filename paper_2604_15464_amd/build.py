@@ -16,6 +16,11 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 VALU forms are kept off on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results stay in ordinary VGPRs also in the kernel that needs more than
+    # 256 registers (wide, head_dim 256): with the accumulator-register form the
+    # compiler copies the whole output accumulator between the two files on every
+    # tile.  The other kernels compile identically with and without it.
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
 ]
 

@@ -565,13 +565,17 @@ rpa_wide_kernel(KernelArgs a) {
     // with dim D0 + i of positions P .. P+3: a piece of the V^T operand with no
     // register shuffling.  Read 0 takes positions 4h .. 4h+3 of the 16-position
     // k-step, read 1 positions 8+4h .. 8+4h+3 (the order the weights are in).
-    uint32_t koff[KSTEPS], voff[DPL][2];
+    // The swizzle touches the low four bits of the chunk index only, so at
+    // D = 256 the offsets of the row's second half are those of the first + 256.
+    constexpr int NKO = KSTEPS < 8 ? KSTEPS : 8; // distinct K offsets
+    constexpr int NVO = DPL < 4 ? DPL : 4;       // distinct V offset pairs
+    uint32_t koff[NKO], voff[NVO][2];
 #pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk) koff[kk] = n32 * ROWB + (((2 * kk + h) ^ swz(n32)) * 16);
+    for (int kk = 0; kk < NKO; ++kk) koff[kk] = n32 * ROWB + (((2 * kk + h) ^ swz(n32)) * 16);
     {
         const int j16 = lane & 15, half16 = (lane >> 4) & 1;
 #pragma unroll
-        for (int jb = 0; jb < DPL; ++jb)
+        for (int jb = 0; jb < NVO; ++jb)
 #pragma unroll
             for (int rd = 0; rd < 2; ++rd) {
                 const int r = 4 * h + (j16 >> 2) + 8 * rd; // position modulo 16
@@ -580,24 +584,44 @@ rpa_wide_kernel(KernelArgs a) {
             }
     }
 
+    // K operands are requested in batches of eight k-steps (32 registers).
+    constexpr int KB = KSTEPS < 8 ? KSTEPS : 8;
+    auto load_k = [&](bf16x8(&dst)[KB], const char* ldsK, int mt, int k0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kk = 0; kk < KB; ++kk)
+            dst[kk] = *(const bf16x8*)(ldsK + koff[(k0 + kk) % NKO] + ((k0 + kk) / NKO) * 256 + mt * 32 * ROWB);
+    };
+
     // One 32-position half of a tile: scores, online-softmax update, PV.
     auto compute_half = [&](const char* ldsK, const char* ldsV, int pos0, int mt_) __attribute__((always_inline)) {
         const int mt = mt_;
+        union VOp {
+            short4v p[2];
+            bf16x8 v;
+        };
+        VOp vop[2][DPL];
+        auto load_v = [&](int kh) {
+            const char* src = ldsV + (32 * mt + 16 * kh) * ROWB;
+#pragma unroll
+            for (int jb = 0; jb < DPL; ++jb) {
+                const char* s2 = src + (jb / NVO) * 256;
+                vop[kh][jb].p[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(s2 + voff[jb % NVO][0]));
+                vop[kh][jb].p[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(s2 + voff[jb % NVO][1]));
+            }
+        };
         // ---- S^T = K Q^T (Alg. 1: S <- C_q C_k^T) --------------------------------
         f32x16 s[NT];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) s[nt][v] = 0.f;
-        // all K operands of the half are requested before the first MFMA, so the
-        // LDS latency is paid once per half, not once per MFMA pair
-        // (in batches of eight: 32 registers)
-        constexpr int KB = KSTEPS < 8 ? KSTEPS : 8;
+        // the K operands of a batch are requested before its first MFMA, so the LDS
+        // latency is paid once per batch, not once per MFMA pair (requesting
+        // further ahead, a whole half or across halves, measured slower)
 #pragma unroll
         for (int k0 = 0; k0 < KSTEPS; k0 += KB) {
             bf16x8 kop[KB];
-#pragma unroll
-            for (int kk = 0; kk < KB; ++kk) kop[kk] = *(const bf16x8*)(ldsK + koff[k0 + kk] + mt * 32 * ROWB);
+            load_k(kop, ldsK, mt, k0);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int kk = 0; kk < KB; ++kk) {
@@ -610,19 +634,6 @@ rpa_wide_kernel(KernelArgs a) {
         // The V^T fragments of the half's first 16 positions are requested now and
         // arrive under the softmax; those of the second 16 are requested after it,
         // ahead of the first PV MFMAs.
-        union VOp {
-            short4v p[2];
-            bf16x8 v;
-        };
-        VOp vop[2][DPL];
-        auto load_v = [&](int kh) {
-            const char* src = ldsV + (32 * mt + 16 * kh) * ROWB;
-#pragma unroll
-            for (int jb = 0; jb < DPL; ++jb) {
-                vop[kh][jb].p[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(src + voff[jb][0]));
-                vop[kh][jb].p[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(src + voff[jb][1]));
-            }
-        };
         load_v(0);
         __builtin_amdgcn_sched_barrier(0);
         // ---- mask + online softmax (Alg. 1: m~, P, l~) ------------------------
@@ -663,25 +674,8 @@ rpa_wide_kernel(KernelArgs a) {
             l_run[nt] = l_run[nt] * alpha + psum;
             m_run[nt] = m_new;
             if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) { // skip when no row's maximum moved
-                if constexpr (D > 128) {
-                    // The accumulator lives in AGPRs at this size.  The multiply goes
-                    // through explicit register moves so that the compiler keeps it
-                    // there on every path instead of copying all of it to VGPRs and
-                    // back around the MFMAs of every half for the sake of this rare one.
 #pragma unroll
-                    for (int j = 0; j < DPL; ++j)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            float t, r;
-                            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(o[nt][j][v]));
-                            t *= alpha;
-                            asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(r) : "v"(t));
-                            o[nt][j][v] = r;
-                        }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < DPL; ++j) o[nt][j] *= alpha;
-                }
+                for (int j = 0; j < DPL; ++j) o[nt][j] *= alpha;
             }
 #pragma unroll
             for (int kh = 0; kh < 2; ++kh) {

@@ -53,13 +53,19 @@ PIN_TESTS = [(n, f) for n, f in inspect.getmembers(pins, inspect.isfunction)
 
 
 def _calls(fn):
-    """Expand pytest parametrisation by hand."""
-    marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
-    if not marks:
-        return [()]
-    names, values = marks[0].args
-    n = len([s for s in names.split(",")])
-    return [v if n > 1 else (v,) for v in values]
+    """Expand pytest parametrisation (stacked marks included) by hand: a list of
+    keyword dicts, one per case."""
+    cases = [{}]
+    for m in getattr(fn, "pytestmark", []):
+        if m.name != "parametrize":
+            continue
+        names = [s.strip() for s in m.args[0].split(",")]
+        expanded = []
+        for v in m.args[1]:
+            vals = v if len(names) > 1 else (v,)
+            expanded += [dict(c, **dict(zip(names, vals))) for c in cases]
+        cases = expanded
+    return cases
 
 
 @pytest.mark.parametrize("name", sorted(MUTATIONS))
@@ -70,7 +76,7 @@ def test_pins_catch_mutation(name, monkeypatch):
     for tname, fn in PIN_TESTS:
         for args in _calls(fn):
             try:
-                fn(*args)
+                fn(**args)
             except (AssertionError, ValueError, IndexError, FloatingPointError):
                 caught.append(tname)
                 break
