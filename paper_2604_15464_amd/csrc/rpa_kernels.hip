@@ -68,6 +68,15 @@ __device__ __forceinline__ void async_load16_stream(const void* gptr, uint32_t l
                  : "memory");
 }
 
+// The same with the address split into a wave-uniform 64-bit base (scalar
+// registers) and a 32-bit per-lane byte offset: no per-lane address arithmetic.
+__device__ __forceinline__ void async_load16_base(const void* sbase, uint32_t voff, uint32_t lds_byte_off) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
+                 :
+                 : "s"(sbase), "v"(voff), "s"(lds_byte_off)
+                 : "memory");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
@@ -512,33 +521,57 @@ rpa_wide_kernel(KernelArgs a) {
     };
     const int ld_tok = lane / NC;
     const int ld_chunk = lane % NC;
-    uint32_t lane_off[NLD];
+    // byte offset of the lane's chunk of load i from the first token of the wave's share
+    uint32_t lane_voff[NLD];
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
         const int r = WPOS * wave + i * TPI + ld_tok; // row inside the 64-position tile
-        lane_off[i] = (uint32_t)g * ROWB + (uint32_t)((ld_chunk ^ swz(r)) * 16);
+        lane_voff[i] = (uint32_t)(i * TPI + ld_tok) * tokstride + (uint32_t)g * ROWB + (uint32_t)((ld_chunk ^ swz(r)) * 16);
     }
 
+    // The positions a wave brings for one tile are WPOS <= 16 consecutive ones
+    // starting at a multiple of WPOS: they lie in one page (a page holds at least
+    // 16 positions), and so do they after clamping to the end of the range.
+    static_assert(WPOS <= 16 && 16 % WPOS == 0, "a wave's share of a tile must lie in one page");
     auto issue_tile = [&](int t) {
         if (a.ablate & 64) return; // measurement: no KV traffic
         const int p0w = kv_begin + t * KT + WPOS * wave; // this wave's positions
         const int slot = t % NST;
         const uint32_t ldsK = lds_base + slot * STAGEB + (WPOS * wave) * ROWB;
         const uint32_t ldsV = ldsK + TILEB;
+        const int pidx = __builtin_amdgcn_readfirstlane(min(p0w, kv_end - 1) >> ps_log2);
+        const int page = clamp_page(pt_row[pidx], num_pages);
+        const bool all_cached = p0w + WPOS <= min(ctx, kv_end);
+        const bool all_new = p0w >= ctx && p0w + WPOS <= kv_end;
+        if (all_cached || all_new) {
+            // the usual case: the whole share comes from one pool and nothing is
+            // clamped, so one scalar base per pool serves every load
+            const uint64_t tok0 = all_cached ? (((uint64_t)(uint32_t)page << ps_log2) + (uint32_t)(p0w & ps_mask))
+                                             : (uint64_t)(uint32_t)(u.seq_q0 + p0w - ctx);
+            const uint64_t boff = tok0 * tokstride;
+            const char* kb = (all_cached ? k_pages : k_new) + boff;
+            const char* vb = (all_cached ? v_pages : v_new) + boff;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            // 8 aligned positions share a page: one scalar page-table read per load
-            const int pidx = __builtin_amdgcn_readfirstlane(min(p0w + (i * TPI / 8) * 8, kv_end - 1) >> ps_log2);
-            const int page = clamp_page(pt_row[pidx], num_pages);
-            const int pos = min(p0w + i * TPI + ld_tok, kv_end - 1);
-            const bool cached = pos < ctx;
-            const size_t tokidx = cached ? (((size_t)page << ps_log2) + (size_t)(pos & ps_mask))
-                                         : (size_t)(u.seq_q0 + pos - ctx);
-            const uint64_t off = (uint64_t)tokidx * tokstride + lane_off[i];
-            const uint64_t ka = (uint64_t)k_new + off + (cached ? k_delta : 0);
-            const uint64_t va = (uint64_t)v_new + off + (cached ? v_delta : 0);
-            async_load16((const void*)ka, ldsK + i * 1024);
-            async_load16((const void*)va, ldsV + i * 1024);
+            for (int i = 0; i < NLD; ++i) {
+                async_load16_base(kb, lane_voff[i], ldsK + i * 1024);
+                async_load16_base(vb, lane_voff[i], ldsV + i * 1024);
+            }
+        } else {
+            // the share straddles the cached/new boundary or the end of the range:
+            // per-lane pool and position, positions past the end re-read the last one
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                const int pos = min(p0w + i * TPI + ld_tok, kv_end - 1);
+                const bool cached = pos < ctx;
+                const size_t tokidx = cached ? (((size_t)page << ps_log2) + (size_t)(pos & ps_mask))
+                                             : (size_t)(u.seq_q0 + pos - ctx);
+                const uint64_t off =
+                    (uint64_t)tokidx * tokstride + (lane_voff[i] - (uint32_t)(i * TPI + ld_tok) * tokstride);
+                const uint64_t ka = (uint64_t)k_new + off + (cached ? k_delta : 0);
+                const uint64_t va = (uint64_t)v_new + off + (cached ? v_delta : 0);
+                async_load16((const void*)ka, ldsK + i * 1024);
+                async_load16((const void*)va, ldsV + i * 1024);
+            }
         }
     };
 
