@@ -77,6 +77,16 @@ __device__ __forceinline__ void async_load16_base(const void* sbase, uint32_t vo
                  : "memory");
 }
 
+// A pointer whose value is the same in every lane, moved to scalar registers in
+// case the compiler did not prove that on its own (the "s" operand of the asm
+// above must never be handed a vector register).
+__device__ __forceinline__ const char* uniform_ptr(const char* p) {
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const char*)(((uint64_t)hi << 32) | lo);
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
@@ -533,7 +543,7 @@ rpa_wide_kernel(KernelArgs a) {
     // starting at a multiple of WPOS: they lie in one page (a page holds at least
     // 16 positions), and so do they after clamping to the end of the range.
     static_assert(WPOS <= 16 && 16 % WPOS == 0, "a wave's share of a tile must lie in one page");
-    auto issue_tile = [&](int t) {
+    auto issue_tile = [&](int t) __attribute__((always_inline)) {
         if (a.ablate & 64) return; // measurement: no KV traffic
         const int p0w = kv_begin + t * KT + WPOS * wave; // this wave's positions
         const int slot = t % NST;
@@ -549,8 +559,8 @@ rpa_wide_kernel(KernelArgs a) {
             const uint64_t tok0 = all_cached ? (((uint64_t)(uint32_t)page << ps_log2) + (uint32_t)(p0w & ps_mask))
                                              : (uint64_t)(uint32_t)(u.seq_q0 + p0w - ctx);
             const uint64_t boff = tok0 * tokstride;
-            const char* kb = (all_cached ? k_pages : k_new) + boff;
-            const char* vb = (all_cached ? v_pages : v_new) + boff;
+            const char* kb = uniform_ptr((all_cached ? k_pages : k_new) + boff);
+            const char* vb = uniform_ptr((all_cached ? v_pages : v_new) + boff);
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
                 async_load16_base(kb, lane_voff[i], ldsK + i * 1024);
@@ -741,7 +751,7 @@ rpa_wide_kernel(KernelArgs a) {
     // The eight-wave shape runs the two halves through one copy of the code (a real
     // loop), the four-wave shape through two copies (the LDS offsets of a half are
     // then immediates); which is faster was measured, not derived.
-    auto compute_tile = [&](const char* ldsK, const char* ldsV, int pos0) {
+    auto compute_tile = [&](const char* ldsK, const char* ldsV, int pos0) __attribute__((always_inline)) {
         const int nh = (pos0 + 32 <= wave_limit) ? 2 : 1;
         if constexpr (WAVES == 4) {
             compute_half(ldsK, ldsV, pos0, 0);
@@ -774,9 +784,9 @@ rpa_wide_kernel(KernelArgs a) {
     wait_vmcnt<0>();
     __syncthreads();
 
-    for (int t = 0; t < ntiles; ++t) {
+    auto tile_step = [&](int t, auto slot) __attribute__((always_inline)) {
         if (t + NST - 1 < ntiles) issue_tile(t + NST - 1);
-        const char* ldsK = lds_ptr + (t % NST) * STAGEB;
+        const char* ldsK = lds_ptr + (int)slot * STAGEB;
         const char* ldsV = ldsK + TILEB;
         const int pos0 = kv_begin + t * KT;
         // tiles wholly above the wave's diagonal are skipped
@@ -787,6 +797,22 @@ rpa_wide_kernel(KernelArgs a) {
         else if (NST >= 3 && behind == 1) wait_vmcnt<(NST >= 3 ? 1 : 0) * LPT>();
         else wait_vmcnt<0>();
         __syncthreads();
+    };
+    if constexpr (D <= 128) {
+        // Unrolled over the ring so that a tile's stage is a compile-time constant:
+        // the stage base then sits in the offset field of every LDS read instead of
+        // costing a vector add per operand (-1.7 %; at D = 256 the doubled loop body
+        // costs more than that saves).
+        static_assert(NST == 2 || NST == 3, "ring depths the loop is unrolled for");
+        for (int t = 0; t < ntiles; t += NST) { // ntiles is the same for every wave: barriers stay matched
+            tile_step(t, std::integral_constant<int, 0>{});
+            if (t + 1 < ntiles) tile_step(t + 1, std::integral_constant<int, 1>{});
+            if constexpr (NST == 3) {
+                if (t + 2 < ntiles) tile_step(t + 2, std::integral_constant<int, 2>{});
+            }
+        }
+    } else {
+        for (int t = 0; t < ntiles; ++t) tile_step(t, t % NST);
     }
 
     // ---- finalize (Alg. 1: diag(l)^-1 B_o) or store the partial state ------------
