@@ -28,6 +28,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 // wave-uniform reads become scalar loads (and stay so next to the inline asm).
 typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
 typedef __attribute__((address_space(3))) short4v lds_short4;
+typedef const __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 
 // The wide kernel lets softmax weights grow to 2^kRescaleGap before it moves a
 // row's reference maximum and rescales the accumulator.
@@ -515,7 +516,6 @@ rpa_wide_kernel(KernelArgs a) {
     if (wave_limit < 0) wave_min_limit = -1;
 
     const uint32_t lds_base = lds_offset(smem);
-    const char* lds_ptr = (const char*)smem;
     const int kv_begin = u.kv_begin, kv_end = u.kv_end;
     const int ntiles = max(0, (kv_end - kv_begin + KT - 1) / KT);
 
@@ -614,7 +614,12 @@ rpa_wide_kernel(KernelArgs a) {
     constexpr int NVO = DPL < 4 ? DPL : 4;       // distinct V offset pairs
     uint32_t koff[NKO], voff[NVO][2];
 #pragma unroll
-    for (int kk = 0; kk < NKO; ++kk) koff[kk] = n32 * ROWB + (((2 * kk + h) ^ swz(n32)) * 16);
+    for (int kk = 0; kk < NKO; ++kk) {
+        koff[kk] = (D <= 128 ? lds_base : 0) + n32 * ROWB + (((2 * kk + h) ^ swz(n32)) * 16);
+        // opaque from here on: otherwise the compiler splits the sum again and
+        // re-adds its parts at every read
+        if constexpr (D <= 128) asm volatile("" : "+v"(koff[kk]));
+    }
     {
         const int j16 = lane & 15, half16 = (lane >> 4) & 1;
 #pragma unroll
@@ -623,20 +628,38 @@ rpa_wide_kernel(KernelArgs a) {
             for (int rd = 0; rd < 2; ++rd) {
                 const int r = 4 * h + (j16 >> 2) + 8 * rd; // position modulo 16
                 const int chunk = 4 * jb + 2 * half16 + ((j16 & 3) >> 1);
-                voff[jb][rd] = r * ROWB + ((chunk ^ swz(r)) * 16) + (j16 & 1) * 8;
+                voff[jb][rd] = (D <= 128 ? lds_base : 0) + r * ROWB + ((chunk ^ swz(r)) * 16) + (j16 & 1) * 8;
+                if constexpr (D <= 128) asm volatile("" : "+v"(voff[jb][rd]));
             }
     }
 
     // K operands are requested in batches of eight k-steps (32 registers).
     constexpr int KB = KSTEPS < 8 ? KSTEPS : 8;
-    auto load_k = [&](bf16x8(&dst)[KB], const char* ldsK, int mt, int k0) __attribute__((always_inline)) {
+    // At D <= 128 (tile loop unrolled, stage a compile-time constant) an LDS
+    // address is one of the registers above, which already include the ring's own
+    // address and are opaque to the compiler, plus a compile-time constant that
+    // goes into the instruction's offset field: no address arithmetic in the loop.
+    // (Formed from the ring's pointer, every operand cost a vector add, a fifth of
+    // the loop's vector instructions.)  At D = 256 the stage is a run-time value
+    // and the addresses are formed from the pointer as usual.
+    constexpr bool IMM = D <= 128;
+    const char* lds_ptr = (const char*)smem;
+    auto read_k = [&](uint32_t reg, uint32_t rest) __attribute__((always_inline)) {
+        if constexpr (IMM) return *(lds_bf16x8*)(uintptr_t)(reg + rest);
+        else return *(const bf16x8*)(lds_ptr + rest + reg);
+    };
+    auto read_v = [&](uint32_t reg, uint32_t rest) __attribute__((always_inline)) {
+        if constexpr (IMM) return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(uintptr_t)(reg + rest));
+        else return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(lds_ptr + rest + reg));
+    };
+    auto load_k = [&](bf16x8(&dst)[KB], uint32_t ldsK, int mt, int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int kk = 0; kk < KB; ++kk)
-            dst[kk] = *(const bf16x8*)(ldsK + koff[(k0 + kk) % NKO] + ((k0 + kk) / NKO) * 256 + mt * 32 * ROWB);
+            dst[kk] = read_k(koff[(k0 + kk) % NKO], ldsK + ((k0 + kk) / NKO) * 256 + mt * 32 * ROWB);
     };
 
     // One 32-position half of a tile: scores, online-softmax update, PV.
-    auto compute_half = [&](const char* ldsK, const char* ldsV, int pos0, int mt_) __attribute__((always_inline)) {
+    auto compute_half = [&](uint32_t ldsK, uint32_t ldsV, int pos0, int mt_) __attribute__((always_inline)) {
         const int mt = mt_;
         union VOp {
             short4v p[2];
@@ -644,12 +667,12 @@ rpa_wide_kernel(KernelArgs a) {
         };
         VOp vop[2][DPL];
         auto load_v = [&](int kh) {
-            const char* src = ldsV + (32 * mt + 16 * kh) * ROWB;
+            const uint32_t src = ldsV + (32 * mt + 16 * kh) * ROWB;
 #pragma unroll
             for (int jb = 0; jb < DPL; ++jb) {
-                const char* s2 = src + (jb / NVO) * 256;
-                vop[kh][jb].p[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(s2 + voff[jb % NVO][0]));
-                vop[kh][jb].p[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(s2 + voff[jb % NVO][1]));
+                const uint32_t s2 = src + (jb / NVO) * 256;
+                vop[kh][jb].p[0] = read_v(voff[jb % NVO][0], s2);
+                vop[kh][jb].p[1] = read_v(voff[jb % NVO][1], s2);
             }
         };
         // ---- S^T = K Q^T (Alg. 1: S <- C_q C_k^T) --------------------------------
@@ -751,9 +774,9 @@ rpa_wide_kernel(KernelArgs a) {
     // The eight-wave shape runs the two halves through one copy of the code (a real
     // loop), the four-wave shape through two copies (the LDS offsets of a half are
     // then immediates); which is faster was measured, not derived.
-    auto compute_tile = [&](const char* ldsK, const char* ldsV, int pos0) __attribute__((always_inline)) {
+    auto compute_tile = [&](uint32_t ldsK, uint32_t ldsV, int pos0) __attribute__((always_inline)) {
         const int nh = (pos0 + 32 <= wave_limit) ? 2 : 1;
-        if constexpr (WAVES == 4) {
+        if constexpr (WAVES == 4 || D <= 128) {
             compute_half(ldsK, ldsV, pos0, 0);
             if (nh == 2) compute_half(ldsK, ldsV, pos0, 1);
         } else {
@@ -786,8 +809,9 @@ rpa_wide_kernel(KernelArgs a) {
 
     auto tile_step = [&](int t, auto slot) __attribute__((always_inline)) {
         if (t + NST - 1 < ntiles) issue_tile(t + NST - 1);
-        const char* ldsK = lds_ptr + (int)slot * STAGEB;
-        const char* ldsV = ldsK + TILEB;
+        // relative to the ring: koff / voff carry the ring's own LDS address
+        const uint32_t ldsK = (int)slot * STAGEB;
+        const uint32_t ldsV = ldsK + TILEB;
         const int pos0 = kv_begin + t * KT;
         // tiles wholly above the wave's diagonal are skipped
         if (pos0 <= wave_limit && !(a.ablate & 128)) compute_tile(ldsK, ldsV, pos0);
