@@ -109,7 +109,7 @@ typedef struct {
     int64_t partial_rows;    /* fp32 partial rows used                                */
     int64_t workspace_bytes; /* device workspace owned by the context                 */
     int32_t wide_rows;       /* query rows (tokens x heads of a group) per wide tile  */
-    int32_t reserved;
+    int32_t concurrent;      /* 1: narrow and wide kernels were enqueued side by side  */
 } rpa_plan_stats;
 
 /* Tuning knobs; all-zero = defaults.  They change speed only, never results
@@ -139,6 +139,12 @@ typedef struct {
     int32_t wide_order;    /* launch order of the wide units: 1 (and 0 = default)
                               longest tile first overall; 2 = by sequence, heaviest
                               sequence first, longest tile first inside a sequence    */
+    int32_t mixed_overlap; /* a batch with narrow and wide work: 0 = the wide kernel
+                              runs beside the narrow one (on a stream of the context,
+                              forked from and joined to the caller's stream) when both
+                              parts are large enough to repay the two extra stream
+                              packets; 1 = always one after the other on the caller's
+                              stream; 2 = always side by side                          */
 } rpa_options;
 
 typedef struct rpa_ctx rpa_ctx;

@@ -24,6 +24,8 @@ struct Staging {
     void* dev = nullptr;         // device copy of the same blob
     hipEvent_t copied = nullptr; // upload finished (recorded on the upload stream)
     hipEvent_t done = nullptr;   // kernels that read `dev` finished (recorded on the caller's stream)
+    hipEvent_t fork = nullptr;   // caller's stream has reached this call (side stream waits for it)
+    hipEvent_t join = nullptr;   // side stream's kernel finished (caller's stream waits for it)
     bool used = false;
 };
 
@@ -51,6 +53,7 @@ struct rpa_ctx {
     Staging ring[kRing];
     int ring_pos = 0;
     hipStream_t upload = nullptr; // work lists are uploaded here, ahead of the caller's stream
+    hipStream_t side = nullptr;   // the wide kernel of a mixed batch runs here, beside the narrow one
     float* part_o = nullptr;
     float* part_ml = nullptr;
     int64_t workspace_bytes = 0;
@@ -118,9 +121,15 @@ extern "C" int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device) {
         if (e != hipSuccess) return cleanup("hipEventCreate", e);
         e = hipEventCreateWithFlags(&c->ring[i].done, hipEventDisableTiming);
         if (e != hipSuccess) return cleanup("hipEventCreate", e);
+        e = hipEventCreateWithFlags(&c->ring[i].fork, hipEventDisableTiming);
+        if (e != hipSuccess) return cleanup("hipEventCreate", e);
+        e = hipEventCreateWithFlags(&c->ring[i].join, hipEventDisableTiming);
+        if (e != hipSuccess) return cleanup("hipEventCreate", e);
         c->workspace_bytes += (int64_t)c->blob_bytes;
     }
     e = hipStreamCreateWithFlags(&c->upload, hipStreamNonBlocking);
+    if (e != hipSuccess) return cleanup("hipStreamCreate", e);
+    e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e != hipSuccess) return cleanup("hipStreamCreate", e);
     const size_t po = (size_t)c->partial_row_cap * shape->head_dim * sizeof(float);
     const size_t pml = (size_t)c->partial_row_cap * 2 * sizeof(float);
@@ -142,10 +151,13 @@ extern "C" void rpa_destroy(rpa_ctx* c) {
     for (int i = 0; i < kRing; ++i) {
         if (c->ring[i].copied) (void)hipEventDestroy(c->ring[i].copied);
         if (c->ring[i].done) (void)hipEventDestroy(c->ring[i].done);
+        if (c->ring[i].fork) (void)hipEventDestroy(c->ring[i].fork);
+        if (c->ring[i].join) (void)hipEventDestroy(c->ring[i].join);
         if (c->ring[i].host) (void)hipHostFree(c->ring[i].host);
         if (c->ring[i].dev) (void)hipFree(c->ring[i].dev);
     }
     if (c->upload) (void)hipStreamDestroy(c->upload);
+    if (c->side) (void)hipStreamDestroy(c->side);
     if (c->part_o) (void)hipFree(c->part_o);
     if (c->part_ml) (void)hipFree(c->part_ml);
     for (auto& p : c->prof)
@@ -171,7 +183,7 @@ extern "C" int rpa_set_options(rpa_ctx* c, const rpa_options* opt) {
         o.units_per_cu < 0 || o.narrow_waves < 0 || o.narrow_waves > kMaxWaves ||
         (o.narrow_waves > 0 && c->shape.num_kv_heads % o.narrow_waves != 0) ||
         (o.wide_rows != 0 && o.wide_rows != 128 && o.wide_rows != 256) || o.wide_order < 0 || o.wide_order > 2 ||
-        !options_fit_shape(c->shape, o))
+        o.mixed_overlap < 0 || o.mixed_overlap > 2 || !options_fit_shape(c->shape, o))
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: bad value");
     c->opt = o;
     return RPA_OK;
@@ -352,11 +364,29 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     int hrc;
     a.units = dev_units;
     a.bins = (const int32_t*)((const char*)slot.dev + bins_off);
+    // Mixed batch: the wide kernel goes to the context's side stream, forked here
+    // (after the caller's stream has the work list) and joined before the combine.
+    // The two kernels touch disjoint query tokens, partial rows and cache slots.
+    const bool concurrent = plan.stats.concurrent != 0;
+    void* wide_stream = stream;
+    if (concurrent) {
+        e = hipEventRecord(slot.fork, st);
+        if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
+        e = hipStreamWaitEvent(c->side, slot.fork, 0);
+        if (e != hipSuccess) return hip_fail(c, "hipStreamWaitEvent", e);
+        wide_stream = (void*)c->side;
+    }
     hrc = launch_narrow(a, (int)n_bins, plan.stats.narrow_waves, stream, pe ? (void**)&pe->ev[0] : nullptr);
     if (hrc != 0) return hip_fail(c, "narrow kernel launch", (hipError_t)hrc);
     a.units = dev_units + n_narrow;
-    hrc = launch_wide(a, (int)n_wide, stream, pe ? (void**)&pe->ev[2] : nullptr);
+    hrc = launch_wide(a, (int)n_wide, wide_stream, pe ? (void**)&pe->ev[2] : nullptr);
     if (hrc != 0) return hip_fail(c, "wide kernel launch", (hipError_t)hrc);
+    if (concurrent) {
+        e = hipEventRecord(slot.join, c->side);
+        if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
+        e = hipStreamWaitEvent(st, slot.join, 0);
+        if (e != hipSuccess) return hip_fail(c, "hipStreamWaitEvent", e);
+    }
     int max_rows = 0;
     for (const rpa_combine_item& it : plan.items) max_rows = std::max(max_rows, (int)it.rows);
     hrc = launch_combine((const rpa_combine_item*)((char*)slot.dev + items_off), (int)n_items, c->part_o, c->part_ml,

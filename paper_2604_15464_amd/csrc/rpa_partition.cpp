@@ -106,7 +106,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         opt.wide_kv_chunk < 0 || opt.units_per_cu < 0 || opt.narrow_waves < 0 || opt.narrow_waves > kMaxWaves ||
         (opt.narrow_waves > 0 && s.num_kv_heads % opt.narrow_waves != 0) ||
         (opt.wide_rows != 0 && opt.wide_rows != 128 && opt.wide_rows != 256) || opt.wide_order < 0 ||
-        opt.wide_order > 2 || !options_fit_shape(s, opt)) {
+        opt.wide_order > 2 || opt.mixed_overlap < 0 || opt.mixed_overlap > 2 || !options_fit_shape(s, opt)) {
         err = "bad options";
         return RPA_ERR_INVALID_ARG;
     }
@@ -198,7 +198,10 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     const int waves = opt.narrow_waves > 0 ? opt.narrow_waves : narrow_waves(s.num_kv_heads, s.head_dim);
     const int ny = s.num_kv_heads / waves;
     const int lds_per_wg = waves * narrow_lds_per_wave(s.head_dim);
-    const int wgs_per_cu = std::max(1, std::min(kLdsBytesPerCu / lds_per_wg, 16 / waves));
+    // Four resident waves (one 64 KB workgroup at head_dim 128) per CU already
+    // stream at the full HBM rate; more only hold LDS that a wide workgroup of a
+    // mixed batch can use, and cut sequences into more pieces.
+    const int wgs_per_cu = std::max(1, std::min(kLdsBytesPerCu / lds_per_wg, kNarrowWavesPerCu / waves));
     const int64_t slots = (int64_t)cus * wgs_per_cu;
     const int oversub = opt.units_per_cu > 0 ? opt.units_per_cu : 1;
     const int64_t want_bins = std::max<int64_t>(1, ceil_div(slots * oversub, ny));
@@ -209,13 +212,27 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     int64_t per_bin = std::max<int64_t>(min_bin, ceil_div(total_tiles, want_bins));
     const int64_t max_piece = opt.kv_chunk > 0 ? ceil_div(opt.kv_chunk, kNarrowKvTile) : ((int64_t)1 << 40);
 
+    // Narrow and wide kernels side by side when both parts are worth more than the
+    // extra stream packets (about 10 us): the narrow kernel is bound by HBM, the
+    // wide one by the matrix and vector pipes, and a CU holds a workgroup of each.
+    bool concurrent = false;
+    if (any_narrow && any_wide && opt.mixed_overlap != 1) {
+        const double narrow_bytes = (double)total_tiles * kNarrowKvTile * s.num_kv_heads * s.head_dim * 4.0;
+        const double wide_flops = (double)work_wide * wide_q_tokens(hg, wide_rows) * 4.0 * s.num_q_heads * s.head_dim;
+        concurrent = opt.mixed_overlap == 2 || (narrow_bytes >= 128e6 && wide_flops >= 2e10);
+    }
+
     int64_t chunk_w;
     if (opt.wide_kv_chunk > 0) {
         chunk_w = round_up(opt.wide_kv_chunk, kWideKvTile);
-    } else if (wide_tiles * s.num_kv_heads >= (int64_t)cus * 4) {
+    } else if (wide_tiles * s.num_kv_heads >= (int64_t)cus * (concurrent ? 1 : 4)) {
+        // enough workgroups as they are.  Beside the narrow kernel the wide one has
+        // one slot per CU and ends under the narrow kernel's time anyway: balance
+        // matters less there than the partial rows and the combine that splits cost.
         chunk_w = (int64_t)1 << 30;
     } else {
-        chunk_w = round_up(std::max<int64_t>(512, ceil_div(work_wide * s.num_kv_heads, (int64_t)cus * 4)),
+        chunk_w = round_up(std::max<int64_t>(512, ceil_div(work_wide * s.num_kv_heads,
+                                                           (int64_t)cus * (concurrent ? 1 : 4))),
                            kWideKvTile);
     }
 
@@ -306,6 +323,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         });
     }
 
+    plan.stats.concurrent = concurrent;
     plan.stats.num_narrow_bins = (int32_t)plan.bins.size() - 1;
     plan.stats.narrow_waves = waves;
     plan.stats.wide_rows = wide_rows;

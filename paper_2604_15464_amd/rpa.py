@@ -41,7 +41,7 @@ class PlanStats(C.Structure):
         "variant", "num_narrow_units", "num_wide_units", "num_combine_items", "max_splits",
         "kv_chunk", "num_narrow_bins", "narrow_waves")] + [("partial_rows", C.c_int64),
                                                              ("workspace_bytes", C.c_int64),
-                                                             ("wide_rows", C.c_int32), ("reserved", C.c_int32)]
+                                                             ("wide_rows", C.c_int32), ("concurrent", C.c_int32)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -50,7 +50,7 @@ class PlanStats(C.Structure):
 class Options(C.Structure):
     _fields_ = [("variant", C.c_int32), ("kv_chunk", C.c_int32), ("wide_kv_chunk", C.c_int32),
                 ("narrow_waves", C.c_int32), ("units_per_cu", C.c_int32), ("ablate", C.c_int32),
-                ("wide_rows", C.c_int32), ("wide_order", C.c_int32)]
+                ("wide_rows", C.c_int32), ("wide_order", C.c_int32), ("mixed_overlap", C.c_int32)]
 
 
 class RpaError(RuntimeError):
@@ -114,7 +114,7 @@ def make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_s
 
 
 def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUTO, kv_chunk=0,
-              wide_kv_chunk=0, max_units=1 << 20, narrow_waves=0, wide_rows=0):
+              wide_kv_chunk=0, max_units=1 << 20, narrow_waves=0, wide_rows=0, mixed_overlap=0):
     """Host-only work partition (no GPU needed).  Returns (units, items, stats)
     with units/items as numpy structured views."""
     l = lib()
@@ -124,7 +124,7 @@ def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUT
     units = (WorkUnit * max_units)()
     items = (CombineItem * max_units)()
     stats = PlanStats()
-    opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, 0, 0, wide_rows, 0)
+    opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, 0, 0, wide_rows, 0, mixed_overlap)
     rc = l.rpa_plan_host(C.byref(shape), cu_p, kv_p, n, C.byref(opt), num_cus, units, max_units, items,
                          max_units, C.byref(stats))
     if rc != RPA_OK:
@@ -171,8 +171,9 @@ class RaggedPagedAttention:
             pass
 
     def set_options(self, variant=VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, narrow_waves=0, units_per_cu=0,
-                    ablate=0, wide_rows=0, wide_order=0):
-        opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, units_per_cu, ablate, wide_rows, wide_order)
+                    ablate=0, wide_rows=0, wide_order=0, mixed_overlap=0):
+        opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, units_per_cu, ablate, wide_rows, wide_order,
+                      mixed_overlap)
         rc = self._lib.rpa_set_options(self._ctx, C.byref(opt))
         if rc != RPA_OK:
             raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())

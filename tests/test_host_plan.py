@@ -123,6 +123,20 @@ def test_plan_head_dim_256(variant):
         assert e.value.code == rpa.ERR_INVALID_ARG
 
 
+def test_mixed_batches_run_side_by_side_when_large_enough():
+    c4 = W.config(4)
+    assert rpa.plan_host(shape_of(c4), c4.cu_q_lens, c4.kv_lens)[2]["concurrent"] == 1
+    assert rpa.plan_host(shape_of(c4), c4.cu_q_lens, c4.kv_lens, mixed_overlap=1)[2]["concurrent"] == 0
+    c1 = W.config(1)                                  # both parts tiny: not worth two stream packets
+    assert rpa.plan_host(shape_of(c1), c1.cu_q_lens, c1.kv_lens)[2]["concurrent"] == 0
+    assert rpa.plan_host(shape_of(c1), c1.cu_q_lens, c1.kv_lens, mixed_overlap=2)[2]["concurrent"] == 1
+    for idx in (2, 3):                                # one kind of work only: nothing to overlap
+        wl = W.config(idx, scale=0.25)
+        assert rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, mixed_overlap=2)[2]["concurrent"] == 0
+    with pytest.raises(rpa.RpaError):
+        rpa.plan_host(shape_of(c1), c1.cu_q_lens, c1.kv_lens, mixed_overlap=3)
+
+
 def test_auto_variant_follows_distribution():
     s2 = rpa.plan_host(shape_of(W.config(2)), W.config(2).cu_q_lens, W.config(2).kv_lens)[2]
     assert s2["variant"] == rpa.VARIANT_DECODE
