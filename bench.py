@@ -6,7 +6,8 @@ upload + fused cache write + attention + split merge) on a batch that is
 already resident in HBM.  The headline line is the decode workload
 (256 sequences, q_len 1, kv_len ~ U[512, 4096], Llama-3-8B attention shape)
 reported as achieved HBM GB/s; the prefill workload (8 x 2048 causal) is
-reported in the same JSON line under "prefill" as attention TFLOP/s.
+reported in the same JSON line under "prefill" as attention TFLOP/s, the
+mixed batch (128 decode + 4 chunked prefills) under "mixed" as time per call.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 
@@ -134,6 +135,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-mixed", action="store_true")
     ap.add_argument("--copy-bytes", type=int, default=1 << 30,
                     help="size of the plain copy that calibrates HBM counters (0 = skip)")
     args = ap.parse_args()
@@ -228,6 +230,35 @@ def main():
                          "avg_kernel_ms": round(wide_ms, 5)},
         }
         del x3, table3
+        torch.cuda.empty_cache()
+
+    # ---- mixed batch (decode + chunked prefill in one call) ---------------------------
+    if not args.no_mixed:
+        wl4 = W.config(4)
+        x4 = W.materialize(wl4, dev, poison=False)
+        table4 = torch.from_numpy(wl4.page_table).to(dev)
+        ctx4 = rpa.RaggedPagedAttention.for_workload(wl4)
+        dt4, prof4, _ = time_steps(ctx4, x4, table4, wl4, args.steps, args.warmup)
+        info4 = ctx4.plan_info()
+        ctx4.close()
+        n4 = max(1, prof4["calls"])
+        us4 = dt4 / args.steps * 1e6
+        log(f"mixed: {us4:.1f} us/step, narrow {prof4['narrow_ms'] / n4 * 1e3:.1f} us, wide "
+            f"{prof4['wide_ms'] / n4 * 1e3:.1f} us, combine {prof4['combine_ms'] / n4 * 1e3:.1f} us, plan {info4}")
+        result["mixed"] = {
+            "metric": "mixed-batch step time", "value": round(us4, 1), "unit": "us", "higher_is_better": False,
+            "steps": args.steps,
+            "config": {"workload": "mixed: 128 decode seqs kv_len~U[256,8192] + 4 chunked prefills of 512 tokens on "
+                                   "contexts 1K/2K/4K/8K, shuffled, Hq32 Hkv8 D128 page16",
+                       "name": wl4.name, "algorithmic_bytes_per_step": wl4.algorithmic_bytes(),
+                       "exact_causal_flops_per_step": wl4.algorithmic_flops(),
+                       "kernels_side_by_side": bool(info4["concurrent"])},
+            "GBps": round(wl4.algorithmic_bytes() / (dt4 / args.steps) / 1e9, 1),
+            "TFLOPs": round(wl4.algorithmic_flops() / (dt4 / args.steps) / 1e12, 1),
+            "kernel_ms": {"narrow": round(prof4["narrow_ms"] / n4, 5), "wide": round(prof4["wide_ms"] / n4, 5),
+                          "combine": round(prof4["combine_ms"] / n4, 5)},
+        }
+        del x4, table4
         torch.cuda.empty_cache()
 
     # ---- CPU oracle baseline ---------------------------------------------------------
