@@ -35,7 +35,9 @@ contiguous KV, page-permutation invariance, decode == last prefill row,
 chunk composition across calls, torch's float64 scaled_dot_product_attention
 on the contiguous single-sequence case, closed forms (constant V, equal K,
 hand-built log-weights, shift invariance), the split-merge identity, sentinel
-bytes, idempotence.  No function here is "parity unpinned".
+bytes, idempotence; for the 8-bit cache torch's float8_e4m3fn casts, a
+nearest-neighbour search over the 256 decoded values, the lossless case and
+power-of-two scale invariance.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -66,6 +68,55 @@ def f64_to_bf16(x: np.ndarray) -> np.ndarray:
     nan = np.isnan(f32)
     out[nan] = 0x7FC0
     return out
+
+
+# --------------------------------------------------------------------------
+# 8-bit KV cache (Sec. 3.6 "Quantization": per-tensor scaling, one scalar per
+# tensor).  The paper names FP8 but neither the encoding nor the rounding; the
+# reading taken here: OCP E4M3 ("fn": sign, 4 exponent bits with bias 7, 3
+# mantissa bits, subnormals, no infinities, 0x7f / 0xff = NaN, largest finite
+# value 448), a stored byte b stands for value(b) * scale, and a new row x is
+# stored as the byte nearest (ties to even) to fp32(x) * fp32(1 / scale),
+# saturated to +-448, both operations in fp32.
+# --------------------------------------------------------------------------
+E4M3_MAX = 448.0
+
+
+def e4m3_to_f64(u8: np.ndarray) -> np.ndarray:
+    """Exact value of E4M3 bytes."""
+    b = np.asarray(u8, dtype=np.uint8).astype(np.int64)
+    sign = np.where(b & 0x80, -1.0, 1.0)
+    e = (b >> 3) & 0xF
+    m = (b & 0x7).astype(np.float64)
+    val = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    val = sign * val
+    return np.where((b & 0x7F) == 0x7F, np.nan, val)
+
+
+def f32_to_e4m3(x: np.ndarray) -> np.ndarray:
+    """fp32 -> nearest E4M3 byte, ties to the even mantissa, saturating at
+    +-448.  (NaN gives a NaN byte; which of the two is not specified.)"""
+    x = np.asarray(x, dtype=np.float32)
+    a = np.minimum(np.abs(x.astype(np.float64)), E4M3_MAX)
+    sign = np.signbit(x).astype(np.int64) << 7
+    frac, expo = np.frexp(a)                       # a = frac * 2**expo, frac in [0.5, 1)
+    e_unb = np.maximum(expo - 1, -6)               # below 2**-6 the grid of the subnormals continues
+    step = np.exp2((e_unb - 3).astype(np.float64))  # spacing of representable values in this binade
+    q = np.rint(a / step).astype(np.int64)         # numpy rounds halves to even; q in [0, 16]
+    carry = q == 16                                # rounded up into the next binade
+    e_unb = np.where(carry, e_unb + 1, e_unb)
+    q = np.where(carry, 8, q)
+    normal = q >= 8
+    code = np.where(normal, ((e_unb + 7) << 3) | (q - 8), q)   # subnormal: exponent field 0, mantissa q
+    code = np.where(np.isnan(x), 0x7F, code)
+    return (sign | code).astype(np.uint8)
+
+
+def quantize_rows(new_u16: np.ndarray, scale: float) -> np.ndarray:
+    """bf16 bit patterns -> E4M3 bytes of value / scale."""
+    inv = np.float32(1.0) / np.float32(scale)
+    x32 = (np.asarray(new_u16, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    return f32_to_e4m3(x32 * inv)                  # fp32 product, rounded to nearest
 
 
 # --------------------------------------------------------------------------
@@ -139,7 +190,7 @@ def attend_sequence(q, k, v, sm_scale, heads=None, causal=True):
 # the whole call
 # --------------------------------------------------------------------------
 def update_and_attend(q, k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens,
-                      num_seqs, sm_scale, seqs=None, heads=None, causal=True):
+                      num_seqs, sm_scale, seqs=None, heads=None, causal=True, kv_scales=None):
     """The oracle of the library call.
 
     All tensor arguments are numpy uint16 arrays of bf16 bit patterns.
@@ -147,10 +198,25 @@ def update_and_attend(q, k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, 
     not modified.  `seqs` restricts the attention part (not the update) to
     some sequences, for sampled checks at large sizes; rows of other
     sequences are NaN.
+
+    kv_scales = (k_scale, v_scale) selects the 8-bit cache: the pools are
+    uint8 arrays of E4M3 bytes, the new rows are quantised on their way in
+    and attention reads value(byte) * scale for every position, this call's
+    own tokens included (the result is as if the update finished first).
     """
-    k_pages = np.array(k_pages, dtype=np.uint16, copy=True)
-    v_pages = np.array(v_pages, dtype=np.uint16, copy=True)
-    update_cache(k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens, num_seqs)
+    if kv_scales is not None:
+        k_scale, v_scale = (float(np.float32(s)) for s in kv_scales)
+        k_pages = np.array(k_pages, dtype=np.uint8, copy=True)
+        v_pages = np.array(v_pages, dtype=np.uint8, copy=True)
+        update_cache(quantize_rows(k_new, k_scale), quantize_rows(v_new, v_scale), k_pages, v_pages, page_table,
+                     cu_q_lens, kv_lens, num_seqs)
+        decode_k = lambda u: e4m3_to_f64(u) * k_scale
+        decode_v = lambda u: e4m3_to_f64(u) * v_scale
+    else:
+        k_pages = np.array(k_pages, dtype=np.uint16, copy=True)
+        v_pages = np.array(v_pages, dtype=np.uint16, copy=True)
+        update_cache(k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens, num_seqs)
+        decode_k = decode_v = bf16_to_f64
     t_total = int(cu_q_lens[num_seqs]) if num_seqs > 0 else 0
     out = np.full((q.shape[0], q.shape[1], q.shape[2]), np.nan, dtype=np.float64)
     for r in (range(num_seqs) if seqs is None else seqs):
@@ -159,8 +225,8 @@ def update_and_attend(q, k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, 
         if l_q == 0:
             continue
         l_kv = int(kv_lens[r])
-        kk = bf16_to_f64(gather_sequence(k_pages, page_table[r], l_kv))
-        vv = bf16_to_f64(gather_sequence(v_pages, page_table[r], l_kv))
+        kk = decode_k(gather_sequence(k_pages, page_table[r], l_kv))
+        vv = decode_v(gather_sequence(v_pages, page_table[r], l_kv))
         qq = bf16_to_f64(q[q0:q0 + l_q])
         res = attend_sequence(qq, kk, vv, sm_scale, heads=heads, causal=causal)
         if heads is None:

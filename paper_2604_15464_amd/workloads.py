@@ -220,10 +220,14 @@ def live_slot_mask(wl: Workload) -> np.ndarray:
     return live
 
 
-def materialize(wl: Workload, device="cpu", poison: bool = True, max_tokens: int | None = None):
+def materialize(wl: Workload, device="cpu", poison: bool = True, max_tokens: int | None = None, kv_scales=None):
     """Random bf16 ~ N(0,1) tensors for the workload, as torch tensors on
     `device`.  With `poison`, every cache slot that is not pre-existing
-    content, and every padding token row, holds a NaN bit pattern."""
+    content, and every padding token row, holds a NaN bit pattern.
+
+    kv_scales = (k_scale, v_scale): the page pools are uint8 tensors of E4M3
+    bytes instead (an 8-bit cache whose stored values stand for value * scale):
+    N(0,1) / scale cast with torch's float8_e4m3fn, NaN bytes in dead slots."""
     import torch
 
     dev = torch.device(device)
@@ -248,11 +252,21 @@ def materialize(wl: Workload, device="cpu", poison: bool = True, max_tokens: int
     v_new = normal((tmax, hkv, d))
     k_pages = normal((wl.num_pages, ps, hkv, d))
     v_pages = normal((wl.num_pages, ps, hkv, d))
+    if kv_scales is not None:
+        def to_bytes(pool, scale):
+            x = (pool.float() / float(scale)).clamp_(-448.0, 448.0)
+            return x.to(torch.float8_e4m3fn).view(torch.uint8)
+        k_pages = to_bytes(k_pages, kv_scales[0])
+        v_pages = to_bytes(v_pages, kv_scales[1])
     if poison:
         bad = torch.tensor([POISON_BITS], dtype=torch.int16, device=dev).view(torch.bfloat16)
         dead = torch.from_numpy(~live_slot_mask(wl)).to(dev)
-        k_pages[dead] = bad
-        v_pages[dead] = bad
+        if kv_scales is not None:
+            k_pages[dead] = 0x7F          # the E4M3 NaN byte
+            v_pages[dead] = 0x7F
+        else:
+            k_pages[dead] = bad
+            v_pages[dead] = bad
         if tmax > t:
             q[t:] = bad
             k_new[t:] = bad
@@ -261,7 +275,10 @@ def materialize(wl: Workload, device="cpu", poison: bool = True, max_tokens: int
 
 
 def bits(t):
-    """torch bf16 tensor -> numpy uint16 bit patterns (host copy)."""
+    """torch bf16 tensor -> numpy uint16 bit patterns (host copy); uint8
+    tensors (8-bit cache pools) come back as they are."""
     import torch
 
+    if t.dtype == torch.uint8:
+        return t.detach().to("cpu").contiguous().numpy()
     return t.detach().to("cpu").contiguous().view(torch.int16).numpy().view(np.uint16)

@@ -32,8 +32,19 @@ MUTATIONS = {
     "update_ignores_seq_offset": ("k_pages[pg, pos % ps] = k_new[q0 + t]", "k_pages[pg, pos % ps] = k_new[t]"),
     "gather_ignores_table": ("ids = np.asarray(table_row[:n_pages], dtype=np.int64)",
                              "ids = np.arange(n_pages, dtype=np.int64)"),
-    "no_update_before_attend": ("    update_cache(k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens, num_seqs)\n    t_total",
-                                "    t_total"),
+    "no_update_before_attend": ("        update_cache(k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens, num_seqs)\n        decode_k = decode_v",
+                                "        decode_k = decode_v"),
+    "e4m3_wrong_bias": ("np.exp2((e - 7).astype(np.float64))", "np.exp2((e - 8).astype(np.float64))"),
+    "e4m3_truncates": ("q = np.rint(a / step).astype(np.int64)", "q = np.floor(a / step).astype(np.int64)"),
+    "e4m3_rounds_half_up": ("q = np.rint(a / step).astype(np.int64)", "q = np.floor(a / step + 0.5).astype(np.int64)"),
+    "e4m3_no_saturation": ("a = np.minimum(np.abs(x.astype(np.float64)), E4M3_MAX)", "a = np.abs(x.astype(np.float64))"),
+    "e4m3_flushes_subnormals": ("e_unb = np.maximum(expo - 1, -6)", "e_unb = expo - 1"),
+    "e4m3_drops_sign": ("return (sign | code).astype(np.uint8)", "return code.astype(np.uint8)"),
+    "fp8_multiplies_by_scale": ("inv = np.float32(1.0) / np.float32(scale)", "inv = np.float32(scale)"),
+    "fp8_k_scale_not_applied": ("decode_k = lambda u: e4m3_to_f64(u) * k_scale", "decode_k = lambda u: e4m3_to_f64(u)"),
+    "fp8_v_uses_k_scale": ("decode_v = lambda u: e4m3_to_f64(u) * v_scale", "decode_v = lambda u: e4m3_to_f64(u) * k_scale"),
+    "fp8_update_skipped": ("        update_cache(quantize_rows(k_new, k_scale), quantize_rows(v_new, v_scale), k_pages, v_pages, page_table,\n                     cu_q_lens, kv_lens, num_seqs)\n", ""),
+    "fp8_v_rows_use_k_scale": ("quantize_rows(v_new, v_scale)", "quantize_rows(v_new, k_scale)"),
     "merge_without_rescale": ("w = 0.0 if m == -np.inf else math.exp(m - big)", "w = 1.0"),
     "q_offset_ignored": ("qq = bf16_to_f64(q[q0:q0 + l_q])", "qq = bf16_to_f64(q[0:l_q])"),
 }

@@ -471,3 +471,141 @@ def test_noncausal_closed_forms():
     # while under the causal mask they differ (later rows see more keys)
     out_c, _, _ = run_oracle(wl, x)
     assert not np.allclose(out_c[0], out_c[lq - 1], atol=1e-6)
+
+
+# ---- 8-bit KV cache (E4M3 bytes, one scale per tensor) --------------------------------------
+KV_SCALES = (1.0 / 64.0, 1.0 / 32.0)
+
+
+def run_oracle_fp8(wl, x, scales=KV_SCALES, **kw):
+    return O.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"],
+                               wl.page_table, wl.cu_q_lens, wl.kv_lens, wl.num_seqs,
+                               wl.sm_scale, kv_scales=scales, **kw)
+
+
+def host_inputs_fp8(wl, scales=KV_SCALES, poison=True):
+    t = W.materialize(wl, "cpu", poison=poison, kv_scales=scales)
+    return {k: W.bits(v) for k, v in t.items()}
+
+
+def test_e4m3_decode_matches_torch_and_format():
+    b = np.arange(256, dtype=np.uint8)
+    ref = torch.from_numpy(b.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    got = O.e4m3_to_f64(b)
+    assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.isnan(got).sum() == 2
+    assert np.array_equal(got[~np.isnan(got)], ref[~np.isnan(ref)])
+    # the format's fixed points: bias 7, largest value 448, smallest 2**-9
+    assert got[0x38] == 1.0 and got[0x7E] == 448.0 and got[0x01] == 2.0 ** -9 and got[0x08] == 2.0 ** -6
+    assert got[0x80] == 0.0 and np.signbit(got[0x80]) and got[0xFE] == -448.0
+
+
+def test_e4m3_encode_matches_torch_and_nearest_search():
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.normal(size=20000) * 3, rng.normal(size=20000) * 150, rng.normal(size=5000) * 1e-2,
+                        rng.normal(size=2000) * 1e-3]).astype(np.float32)
+    x = np.clip(x, -448, 448)
+    got = O.f32_to_e4m3(x)
+    ref = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(got, ref)
+    # structurally different: nearest of the 254 finite values, ties to the even code
+    table = O.e4m3_to_f64(np.arange(256, dtype=np.uint8))
+    for v, code in zip(x[::97].tolist(), got[::97].tolist()):
+        dist = np.abs(table - v)
+        dist[np.isnan(dist)] = np.inf
+        best = np.flatnonzero(dist == dist.min())
+        if v == 0.0 or abs(table[code]) == 0.0:
+            assert table[code] == 0.0 and 0 in (best & 0x7F)
+            continue
+        cands = [c for c in best if np.signbit(table[c]) == np.signbit(v)]
+        assert code in cands
+        if len(cands) == 2:                        # a tie: the even mantissa wins
+            assert code % 2 == 0
+
+
+def test_e4m3_encode_special_cases():
+    enc = lambda *v: O.f32_to_e4m3(np.asarray(v, dtype=np.float32)).tolist()
+    assert enc(0.0, 1.0, -1.0) == [0x00, 0x38, 0xB8]
+    assert enc(1.0625, 1.1875) == [0x38, 0x3A]                 # ties go to the even mantissa
+    assert enc(448.0, 449.0, 464.0, 465.0, 1e6, np.inf) == [0x7E] * 6     # saturates, never a NaN byte
+    assert enc(-500.0, -np.inf) == [0xFE, 0xFE]
+    assert enc(2.0 ** -9, 2.0 ** -10, 1.5 * 2.0 ** -9, 2.0 ** -6) == [0x01, 0x00, 0x02, 0x08]
+    # every finite byte survives a round trip
+    b = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    assert np.array_equal(O.f32_to_e4m3(O.e4m3_to_f64(b).astype(np.float32)), b)
+    # half an ulp of three mantissa bits in the normal range
+    x = np.random.default_rng(3).uniform(2.0 ** -6, 448, size=5000).astype(np.float32)
+    err = np.abs(O.e4m3_to_f64(O.f32_to_e4m3(x)) - x) / x
+    assert err.max() <= 2.0 ** -4
+
+
+def test_fp8_cache_update_writes_quantised_rows_only():
+    wl = W.ragged(7, num_seqs=5, hq=4, hkv=2, d=16, ps=16, max_q=20, max_ctx=50)
+    x = host_inputs_fp8(wl)
+    _, kp, vp = run_oracle_fp8(wl, x)
+    assert kp.dtype == np.uint8
+    changed = np.zeros(kp.shape[:2], dtype=bool)
+    for r in range(wl.num_seqs):
+        q0, lq, ctx = int(wl.cu_q_lens[r]), int(wl.q_lens[r]), int(wl.ctx_lens[r])
+        for t in range(lq):
+            pos = ctx + t
+            pg = wl.page_table[r, pos // wl.page_size]
+            changed[pg, pos % wl.page_size] = True
+            for name, pool, scale in (("k_new", kp, KV_SCALES[0]), ("v_new", vp, KV_SCALES[1])):
+                val = O.bf16_to_f64(x[name][q0 + t]).astype(np.float32) * (np.float32(1) / np.float32(scale))
+                ref = torch.from_numpy(np.clip(val, -448, 448)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+                assert np.array_equal(pool[pg, pos % wl.page_size], ref)
+    assert np.array_equal(kp[~changed], x["k_pages"][~changed]) and np.array_equal(vp[~changed], x["v_pages"][~changed])
+
+
+def test_fp8_path_equals_bf16_path_on_dequantised_inputs():
+    """Attention over the 8-bit cache is plain attention over value(byte) * scale: feed
+    those values (exact in bf16 for power-of-two scales) to the 16-bit path."""
+    wl = W.ragged(8, num_seqs=5, hq=4, hkv=2, d=16, ps=16, max_q=20, max_ctx=50)
+    x = host_inputs_fp8(wl, poison=False)
+    out8, kp8, vp8 = run_oracle_fp8(wl, x)
+    y = dict(x)
+    y["k_pages"] = f32_to_bf16_bits(O.e4m3_to_f64(x["k_pages"]) * KV_SCALES[0])
+    y["v_pages"] = f32_to_bf16_bits(O.e4m3_to_f64(x["v_pages"]) * KV_SCALES[1])
+    y["k_new"] = f32_to_bf16_bits(O.e4m3_to_f64(O.quantize_rows(x["k_new"], KV_SCALES[0])) * KV_SCALES[0])
+    y["v_new"] = f32_to_bf16_bits(O.e4m3_to_f64(O.quantize_rows(x["v_new"], KV_SCALES[1])) * KV_SCALES[1])
+    out16, _, _ = run_oracle(wl, y)
+    live = ~np.isnan(out16)
+    assert np.array_equal(np.isnan(out8), np.isnan(out16))
+    assert np.allclose(out8[live], out16[live], rtol=0, atol=1e-12)
+
+
+def test_fp8_power_of_two_scale_invariance():
+    """Doubling the new rows and both scales leaves the stored bytes unchanged; the
+    bytes then stand for doubled K and V, so with half the softmax scale the output
+    is exactly doubled (away from the subnormal and saturation ends of the format)."""
+    wl = W.ragged(9, num_seqs=4, hq=4, hkv=2, d=16, ps=16, max_q=12, max_ctx=0)      # new tokens only
+    xa = host_inputs_fp8(wl)
+    xb = dict(xa)
+    xb["k_new"] = f32_to_bf16_bits(O.bf16_to_f64(xa["k_new"]) * 2.0)
+    xb["v_new"] = f32_to_bf16_bits(O.bf16_to_f64(xa["v_new"]) * 2.0)
+    oa, ka, va = run_oracle_fp8(wl, xa)
+    ob, kb, vb = O.update_and_attend(xb["q"], xb["k_new"], xb["v_new"], xb["k_pages"], xb["v_pages"], wl.page_table,
+                                     wl.cu_q_lens, wl.kv_lens, wl.num_seqs, wl.sm_scale / 2,
+                                     kv_scales=(2 * KV_SCALES[0], 2 * KV_SCALES[1]))
+    assert np.array_equal(ka, kb) and np.array_equal(va, vb)
+    live = ~np.isnan(oa)
+    assert live.any() and np.allclose(2.0 * oa[live], ob[live], rtol=0, atol=1e-12)
+
+
+def test_fp8_decode_equals_last_prefill_row():
+    """q_len 1 on a cache that an earlier call filled == last row of the one-call prefill."""
+    hq, hkv, d, ps, n = 4, 2, 16, 16, 23
+    rng = np.random.default_rng(11)
+    wl_full = W.Workload("f", 3, hq, hkv, d, ps, 4, [n], [n], W.make_page_table([n], ps, 4, rng))
+    x = host_inputs_fp8(wl_full)
+    out_full, kp, vp = run_oracle_fp8(wl_full, x)
+    wl_pre = W.Workload("p", 3, hq, hkv, d, ps, 4, [n - 1], [n - 1], wl_full.page_table)
+    _, kp1, vp1 = run_oracle_fp8(wl_pre, x)
+    wl_dec = W.Workload("d", 3, hq, hkv, d, ps, 4, [1], [n], wl_full.page_table)
+    y = dict(x)
+    y["k_pages"], y["v_pages"] = kp1, vp1
+    for name in ("q", "k_new", "v_new"):
+        y[name] = x[name][n - 1:n]
+    out_dec, kp2, vp2 = run_oracle_fp8(wl_dec, y)
+    assert np.array_equal(kp2, kp) and np.array_equal(vp2, vp)
+    assert np.allclose(out_dec[0], out_full[n - 1], rtol=0, atol=1e-12)
