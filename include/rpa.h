@@ -57,6 +57,18 @@ typedef struct {
                                   (the default; Alg. 1 "mask S if needed"); 1: no mask,
                                   every query token sees all kv_len positions (the
                                   paper's non-causal prefill measurements, Sec. 4.2)  */
+    int32_t kv_fp8;            /* 0: k_pages / v_pages hold bf16.  1: they hold one byte
+                                  per element, OCP E4M3 (bias 7, largest value 448, no
+                                  infinities), scaled per tensor (Sec. 3.6
+                                  "Quantization"): a byte b stands for value(b) * scale.
+                                  k_new / v_new stay bf16; a new row x is stored as the
+                                  byte nearest (ties to even) to fp32(x) * fp32(1/scale),
+                                  saturated to +-448, and attention reads the stored
+                                  values for every position, the call's own tokens
+                                  included.  Every batch then runs on the narrow kernel
+                                  (built for the bandwidth-bound decode case).          */
+    float k_scale;             /* scale of k_pages (> 0, finite); read if kv_fp8 only   */
+    float v_scale;             /* scale of v_pages                                       */
 } rpa_shape;
 
 /* Kernel variants (Sec. 3.4 "Distribution-aware Compilation": decode-only,
@@ -182,6 +194,7 @@ void rpa_destroy(rpa_ctx* ctx);
  *   v_new      dev  bf16 [max_tokens, num_kv_heads, head_dim]
  *   k_pages    dev  bf16 [num_pages, page_size, num_kv_heads, head_dim]  updated in place
  *   v_pages    dev  bf16 [num_pages, page_size, num_kv_heads, head_dim]  updated in place
+ *              (with rpa_shape.kv_fp8: one E4M3 byte per element, same index order)
  *   page_table dev  int32 [max_seqs, max_pages_per_seq]; ids outside
  *                   [0, num_pages) are clamped into range (wrong result, no fault)
  *   cu_q_lens  host int32 [num_seqs + 1], cu_q_lens[0] = 0, non-decreasing

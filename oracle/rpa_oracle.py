@@ -102,7 +102,8 @@ def f32_to_e4m3(x: np.ndarray) -> np.ndarray:
     frac, expo = np.frexp(a)                       # a = frac * 2**expo, frac in [0.5, 1)
     e_unb = np.maximum(expo - 1, -6)               # below 2**-6 the grid of the subnormals continues
     step = np.exp2((e_unb - 3).astype(np.float64))  # spacing of representable values in this binade
-    q = np.rint(a / step).astype(np.int64)         # numpy rounds halves to even; q in [0, 16]
+    with np.errstate(invalid="ignore"):            # NaN input (padding rows) is handled below
+        q = np.rint(a / step).astype(np.int64)     # numpy rounds halves to even; q in [0, 16]
     carry = q == 16                                # rounded up into the next binade
     e_unb = np.where(carry, e_unb + 1, e_unb)
     q = np.where(carry, 8, q)

@@ -56,6 +56,8 @@ struct rpa_ctx {
     hipStream_t side = nullptr;   // the wide kernel of a mixed batch runs here, beside the narrow one
     float* part_o = nullptr;
     float* part_ml = nullptr;
+    void* new8_k = nullptr; // 8-bit cache: quantised copy of this call's k_new / v_new rows
+    void* new8_v = nullptr;
     int64_t workspace_bytes = 0;
     Plan plan;
     rpa_plan_stats last{};
@@ -138,6 +140,14 @@ extern "C" int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device) {
     e = hipMalloc((void**)&c->part_ml, pml);
     if (e != hipSuccess) return cleanup("hipMalloc", e);
     c->workspace_bytes += (int64_t)(po + pml);
+    if (shape->kv_fp8) {
+        const size_t nb = (size_t)shape->max_tokens * shape->num_kv_heads * shape->head_dim;
+        e = hipMalloc(&c->new8_k, nb);
+        if (e != hipSuccess) return cleanup("hipMalloc", e);
+        e = hipMalloc(&c->new8_v, nb);
+        if (e != hipSuccess) return cleanup("hipMalloc", e);
+        c->workspace_bytes += (int64_t)(2 * nb);
+    }
     if (kernels_init(device, msg) != 0) {
         rpa_destroy(c);
         return fail(nullptr, RPA_ERR_HIP, msg);
@@ -160,6 +170,8 @@ extern "C" void rpa_destroy(rpa_ctx* c) {
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->part_o) (void)hipFree(c->part_o);
     if (c->part_ml) (void)hipFree(c->part_ml);
+    if (c->new8_k) (void)hipFree(c->new8_k);
+    if (c->new8_v) (void)hipFree(c->new8_v);
     for (auto& p : c->prof)
         for (auto& e : p.ev)
             if (e) (void)hipEventDestroy(e);
@@ -358,6 +370,21 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     a.scale_log2 = sm_scale * 1.4426950408889634f;
     a.ablate = c->opt.ablate;
     a.causal = c->shape.non_causal ? 0 : 1;
+    a.kv_fp8 = c->shape.kv_fp8;
+    a.out_scale = 1.f;
+    if (a.kv_fp8) {
+        // The new rows are quantised into the staging copy first; from there on the
+        // kernels see bytes only.  K's scale folds into the softmax scale, V's is
+        // applied to the output rows.
+        const size_t elems = (size_t)cu_q_lens[num_seqs] * a.num_kv_heads * a.head_dim;
+        const int qrc = launch_quantize(k_new, v_new, c->new8_k, c->new8_v, elems, 1.f / c->shape.k_scale,
+                                        1.f / c->shape.v_scale, c->num_cus, stream);
+        if (qrc != 0) return hip_fail(c, "quantise kernel launch", (hipError_t)qrc);
+        a.k_new = (const uint16_t*)c->new8_k;
+        a.v_new = (const uint16_t*)c->new8_v;
+        a.scale_log2 *= c->shape.k_scale;
+        a.out_scale = c->shape.v_scale;
+    }
 
     const rpa_work_unit* dev_units = (const rpa_work_unit*)slot.dev;
     ProfEvents* pe = (c->prof_on && c->prof_count < kProfCalls) ? &c->prof[c->prof_count] : nullptr;

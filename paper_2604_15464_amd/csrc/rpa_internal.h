@@ -83,6 +83,8 @@ struct KernelArgs {
     float scale_log2; // sm_scale * log2(e)
     int32_t ablate;   // measurement switches (rpa_options.ablate)
     int32_t causal;   // 0: no mask beyond the end of the sequence
+    int32_t kv_fp8;   // 1: pools and k_new / v_new (here: the quantised staging copy) hold E4M3 bytes
+    float out_scale;  // V scale of the 8-bit cache, else 1
 };
 
 // Launchers (rpa_kernels.hip).  Return a hipError_t value as int.  `ev` is either
@@ -94,6 +96,9 @@ int launch_combine(const rpa_combine_item* items, int num_items, const float* pa
                    const float* part_ml, uint16_t* out, int num_q_heads, int head_dim, int max_rows,
                    void* stream, void** ev);
 int launch_copy(void* dst, const void* src, size_t n16, int num_cus, void* stream, void** ev);
+// new K/V rows (bf16, `elems` elements each, a multiple of 8) -> E4M3 bytes of x * inv_scale
+int launch_quantize(const void* k_new, const void* v_new, void* k8, void* v8, size_t elems, float inv_k, float inv_v,
+                    int num_cus, void* stream);
 int kernels_init(int device, std::string& err);
 
 } // namespace rpa

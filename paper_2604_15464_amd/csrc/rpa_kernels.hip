@@ -120,6 +120,17 @@ __device__ __forceinline__ float max_across_halves(float x) {
     return fmaxf(lo, hi);
 }
 
+// Eight E4M3 bytes (an 8-bit KV cache row piece) -> eight bf16, exact: every
+// E4M3 value, subnormals included, is a bf16 value.  Byte j becomes element j.
+__device__ __forceinline__ bf16x8 e4m3x8_to_bf16x8(const uint2& r) {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r.x, 1.0f, false);
+    const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r.x, 1.0f, true);
+    const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r.y, 1.0f, false);
+    const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r.y, 1.0f, true);
+    return bf16x8{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+}
+
 __device__ __forceinline__ int clamp_page(int page, int num_pages) {
     return min(max(page, 0), num_pages - 1);
 }
@@ -133,10 +144,16 @@ __device__ __forceinline__ int clamp_page(int page, int num_pages) {
 // runs; bandwidth-bound.  A unit covers KV positions [kv_begin, kv_end) and
 // either writes the final rows or an un-normalised partial (m, l, O).
 // ---------------------------------------------------------------------------
-template <int D, int NST>
+//
+// KV8: the cache (and the staged copy of the new rows) holds one E4M3 byte per
+// element (Sec. 3.6 "Quantization").  Rows are half as long, the ring is twice
+// as deep, and operands are widened to bf16 after the LDS read; everything else
+// is the same code.
+template <int D, int NST, bool KV8>
 __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a) {
-    constexpr int ROWB = D * 2;                 // bytes of one token row of one head
-    constexpr int NC = D / 8;                   // 16-byte chunks per row
+    constexpr int ROWB = D * (KV8 ? 1 : 2);     // bytes of one token row of one head
+    constexpr int NC = ROWB / 16;               // 16-byte chunks per row
+    constexpr int NG = D / 8;                   // groups of 8 elements per row
     constexpr int TPI = 64 / NC;                // tokens covered by one wave-wide load
     constexpr int NLD = kNarrowKvTile / TPI;    // loads per K (or V) tile
     constexpr int TILEB = kNarrowKvTile * ROWB; // bytes of a K (or V) tile
@@ -282,11 +299,19 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         }
 
         // ---- S^T = K Q^T (Alg. 1: S <- C_q C_k^T) --------------------------------
+        // byte offset in a tile of elements 8*gi .. 8*gi+7 of token row r (the XOR
+        // swizzle works on 16-byte chunks: a whole group, or two with 8-bit elements)
+        auto group_off = [](int r, int gi) {
+            return KV8 ? r * ROWB + (((gi >> 1) ^ (r % NC)) * 16) + (gi & 1) * 8 : r * ROWB + ((gi ^ (r % NC)) * 16);
+        };
+        auto read_group = [&](const char* tile, int r, int gi) {
+            if constexpr (KV8) return e4m3x8_to_bf16x8(*(const uint2*)(tile + group_off(r, gi)));
+            else return *(const bf16x8*)(tile + group_off(r, gi));
+        };
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) {
-            const int c = 4 * kk + quad;
-            const bf16x8 kop = *(const bf16x8*)(ldsK + n * ROWB + ((c ^ (n % NC)) * 16));
+            const bf16x8 kop = read_group(ldsK, n, 4 * kk + quad);
             s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[kk], s, 0, 0, 0);
         }
 
@@ -330,11 +355,11 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 #pragma unroll
         for (int vg = 0; vg < VG; ++vg) {
             uint32_t vr[4][4];
-            const int ch = 16 * vg + n % NC;
+            const int ch = 16 * vg + n % NG;
 #pragma unroll
             for (int tt = 0; tt < 4; ++tt) {
                 const int tok = 4 * quad + tt;
-                const uint4 raw = *(const uint4*)(ldsV + tok * ROWB + ((ch ^ (tok % NC)) * 16));
+                const uint4 raw = __builtin_bit_cast(uint4, read_group(ldsV, tok, ch));
                 vr[tt][0] = raw.x;
                 vr[tt][1] = raw.y;
                 vr[tt][2] = raw.z;
@@ -357,7 +382,7 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
                 for (int j = 0; j < 8; ++j)
                     acc[8 * vg + j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[j], pop.v, acc[8 * vg + j], 0, 0, 0);
             } else {
-                const bool upper = n >= NC; // lanes 8..15 serve dims j+4 of their chunk
+                const bool upper = n >= NG; // lanes 8..15 serve dims j+4 of their chunk
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     short4v pick;
@@ -378,12 +403,12 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         for (int t = lane / NC; t < u.n_q; t += TPI) {
             const int pos = ctx + u.q_pos0 + t;
             const int page = clamp_page(pt_row[pos >> ps_log2], num_pages);
-            const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * D + c * 8;
-            const size_t dst = ((((size_t)page << ps_log2) + (pos & ps_mask)) * Hkv + g) * D + c * 8;
-            const uint4 kk = *(const uint4*)(a.k_new + src);
-            const uint4 vv = *(const uint4*)(a.v_new + src);
-            store16_streaming(a.k_pages + dst, kk);
-            store16_streaming(a.v_pages + dst, vv);
+            const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * ROWB + c * 16; // bytes
+            const size_t dst = ((((size_t)page << ps_log2) + (pos & ps_mask)) * Hkv + g) * ROWB + c * 16;
+            const uint4 kk = *(const uint4*)(k_new + src);
+            const uint4 vv = *(const uint4*)(v_new + src);
+            store16_streaming((char*)a.k_pages + dst, kk);
+            store16_streaming((char*)a.v_pages + dst, vv);
         }
     }
 
@@ -395,14 +420,15 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         // nothing to store for a padding row
     } else if (u.part_row < 0) {
         // accumulator elements acc[JW*vg .. JW*vg + JW-1][v] of a lane are JW consecutive dims
-        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        // (a.out_scale is the V scale of an 8-bit cache, else 1)
+        const float inv = l_tot > 0.f ? a.out_scale / l_tot : 0.f;
         uint16_t* orow = a.out + ((size_t)(u.q_start + tok_n) * Hq + head) * D;
 #pragma unroll
         for (int v = 0; v < 4; ++v)
 #pragma unroll
             for (int vg = 0; vg < VG; ++vg) {
                 const int mrow = 4 * quad + v;
-                const int d0 = 128 * vg + 8 * (mrow % NC) + JW * (mrow / NC);
+                const int d0 = 128 * vg + 8 * (mrow % NG) + JW * (mrow / NG);
                 uint32_t w[JW / 2];
 #pragma unroll
                 for (int jj = 0; jj < JW / 2; ++jj)
@@ -418,12 +444,13 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 #pragma unroll
             for (int vg = 0; vg < VG; ++vg) {
                 const int mrow = 4 * quad + v;
-                const int d0 = 128 * vg + 8 * (mrow % NC) + JW * (mrow / NC);
+                const int d0 = 128 * vg + 8 * (mrow % NG) + JW * (mrow / NG);
+                const float os = KV8 ? a.out_scale : 1.f; // partial sums carry the V scale
 #pragma unroll
                 for (int c4 = 0; c4 < JW / 4; ++c4)
                     *(float4*)(po + d0 + 4 * c4) =
-                        make_float4(acc[JW * vg + 4 * c4][v], acc[JW * vg + 4 * c4 + 1][v], acc[JW * vg + 4 * c4 + 2][v],
-                                    acc[JW * vg + 4 * c4 + 3][v]);
+                        make_float4(acc[JW * vg + 4 * c4][v] * os, acc[JW * vg + 4 * c4 + 1][v] * os,
+                                    acc[JW * vg + 4 * c4 + 2][v] * os, acc[JW * vg + 4 * c4 + 3][v] * os);
             }
         if (quad == 0) {
             a.part_ml[prow * 2] = m_run;
@@ -959,6 +986,43 @@ __global__ void __launch_bounds__(256) rpa_combine_kernel(const rpa_combine_item
 }
 
 // ---------------------------------------------------------------------------
+// 8-bit cache: the new K/V rows are quantised once per call into a staging copy
+// (Sec. 3.6: one scale per tensor).  Byte = nearest E4M3 value (ties to even) of
+// fp32(x) * inv_scale, saturated to +-448; the attention kernel then reads the
+// new rows from the staging copy exactly like cached ones, and the cache write
+// is a byte copy.  One thread = eight elements of K and of V.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint2 quantize8(const uint4& raw, float inv_scale) {
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    float f[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __uint_as_float(w[i] << 16);          // bf16 -> fp32, exact
+        f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float y = f[i] * inv_scale;
+        f[i] = (y != y) ? y : fminf(fmaxf(y, -448.f), 448.f); // the conversion itself does not saturate
+    }
+    int lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], 0, false);
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], lo, true);
+    int hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], 0, false);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], hi, true);
+    return make_uint2((uint32_t)lo, (uint32_t)hi);
+}
+
+__global__ __launch_bounds__(256) void rpa_quantize_kernel(const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
+                                                           uint2* __restrict__ k8, uint2* __restrict__ v8, size_t n8,
+                                                           float inv_k, float inv_v) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += stride) {
+        k8[i] = quantize8(k_new[i], inv_k);
+        v8[i] = quantize8(v_new[i], inv_v);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Plain streaming copy, 16 bytes per lane per step.  Not part of the method: it
 // is the known-size workload against which HBM byte counters and the narrow
 // kernel's bandwidth are calibrated.
@@ -985,11 +1049,22 @@ static size_t wide_lds_bytes(int stages) {
 int kernels_init(int device, std::string& err) {
     (void)device;
     hipError_t e;
-    e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<128, kNarrowStages>,
+    e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<128, kNarrowStages, false>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<128>(kMaxWaves));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<64, kNarrowStages>,
+        e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<64, kNarrowStages, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<64>(kMaxWaves));
+    // 8-bit cache: rows half as long, ring twice as deep, the same bytes per wave
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<128, 2 * kNarrowStages, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<128>(kMaxWaves));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<64, 2 * kNarrowStages, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<64>(kMaxWaves));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<256, 2 * kNarrowStages, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)narrow_lds_bytes<256>(kLdsBytesPerCu / narrow_lds_per_wave(256)));
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 8, kWideStages>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<128>(kWideStages));
@@ -1003,7 +1078,7 @@ int kernels_init(int device, std::string& err) {
         e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 4, kWideStagesHalf>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<64>(kWideStagesHalf));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<256, kNarrowStages>,
+        e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<256, kNarrowStages, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)narrow_lds_bytes<256>(kLdsBytesPerCu / narrow_lds_per_wave(256)));
     if (e == hipSuccess)
@@ -1025,12 +1100,34 @@ int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream, vo
     dim3 grid(num_bins, a.num_kv_heads / waves);
     dim3 block(64 * waves);
     hipStream_t st = (hipStream_t)stream;
-    if (a.head_dim == 256)
-        RPA_LAUNCH((rpa_narrow_kernel<256, kNarrowStages>), grid, block, narrow_lds_bytes<256>(waves), st, ev, a);
+    if (a.kv_fp8) {
+        if (a.head_dim == 256)
+            RPA_LAUNCH((rpa_narrow_kernel<256, 2 * kNarrowStages, true>), grid, block, narrow_lds_bytes<256>(waves), st,
+                       ev, a);
+        else if (a.head_dim == 128)
+            RPA_LAUNCH((rpa_narrow_kernel<128, 2 * kNarrowStages, true>), grid, block, narrow_lds_bytes<128>(waves), st,
+                       ev, a);
+        else
+            RPA_LAUNCH((rpa_narrow_kernel<64, 2 * kNarrowStages, true>), grid, block, narrow_lds_bytes<64>(waves), st,
+                       ev, a);
+    } else if (a.head_dim == 256)
+        RPA_LAUNCH((rpa_narrow_kernel<256, kNarrowStages, false>), grid, block, narrow_lds_bytes<256>(waves), st, ev, a);
     else if (a.head_dim == 128)
-        RPA_LAUNCH((rpa_narrow_kernel<128, kNarrowStages>), grid, block, narrow_lds_bytes<128>(waves), st, ev, a);
+        RPA_LAUNCH((rpa_narrow_kernel<128, kNarrowStages, false>), grid, block, narrow_lds_bytes<128>(waves), st, ev, a);
     else
-        RPA_LAUNCH((rpa_narrow_kernel<64, kNarrowStages>), grid, block, narrow_lds_bytes<64>(waves), st, ev, a);
+        RPA_LAUNCH((rpa_narrow_kernel<64, kNarrowStages, false>), grid, block, narrow_lds_bytes<64>(waves), st, ev, a);
+    return (int)hipGetLastError();
+}
+
+int launch_quantize(const void* k_new, const void* v_new, void* k8, void* v8, size_t elems, float inv_k, float inv_v,
+                    int num_cus, void* stream) {
+    const size_t n8 = elems / 8;
+    if (n8 == 0) return 0;
+    const size_t want = (n8 + 255) / 256;
+    const size_t cap = (size_t)num_cus * 8;
+    dim3 grid((unsigned)(want < cap ? want : cap));
+    RPA_LAUNCH(rpa_quantize_kernel, grid, dim3(256), 0, (hipStream_t)stream, (void**)nullptr, (const uint4*)k_new,
+               (const uint4*)v_new, (uint2*)k8, (uint2*)v8, n8, inv_k, inv_v);
     return (int)hipGetLastError();
 }
 

@@ -13,6 +13,8 @@
 #include <algorithm>
 #include <cstdio>
 
+#include <cmath>
+
 #include "rpa_internal.h"
 
 namespace rpa {
@@ -42,6 +44,15 @@ int check_shape(const rpa_shape& s, std::string& err) {
         snprintf(buf, sizeof buf, "page_size %d unsupported (power of two, at least 16)", s.page_size);
         err = buf;
         return RPA_ERR_UNSUPPORTED;
+    }
+    if (s.kv_fp8 != 0 && s.kv_fp8 != 1) {
+        err = "kv_fp8 must be 0 or 1";
+        return RPA_ERR_INVALID_ARG;
+    }
+    if (s.kv_fp8 && !(s.k_scale > 0.f && s.v_scale > 0.f && std::isfinite(s.k_scale) && std::isfinite(s.v_scale) &&
+                      std::isfinite(1.f / s.k_scale) && std::isfinite(1.f / s.v_scale))) {
+        err = "k_scale and v_scale must be positive and finite, and so must their reciprocals";
+        return RPA_ERR_INVALID_ARG;
     }
     if ((int64_t)s.num_pages * s.page_size * s.num_kv_heads * s.head_dim >= ((int64_t)1 << 40)) {
         err = "page pool too large";
@@ -158,7 +169,8 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         const int32_t tq256 = wide_q_tokens(hg, 256);
         for (int32_t r = 0; r < n; ++r) {
             const int32_t lq = cu[r + 1] - cu[r];
-            const bool wide = opt.variant == RPA_VARIANT_PREFILL || (opt.variant != RPA_VARIANT_DECODE && lq > narrow_max_q);
+            const bool wide = !s.kv_fp8 && (opt.variant == RPA_VARIANT_PREFILL ||
+                                            (opt.variant != RPA_VARIANT_DECODE && lq > narrow_max_q));
             if (lq > 0 && wide) tiles256 += ceil_div(lq, tq256);
         }
         wide_rows = tiles256 * s.num_kv_heads >= 4 * (int64_t)std::max(1, num_cus) ? 256 : kWideRows;
@@ -170,7 +182,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         const int32_t lq = cu[r + 1] - cu[r];
         if (lq == 0) continue;
         bool wide;
-        switch (opt.variant) {
+        switch (s.kv_fp8 ? RPA_VARIANT_DECODE : opt.variant) { // the 8-bit cache has the narrow kernel only
         case RPA_VARIANT_DECODE: wide = false; break;
         case RPA_VARIANT_PREFILL: wide = true; break;
         default: wide = lq > narrow_max_q; break;
@@ -197,7 +209,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     const int cus = std::max(1, num_cus);
     const int waves = opt.narrow_waves > 0 ? opt.narrow_waves : narrow_waves(s.num_kv_heads, s.head_dim);
     const int ny = s.num_kv_heads / waves;
-    const int lds_per_wg = waves * narrow_lds_per_wave(s.head_dim);
+    const int lds_per_wg = waves * narrow_lds_per_wave(s.head_dim); // the same with the 8-bit cache: half the row, twice the stages
     // Four resident waves (one 64 KB workgroup at head_dim 128) per CU already
     // stream at the full HBM rate; more only hold LDS that a wide workgroup of a
     // mixed batch can use, and cut sequences into more pieces.

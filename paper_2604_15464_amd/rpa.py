@@ -23,7 +23,7 @@ VARIANT_NAMES = {0: "auto", 1: "decode", 2: "prefill", 3: "mixed"}
 class Shape(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "num_q_heads", "num_kv_heads", "head_dim", "page_size", "max_tokens", "max_seqs",
-        "max_pages_per_seq", "num_pages", "non_causal")]
+        "max_pages_per_seq", "num_pages", "non_causal", "kv_fp8")] + [("k_scale", C.c_float), ("v_scale", C.c_float)]
 
 
 class WorkUnit(C.Structure):
@@ -108,9 +108,11 @@ def _i32(a):
 
 
 def make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs, max_pages_per_seq,
-               num_pages, causal=True) -> Shape:
+               num_pages, causal=True, kv_scales=None) -> Shape:
+    """kv_scales = (k_scale, v_scale) selects the 8-bit (E4M3) cache."""
+    k_scale, v_scale = kv_scales if kv_scales is not None else (0.0, 0.0)
     return Shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs, max_pages_per_seq,
-                 num_pages, 0 if causal else 1)
+                 num_pages, 0 if causal else 1, 0 if kv_scales is None else 1, k_scale, v_scale)
 
 
 def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUTO, kv_chunk=0,
@@ -143,10 +145,10 @@ class RaggedPagedAttention:
     """One context = one static shape on one GPU."""
 
     def __init__(self, num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs,
-                 max_pages_per_seq, num_pages, device=0, causal=True):
+                 max_pages_per_seq, num_pages, device=0, causal=True, kv_scales=None):
         self._lib = lib()
         self.shape = make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs,
-                                max_pages_per_seq, num_pages, causal)
+                                max_pages_per_seq, num_pages, causal, kv_scales)
         self._ctx = C.c_void_p()
         rc = self._lib.rpa_create(C.byref(self._ctx), C.byref(self.shape), int(device))
         if rc != RPA_OK:
@@ -154,10 +156,10 @@ class RaggedPagedAttention:
         self.device = int(device)
 
     @classmethod
-    def for_workload(cls, wl, max_tokens=None, max_seqs=None, device=0, causal=True):
+    def for_workload(cls, wl, max_tokens=None, max_seqs=None, device=0, causal=True, kv_scales=None):
         return cls(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size,
                    max(1, max_tokens or wl.num_tokens), max(1, max_seqs or wl.num_seqs),
-                   wl.max_pages_per_seq, wl.num_pages, device, causal)
+                   wl.max_pages_per_seq, wl.num_pages, device, causal, kv_scales)
 
     def close(self):
         if getattr(self, "_ctx", None) is not None and self._ctx.value:
@@ -225,8 +227,8 @@ class RaggedPagedAttention:
 
     def update_and_attend(self, q, k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, kv_lens,
                           sm_scale, out=None, stream=None):
-        """torch tensors on this context's GPU (bf16; page_table int32);
-        cu_q_lens / kv_lens host arrays.  k_pages / v_pages are updated in
+        """torch tensors on this context's GPU (bf16, the page pools uint8 with
+        the 8-bit cache; page_table int32); cu_q_lens / kv_lens host arrays.  k_pages / v_pages are updated in
         place; returns out.  The call is asynchronous on `stream` (default:
         torch's current stream)."""
         import torch
@@ -237,13 +239,15 @@ class RaggedPagedAttention:
         if cu.shape[0] != n + 1:
             raise ValueError("cu_q_lens must have num_seqs + 1 entries")
         sh = self.shape
-        for name, t, shape in (("q", q, (sh.max_tokens, sh.num_q_heads, sh.head_dim)),
-                               ("k_new", k_new, (sh.max_tokens, sh.num_kv_heads, sh.head_dim)),
-                               ("v_new", v_new, (sh.max_tokens, sh.num_kv_heads, sh.head_dim)),
-                               ("k_pages", k_pages, (sh.num_pages, sh.page_size, sh.num_kv_heads, sh.head_dim)),
-                               ("v_pages", v_pages, (sh.num_pages, sh.page_size, sh.num_kv_heads, sh.head_dim))):
-            if tuple(t.shape) != shape or t.dtype != torch.bfloat16 or not t.is_contiguous() or not t.is_cuda:
-                raise ValueError(f"{name}: expected contiguous cuda bf16 tensor of shape {shape}, "
+        pool_dtype = torch.uint8 if sh.kv_fp8 else torch.bfloat16     # 8-bit cache: E4M3 bytes
+        pool_shape = (sh.num_pages, sh.page_size, sh.num_kv_heads, sh.head_dim)
+        for name, t, shape, dtype in (("q", q, (sh.max_tokens, sh.num_q_heads, sh.head_dim), torch.bfloat16),
+                                      ("k_new", k_new, (sh.max_tokens, sh.num_kv_heads, sh.head_dim), torch.bfloat16),
+                                      ("v_new", v_new, (sh.max_tokens, sh.num_kv_heads, sh.head_dim), torch.bfloat16),
+                                      ("k_pages", k_pages, pool_shape, pool_dtype),
+                                      ("v_pages", v_pages, pool_shape, pool_dtype)):
+            if tuple(t.shape) != shape or t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
+                raise ValueError(f"{name}: expected contiguous cuda {dtype} tensor of shape {shape}, "
                                  f"got {tuple(t.shape)} {t.dtype}")
         if (tuple(page_table.shape) != (sh.max_seqs, sh.max_pages_per_seq) or page_table.dtype != torch.int32
                 or not page_table.is_contiguous() or not page_table.is_cuda):

@@ -27,13 +27,13 @@ from . import workloads as W
 LENGTHS = (512, 1024, 2048, 4096, 8192, 16384, 32768)
 
 
-def time_workload(wl, steps, warmup, causal=True):
+def time_workload(wl, steps, warmup, causal=True, kv_scales=None):
     import torch
 
     dev = torch.device("cuda:0")
-    x = W.materialize(wl, dev, poison=False)
+    x = W.materialize(wl, dev, poison=False, kv_scales=kv_scales)
     table = torch.from_numpy(wl.page_table).to(dev)
-    ctx = rpa.RaggedPagedAttention.for_workload(wl, causal=causal)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl, causal=causal, kv_scales=kv_scales)
     out = torch.empty_like(x["q"])
 
     def call():
@@ -69,8 +69,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--max-len", type=int, default=32768)
     ap.add_argument("--head-dim", type=int, default=128, choices=(128, 256))
+    ap.add_argument("--kv-fp8", action="store_true",
+                    help="decode table with the 8-bit (E4M3) KV cache; bytes counted at one byte per cached element")
     args = ap.parse_args()
     d = args.head_dim
+    if args.kv_fp8:
+        args.decode, args.prefill = True, False      # the 8-bit cache is built for the decode case
+    kv_scales = (1.0 / 64.0, 1.0 / 32.0) if args.kv_fp8 else None
     both = not (args.decode or args.prefill)
     rows = []
     if args.decode or both:
@@ -78,9 +83,10 @@ def main():
             if c > args.max_len:
                 break
             wl = W.uniform(128, 1, c + 1, d=d)
-            dt, k, info = time_workload(wl, args.steps, args.warmup)
-            gbps = wl.algorithmic_bytes() / dt / 1e9
-            rec = {"sweep": "decode", "head_dim": d, "n": 128, "context": c, "page_size": 256,
+            dt, k, info = time_workload(wl, args.steps, args.warmup, kv_scales=kv_scales)
+            gbps = wl.algorithmic_bytes(kv_fp8=args.kv_fp8) / dt / 1e9
+            rec = {"sweep": "decode_fp8_cache" if args.kv_fp8 else "decode", "head_dim": d, "n": 128, "context": c,
+                   "page_size": 256,
                    "latency_us": round(dt * 1e6, 1),
                    "GBps": round(gbps, 1), "pct_of_8TBps": round(gbps / 80.0, 2),
                    "narrow_kernel_us": round(k["narrow_ms"] * 1e3, 1), "combine_kernel_us": round(k["combine_ms"] * 1e3, 1),

@@ -68,13 +68,18 @@ class Workload:
         return (self.kv_lens - self.q_lens).astype(np.int32)
 
     # ---- algorithmic work, used by the benchmark only -------------------
-    def algorithmic_bytes(self) -> int:
+    def algorithmic_bytes(self, kv_fp8: bool = False) -> int:
         """Bytes the method itself must move (Sec. 4.1 throughput formula,
         generalised to ragged lengths): every cached or new K/V element read
-        once, every new K/V element written once, q read and out written."""
+        once, every new K/V element written once, q read and out written.
+        With the 8-bit cache a cached element and a written one are one byte;
+        the new rows still arrive as bf16."""
         d, hkv, hq = self.head_dim, self.num_kv_heads, self.num_q_heads
         kv = int(self.kv_lens.astype(np.int64).sum())
         ql = int(self.q_lens.astype(np.int64).sum())
+        if kv_fp8:
+            ctx = kv - ql
+            return d * (2 * hkv * (ctx * 1 + ql * 2 + ql * 1) + 2 * 2 * ql * hq)
         return 2 * d * ((kv + ql) * 2 * hkv + 2 * ql * hq)
 
     def algorithmic_flops(self) -> int:

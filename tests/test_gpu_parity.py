@@ -22,18 +22,18 @@ def to_f64(t):
 
 def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=True, pad_tokens=0,
              pad_seqs=0, seqs=None, calls=1, narrow_waves=0, units_per_cu=0, wide_rows=0, causal=True,
-             mixed_overlap=0):
+             mixed_overlap=0, kv_scales=None):
     """Run the HIP path and the oracle on the workload; returns a dict of results."""
     dev = torch.device("cuda:0")
     max_tokens = wl.num_tokens + pad_tokens
     max_seqs = wl.num_seqs + pad_seqs
-    x = W.materialize(wl, dev, poison=poison, max_tokens=max(1, max_tokens))
+    x = W.materialize(wl, dev, poison=poison, max_tokens=max(1, max_tokens), kv_scales=kv_scales)
     host = {k: W.bits(v) for k, v in x.items()}
     table = np.full((max(1, max_seqs), wl.max_pages_per_seq), -1, dtype=np.int32)
     table[:wl.num_seqs] = wl.page_table
     table_dev = torch.from_numpy(table).to(dev)
     ctx = rpa.RaggedPagedAttention.for_workload(wl, max_tokens=max(1, max_tokens), max_seqs=max(1, max_seqs),
-                                                causal=causal)
+                                                causal=causal, kv_scales=kv_scales)
     ctx.set_options(variant=variant, kv_chunk=kv_chunk, wide_kv_chunk=wide_kv_chunk, narrow_waves=narrow_waves,
                     units_per_cu=units_per_cu, wide_rows=wide_rows, mixed_overlap=mixed_overlap)
     out = torch.full_like(x["q"], float("nan"))
@@ -46,7 +46,7 @@ def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=T
     ctx.close()
     ref, kp, vp = O.update_and_attend(host["q"], host["k_new"], host["v_new"], host["k_pages"],
                                       host["v_pages"], wl.page_table, wl.cu_q_lens, wl.kv_lens,
-                                      wl.num_seqs, wl.sm_scale, seqs=seqs, causal=causal)
+                                      wl.num_seqs, wl.sm_scale, seqs=seqs, causal=causal, kv_scales=kv_scales)
     return {"out": out, "ref": ref, "kp": W.bits(x["k_pages"]), "vp": W.bits(x["v_pages"]), "kp_ref": kp,
             "vp_ref": vp, "info": info, "sentinel": sentinel, "x": x}
 
@@ -389,6 +389,66 @@ def test_head_dim_256_uniform_prefill_full_size():
     res = run_case(wl, poison=False, seqs=[2])
     check(wl, res, seqs=[2])
     assert res["info"]["variant"] == rpa.VARIANT_PREFILL and res["info"]["wide_rows"] == 128
+    assert torch.isfinite(res["out"][:wl.num_tokens].float()).all()
+
+
+# ---------------------------------------------------------------------------
+# 8-bit KV cache (E4M3 bytes, one scale per tensor; Sec. 3.6).  The cache bytes,
+# i.e. the quantisation of the new rows, must match the oracle bit for bit.
+# ---------------------------------------------------------------------------
+KV_SCALES = (1.0 / 64.0, 1.0 / 32.0)
+
+
+@pytest.mark.parametrize("shape", [(4, 2, 64), (32, 8, 128), (8, 2, 256), (16, 1, 128), (8, 8, 64)])
+@pytest.mark.parametrize("ps", [16, 256])
+def test_fp8_cache_ragged(shape, ps):
+    hq, hkv, d = shape
+    wl = W.ragged(1700 + hq + d, num_seqs=9, hq=hq, hkv=hkv, d=d, ps=ps, max_q=70, max_ctx=500, p_decode=0.5)
+    for chunk in (0, 48):
+        res = run_case(wl, kv_chunk=chunk, kv_scales=KV_SCALES, pad_tokens=5, pad_seqs=1)
+        check(wl, res)
+        assert res["info"]["num_wide_units"] == 0          # the 8-bit cache runs on the narrow kernel
+    res = run_case(wl, kv_scales=KV_SCALES, causal=False)
+    check(wl, res)
+
+
+@pytest.mark.parametrize("scales", [(1.0, 1.0), (0.37, 0.011), (1.0 / 1024, 2.0)])
+def test_fp8_cache_scales(scales):
+    """Scales that are not powers of two; a scale so small that new rows saturate at
+    +-448 (1/1024), one so large that they fall into the subnormals (2.0)."""
+    wl = W.ragged(1800, num_seqs=8, hq=32, hkv=8, d=128, ps=16, max_q=40, max_ctx=300, p_decode=0.5)
+    res = run_case(wl, kv_scales=scales)
+    check(wl, res)
+
+
+def test_fp8_cache_repeated_calls_and_forced_variants():
+    wl = W.ragged(1801, num_seqs=8, hq=32, hkv=8, d=128, ps=32, max_q=60, max_ctx=300)
+    for variant in (rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL, rpa.VARIANT_MIXED):
+        res = run_case(wl, variant=variant, kv_scales=KV_SCALES, calls=3)
+        check(wl, res)
+
+
+def test_fp8_cache_rejects_bad_scales_and_wrong_pool_dtype():
+    wl = W.config(1)
+    for bad in ((0.0, 1.0), (1.0, -1.0), (float("inf"), 1.0), (1.0, float("nan")), (1e-45, 1.0)):
+        with pytest.raises(rpa.RpaError) as e:
+            rpa.RaggedPagedAttention.for_workload(wl, kv_scales=bad)
+        assert e.value.code == rpa.ERR_INVALID_ARG
+    ctx = rpa.RaggedPagedAttention.for_workload(wl, kv_scales=KV_SCALES)
+    x = W.materialize(wl, torch.device("cuda:0"))            # 16-bit pools
+    table = torch.from_numpy(wl.page_table).to("cuda:0")
+    with pytest.raises(ValueError):
+        ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], table, wl.cu_q_lens,
+                              wl.kv_lens, wl.sm_scale)
+    ctx.close()
+
+
+def test_fp8_cache_full_size_decode():
+    """Config 2 with the 8-bit cache: all cache bytes, outputs of sampled sequences."""
+    wl = W.config(2)
+    sample = [0, 17, int(np.argmax(wl.kv_lens)), int(np.argmin(wl.kv_lens)), 255]
+    res = run_case(wl, kv_scales=KV_SCALES, seqs=sample)
+    check(wl, res, seqs=sample)
     assert torch.isfinite(res["out"][:wl.num_tokens].float()).all()
 
 
