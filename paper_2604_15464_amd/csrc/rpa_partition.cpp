@@ -213,7 +213,10 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     // Four resident waves (one 64 KB workgroup at head_dim 128) per CU already
     // stream at the full HBM rate; more only hold LDS that a wide workgroup of a
     // mixed batch can use, and cut sequences into more pieces.
-    const int wgs_per_cu = std::max(1, std::min(kLdsBytesPerCu / lds_per_wg, kNarrowWavesPerCu / waves));
+    // (The 8-bit cache has twice the positions, hence twice the arithmetic, per
+    // byte: eight waves per CU there, measured 6 % faster than four.)
+    const int waves_per_cu = s.kv_fp8 ? 2 * kNarrowWavesPerCu : kNarrowWavesPerCu;
+    const int wgs_per_cu = std::max(1, std::min(kLdsBytesPerCu / lds_per_wg, waves_per_cu / waves));
     const int64_t slots = (int64_t)cus * wgs_per_cu;
     const int oversub = opt.units_per_cu > 0 ? opt.units_per_cu : 1;
     const int64_t want_bins = std::max<int64_t>(1, ceil_div(slots * oversub, ny));
