@@ -65,8 +65,9 @@ typedef struct {
                                   byte nearest (ties to even) to fp32(x) * fp32(1/scale),
                                   saturated to +-448, and attention reads the stored
                                   values for every position, the call's own tokens
-                                  included.  Every batch then runs on the narrow kernel
-                                  (built for the bandwidth-bound decode case).          */
+                                  included.  At head_dim 128 both kernels have this
+                                  variant; at 64 and 256 every batch then runs on the
+                                  narrow kernel (built for the bandwidth-bound decode). */
     float k_scale;             /* scale of k_pages (> 0, finite); read if kv_fp8 only   */
     float v_scale;             /* scale of v_pages                                       */
 } rpa_shape;

@@ -29,6 +29,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
 typedef __attribute__((address_space(3))) short4v lds_short4;
 typedef const __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+typedef __attribute__((ext_vector_type(2))) int int2v;
+typedef __attribute__((address_space(3))) int2v lds_int2;
 
 // The wide kernel lets softmax weights grow to 2^kRescaleGap before it moves a
 // row's reference maximum and rescales the accumulator.
@@ -129,6 +131,10 @@ __device__ __forceinline__ bf16x8 e4m3x8_to_bf16x8(const uint2& r) {
     const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r.y, 1.0f, false);
     const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r.y, 1.0f, true);
     return bf16x8{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+}
+
+__device__ __forceinline__ bf16x8 e4m3x8_to_bf16x8(int2v r) {
+    return e4m3x8_to_bf16x8(make_uint2((uint32_t)r[0], (uint32_t)r[1]));
 }
 
 __device__ __forceinline__ int clamp_page(int page, int num_pages) {
@@ -474,12 +480,20 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 // and chunked prefill; bound by the MFMA and vector pipes together (they do not
 // overlap on this part).
 // ---------------------------------------------------------------------------
-template <int D, int WAVES, int NST>
+//
+// KV8 (head_dim 128 only): K/V tiles of E4M3 bytes (Sec. 3.6), see the narrow
+// kernel.  Rows are 128 bytes, operands are widened to bf16 after the LDS read
+// (the V^T fragment comes from the 8-bit transposing read), the MFMAs and the
+// softmax are the same.
+template <int D, int WAVES, int NST, bool KV8>
 __global__ void __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(D > 128 ? 1 : 2)))
 rpa_wide_kernel(KernelArgs a) {
+    static_assert(!KV8 || D == 128, "the 8-bit wide kernel is built for head_dim 128");
     constexpr int NT = 1; // 32-row groups per wave
-    constexpr int ROWB = D * 2;
-    constexpr int NC = D / 8;
+    constexpr int ROWB = D * (KV8 ? 1 : 2); // bytes of a K/V row of one head
+    constexpr int OROWB = D * 2;            // bytes of a q / out row of one head
+    constexpr int NC = ROWB / 16;           // 16-byte chunks per K/V row
+    constexpr int ONC = OROWB / 16;
     constexpr int TPI = 64 / NC;   // positions per wave-wide load
     constexpr int KT = kWideKvTile;
     constexpr int TILEB = KT * ROWB;
@@ -553,7 +567,12 @@ rpa_wide_kernel(KernelArgs a) {
     // LDS banks repeat every 256 bytes, i.e. every row at D = 128 (every half row at
     // D = 256, where the swizzle leaves the chunk's top bit alone) and every second
     // row at D = 64, where the row's parity already separates two rows.
+    // With 8-bit elements a row is 128 bytes (8 chunks, two rows per bank period)
+    // and operand reads are 8 bytes wide: the row's parity separates two rows, and
+    // bits 1..3 of the row index, permuted, spread the eight rows of a K read and
+    // the position pairs of a transposing V read over the eight chunk positions.
     auto swz = [](int r) {
+        if (KV8) return (((r >> 1) & 1) << 1) | (((r >> 3) & 1) << 2) | ((r >> 2) & 1);
         return D >= 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
     };
     const int ld_tok = lane / NC;
@@ -642,7 +661,9 @@ rpa_wide_kernel(KernelArgs a) {
     uint32_t koff[NKO], voff[NVO][2];
 #pragma unroll
     for (int kk = 0; kk < NKO; ++kk) {
-        koff[kk] = (D <= 128 ? lds_base : 0) + n32 * ROWB + (((2 * kk + h) ^ swz(n32)) * 16);
+        // 8-bit rows: k-step kk is chunk kk, its two 8-element halves go to the wave's two halves
+        koff[kk] = KV8 ? lds_base + n32 * ROWB + ((kk ^ swz(n32)) * 16) + 8 * h
+                       : (D <= 128 ? lds_base : 0) + n32 * ROWB + (((2 * kk + h) ^ swz(n32)) * 16);
         // opaque from here on: otherwise the compiler splits the sum again and
         // re-adds its parts at every read
         if constexpr (D <= 128) asm volatile("" : "+v"(koff[kk]));
@@ -653,6 +674,20 @@ rpa_wide_kernel(KernelArgs a) {
         for (int jb = 0; jb < NVO; ++jb)
 #pragma unroll
             for (int rd = 0; rd < 2; ++rd) {
+                if constexpr (KV8) {
+                    // The 8-bit transposing read works on 16 lanes x 8 bytes = 8 rows of
+                    // 16 bytes: lanes 2k, 2k+1 supply row k, lane i receives byte i of
+                    // rows 0..7.  Row k is made position 8*(k/4) + 4*h + k%4 of the
+                    // k-step (the order the weights are in) and the 16 bytes are dims
+                    // 32*jb + 16*half16 .. +15: lane i then holds dim 32*jb + 16*half16 + i
+                    // for the eight positions of its half of the k-step.  One read per
+                    // (k-step, jb): voff[jb][1] is unused.
+                    const int k = j16 >> 1;
+                    const int r = 8 * (k >> 2) + 4 * h + (k & 3);
+                    const int chunk = 2 * jb + half16;
+                    voff[jb][rd] = lds_base + r * ROWB + ((chunk ^ swz(r)) * 16) + (j16 & 1) * 8;
+                    continue;
+                }
                 const int r = 4 * h + (j16 >> 2) + 8 * rd; // position modulo 16
                 const int chunk = 4 * jb + 2 * half16 + ((j16 & 3) >> 1);
                 voff[jb][rd] = (D <= 128 ? lds_base : 0) + r * ROWB + ((chunk ^ swz(r)) * 16) + (j16 & 1) * 8;
@@ -672,8 +707,14 @@ rpa_wide_kernel(KernelArgs a) {
     constexpr bool IMM = D <= 128;
     const char* lds_ptr = (const char*)smem;
     auto read_k = [&](uint32_t reg, uint32_t rest) __attribute__((always_inline)) {
-        if constexpr (IMM) return *(lds_bf16x8*)(uintptr_t)(reg + rest);
-        else return *(const bf16x8*)(lds_ptr + rest + reg);
+        if constexpr (KV8) {
+            const int2v raw = *(const lds_int2*)(uintptr_t)(reg + rest);
+            return e4m3x8_to_bf16x8(raw);
+        } else if constexpr (IMM) {
+            return (bf16x8) * (lds_bf16x8*)(uintptr_t)(reg + rest);
+        } else {
+            return *(const bf16x8*)(lds_ptr + rest + reg);
+        }
     };
     auto read_v = [&](uint32_t reg, uint32_t rest) __attribute__((always_inline)) {
         if constexpr (IMM) return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(uintptr_t)(reg + rest));
@@ -698,8 +739,13 @@ rpa_wide_kernel(KernelArgs a) {
 #pragma unroll
             for (int jb = 0; jb < DPL; ++jb) {
                 const uint32_t s2 = src + (jb / NVO) * 256;
-                vop[kh][jb].p[0] = read_v(voff[jb % NVO][0], s2);
-                vop[kh][jb].p[1] = read_v(voff[jb % NVO][1], s2);
+                if constexpr (KV8) {
+                    vop[kh][jb].v = e4m3x8_to_bf16x8(
+                        __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_int2*)(uintptr_t)(voff[jb][0] + s2)));
+                } else {
+                    vop[kh][jb].p[0] = read_v(voff[jb % NVO][0], s2);
+                    vop[kh][jb].p[1] = read_v(voff[jb % NVO][1], s2);
+                }
             }
         };
         // ---- S^T = K Q^T (Alg. 1: S <- C_q C_k^T) --------------------------------
@@ -876,9 +922,9 @@ rpa_wide_kernel(KernelArgs a) {
             // Rows go through this wave's slice of the (now idle) LDS ring so that
             // the global stores are whole 256-byte rows, 16 lanes per row.  The
             // loop's last barrier guarantees nobody still reads the ring.
-            constexpr int SROW = ROWB + 16; // padded row: conflict-free 8-byte writes
+            constexpr int SROW = OROWB + 16; // padded row: conflict-free 8-byte writes
             char* stage = (char*)smem + (size_t)(NT * wave + nt) * 32 * SROW;
-            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+            const float inv = l_tot > 0.f ? a.out_scale / l_tot : 0.f; // out_scale: V scale of an 8-bit cache, else 1
             // accumulator element v of block jb is dim 32*jb + 8*(v/4) + 4*h + v%4
 #pragma unroll
             for (int jb = 0; jb < DPL; ++jb)
@@ -896,8 +942,9 @@ rpa_wide_kernel(KernelArgs a) {
             for (int jb = 0; jb < DPL; ++jb)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
-                    float4 w = make_float4(o[nt][jb][4 * q4], o[nt][jb][4 * q4 + 1], o[nt][jb][4 * q4 + 2],
-                                           o[nt][jb][4 * q4 + 3]);
+                    const float os = KV8 ? a.out_scale : 1.f; // partial sums carry the V scale
+                    float4 w = make_float4(o[nt][jb][4 * q4] * os, o[nt][jb][4 * q4 + 1] * os, o[nt][jb][4 * q4 + 2] * os,
+                                           o[nt][jb][4 * q4 + 3] * os);
                     *(float4*)(po + 32 * jb + 8 * q4 + 4 * h) = w;
                 }
             if (h == 0) {
@@ -908,19 +955,19 @@ rpa_wide_kernel(KernelArgs a) {
     }
 
     if (u.part_row < 0 && !(a.ablate & 256)) {
-        constexpr int SROW = ROWB + 16;
-        constexpr int RPI = 64 / NC; // rows per wave-wide 16-byte store
+        constexpr int SROW = OROWB + 16;
+        constexpr int RPI = 64 / ONC; // rows per wave-wide 16-byte store
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const char* stage = (const char*)smem + (size_t)(NT * wave + nt) * 32 * SROW;
 #pragma unroll
             for (int i = 0; i < 32 / RPI; ++i) {
-                const int r = i * RPI + lane / NC;
+                const int r = i * RPI + lane / ONC;
                 const int rho = 32 * (NT * wave + nt) + r;
                 const int t_r = rho & tq_mask, h_r = rho >> tq_log2;
-                const uint4 w = *(const uint4*)(stage + r * SROW + (lane % NC) * 16);
+                const uint4 w = *(const uint4*)(stage + r * SROW + (lane % ONC) * 16);
                 if (t_r < u.n_q)
-                    store16_streaming(a.out + ((size_t)(u.q_start + t_r) * Hq + g * hg + h_r) * D + (lane % NC) * 8, w);
+                    store16_streaming(a.out + ((size_t)(u.q_start + t_r) * Hq + g * hg + h_r) * D + (lane % ONC) * 8, w);
             }
         }
     }
@@ -931,12 +978,12 @@ rpa_wide_kernel(KernelArgs a) {
         for (int t = threadIdx.x / NC; t < u.n_q; t += (64 * WAVES) / NC) {
             const int pos = ctx + u.q_pos0 + t;
             const int page = clamp_page(pt_row[pos >> ps_log2], num_pages);
-            const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * D + c * 8;
-            const size_t dst = ((((size_t)page << ps_log2) + (pos & ps_mask)) * Hkv + g) * D + c * 8;
-            const uint4 kk = *(const uint4*)(a.k_new + src);
-            const uint4 vv = *(const uint4*)(a.v_new + src);
-            store16_streaming(a.k_pages + dst, kk);
-            store16_streaming(a.v_pages + dst, vv);
+            const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * ROWB + c * 16; // bytes
+            const size_t dst = ((((size_t)page << ps_log2) + (pos & ps_mask)) * Hkv + g) * ROWB + c * 16;
+            const uint4 kk = *(const uint4*)(k_new + src);
+            const uint4 vv = *(const uint4*)(v_new + src);
+            store16_streaming((char*)a.k_pages + dst, kk);
+            store16_streaming((char*)a.v_pages + dst, vv);
         }
     }
 }
@@ -1046,6 +1093,12 @@ static size_t wide_lds_bytes(int stages) {
     return (size_t)stages * 2 * kWideKvTile * D * 2;
 }
 
+// 8-bit K/V rows: the ring is half the size and the output staging of the
+// epilogue (32 padded bf16 rows per wave) is what sizes the allocation.
+static size_t wide_lds_bytes_kv8(int stages, int waves) {
+    return std::max((size_t)stages * 2 * kWideKvTile * 128, (size_t)waves * 32 * (128 * 2 + 16));
+}
+
 int kernels_init(int device, std::string& err) {
     (void)device;
     hipError_t e;
@@ -1066,23 +1119,29 @@ int kernels_init(int device, std::string& err) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)narrow_lds_bytes<256>(kLdsBytesPerCu / narrow_lds_per_wave(256)));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 8, kWideStages>,
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 8, kWideStages, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<128>(kWideStages));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 8, kWideStages>,
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 8, kWideStages, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<64>(kWideStages));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 4, kWideStagesHalf>,
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 4, kWideStagesHalf, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<128>(kWideStagesHalf));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 4, kWideStagesHalf>,
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 4, kWideStagesHalf, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<64>(kWideStagesHalf));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 8, kWideStages, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes_kv8(kWideStages, 8));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 4, kWideStagesHalf, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes_kv8(kWideStagesHalf, 4));
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<256, kNarrowStages, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)narrow_lds_bytes<256>(kLdsBytesPerCu / narrow_lds_per_wave(256)));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<256, 4, kWideStagesHalf>,
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<256, 4, kWideStagesHalf, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<256>(kWideStagesHalf));
     if (e != hipSuccess) {
         err = std::string("hipFuncSetAttribute: ") + hipGetErrorString(e);
@@ -1148,25 +1207,33 @@ int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev) {
     // but the 512-register shape that needs is beyond what the compiler allocates
     // without spilling.
     const bool half = (a.hg << a.wide_tq_log2) == 128; // 128-row tiles: four waves, two workgroups per CU
-    if (a.head_dim == 256) {
+    if (a.kv_fp8) {
+        if (a.head_dim != 128) return (int)hipErrorInvalidValue; // other sizes run on the narrow kernel
+        if (half)
+            RPA_LAUNCH((rpa_wide_kernel<128, 4, kWideStagesHalf, true>), grid, dim3(256),
+                       wide_lds_bytes_kv8(kWideStagesHalf, 4), st, ev, a);
+        else
+            RPA_LAUNCH((rpa_wide_kernel<128, 8, kWideStages, true>), grid, dim3(512), wide_lds_bytes_kv8(kWideStages, 8),
+                       st, ev, a);
+    } else if (a.head_dim == 256) {
         // one shape only: 128 rows, four waves with the whole register file each, and
         // a ring of two 64 KB stages (one workgroup per CU)
         if (!half) return (int)hipErrorInvalidValue;
-        RPA_LAUNCH((rpa_wide_kernel<256, 4, kWideStagesHalf>), grid, dim3(256), wide_lds_bytes<256>(kWideStagesHalf),
+        RPA_LAUNCH((rpa_wide_kernel<256, 4, kWideStagesHalf, false>), grid, dim3(256), wide_lds_bytes<256>(kWideStagesHalf),
                    st, ev, a);
     } else if (a.head_dim == 128) {
         if (half)
-            RPA_LAUNCH((rpa_wide_kernel<128, 4, kWideStagesHalf>), grid, dim3(256),
+            RPA_LAUNCH((rpa_wide_kernel<128, 4, kWideStagesHalf, false>), grid, dim3(256),
                        wide_lds_bytes<128>(kWideStagesHalf), st, ev, a);
         else
-            RPA_LAUNCH((rpa_wide_kernel<128, 8, kWideStages>), grid, dim3(512), wide_lds_bytes<128>(kWideStages), st,
+            RPA_LAUNCH((rpa_wide_kernel<128, 8, kWideStages, false>), grid, dim3(512), wide_lds_bytes<128>(kWideStages), st,
                        ev, a);
     } else {
         if (half)
-            RPA_LAUNCH((rpa_wide_kernel<64, 4, kWideStagesHalf>), grid, dim3(256),
+            RPA_LAUNCH((rpa_wide_kernel<64, 4, kWideStagesHalf, false>), grid, dim3(256),
                        wide_lds_bytes<64>(kWideStagesHalf), st, ev, a);
         else
-            RPA_LAUNCH((rpa_wide_kernel<64, 8, kWideStages>), grid, dim3(512), wide_lds_bytes<64>(kWideStages), st,
+            RPA_LAUNCH((rpa_wide_kernel<64, 8, kWideStages, false>), grid, dim3(512), wide_lds_bytes<64>(kWideStages), st,
                        ev, a);
     }
     return (int)hipGetLastError();

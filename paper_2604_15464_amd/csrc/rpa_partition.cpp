@@ -158,6 +158,8 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
 
     // ---- regime per sequence (Sec. 3.4) ---------------------------------
     const int64_t narrow_max_q = 2 * (int64_t)tq_narrow; // up to two narrow tiles
+    // the 8-bit cache has a wide kernel at head_dim 128 only; elsewhere every batch runs narrow
+    const bool narrow_only = s.kv_fp8 && s.head_dim != 128;
     // Wide tile height: 256 rows (half the K/V staging traffic per row, no stall
     // on the loads) when that still gives every CU several workgroups, else 128
     // rows (twice as many, independent workgroups).
@@ -169,8 +171,8 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         const int32_t tq256 = wide_q_tokens(hg, 256);
         for (int32_t r = 0; r < n; ++r) {
             const int32_t lq = cu[r + 1] - cu[r];
-            const bool wide = !s.kv_fp8 && (opt.variant == RPA_VARIANT_PREFILL ||
-                                            (opt.variant != RPA_VARIANT_DECODE && lq > narrow_max_q));
+            const bool wide = !narrow_only && (opt.variant == RPA_VARIANT_PREFILL ||
+                                               (opt.variant != RPA_VARIANT_DECODE && lq > narrow_max_q));
             if (lq > 0 && wide) tiles256 += ceil_div(lq, tq256);
         }
         wide_rows = tiles256 * s.num_kv_heads >= 4 * (int64_t)std::max(1, num_cus) ? 256 : kWideRows;
@@ -182,7 +184,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         const int32_t lq = cu[r + 1] - cu[r];
         if (lq == 0) continue;
         bool wide;
-        switch (s.kv_fp8 ? RPA_VARIANT_DECODE : opt.variant) { // the 8-bit cache has the narrow kernel only
+        switch (narrow_only ? RPA_VARIANT_DECODE : opt.variant) {
         case RPA_VARIANT_DECODE: wide = false; break;
         case RPA_VARIANT_PREFILL: wide = true; break;
         default: wide = lq > narrow_max_q; break;
@@ -207,6 +209,22 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     // one bin and walks its pieces back to back, so every workgroup streams the
     // same number of KV tiles and there is no tail.
     const int cus = std::max(1, num_cus);
+    int64_t total_tiles = 0; // KV volume of all narrow tiles, in 16-position tiles
+    for (const Tile& t : tiles)
+        if (!t.wide) total_tiles += ceil_div(t.kv_hi, kNarrowKvTile);
+
+    // Narrow and wide kernels side by side when both parts are worth more than the
+    // extra stream packets (about 10 us): the narrow kernel is bound by HBM, the
+    // wide one by the matrix and vector pipes, and a CU holds a workgroup of each.
+    bool concurrent = false;
+    if (any_narrow && any_wide && opt.mixed_overlap != 1) {
+        const double kv_elem_bytes = s.kv_fp8 ? 1.0 : 2.0;
+        const double narrow_bytes =
+            (double)total_tiles * kNarrowKvTile * s.num_kv_heads * s.head_dim * 2.0 * kv_elem_bytes;
+        const double wide_flops = (double)work_wide * wide_q_tokens(hg, wide_rows) * 4.0 * s.num_q_heads * s.head_dim;
+        concurrent = opt.mixed_overlap == 2 || (narrow_bytes >= 128e6 && wide_flops >= 2e10);
+    }
+
     const int waves = opt.narrow_waves > 0 ? opt.narrow_waves : narrow_waves(s.num_kv_heads, s.head_dim);
     const int ny = s.num_kv_heads / waves;
     const int lds_per_wg = waves * narrow_lds_per_wave(s.head_dim); // the same with the 8-bit cache: half the row, twice the stages
@@ -214,28 +232,16 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     // stream at the full HBM rate; more only hold LDS that a wide workgroup of a
     // mixed batch can use, and cut sequences into more pieces.
     // (The 8-bit cache has twice the positions, hence twice the arithmetic, per
-    // byte: eight waves per CU there, measured 6 % faster than four.)
-    const int waves_per_cu = s.kv_fp8 ? 2 * kNarrowWavesPerCu : kNarrowWavesPerCu;
+    // byte: eight waves per CU there, measured 6 % faster than four, unless a wide
+    // workgroup is to fit beside them.)
+    const int waves_per_cu = (s.kv_fp8 && !concurrent) ? 2 * kNarrowWavesPerCu : kNarrowWavesPerCu;
     const int wgs_per_cu = std::max(1, std::min(kLdsBytesPerCu / lds_per_wg, waves_per_cu / waves));
     const int64_t slots = (int64_t)cus * wgs_per_cu;
     const int oversub = opt.units_per_cu > 0 ? opt.units_per_cu : 1;
     const int64_t want_bins = std::max<int64_t>(1, ceil_div(slots * oversub, ny));
-    int64_t total_tiles = 0; // KV volume of all narrow tiles, in 16-position tiles
-    for (const Tile& t : tiles)
-        if (!t.wide) total_tiles += ceil_div(t.kv_hi, kNarrowKvTile);
     const int64_t min_bin = 8; // 128 KV positions: below that a bin is not worth a workgroup
     int64_t per_bin = std::max<int64_t>(min_bin, ceil_div(total_tiles, want_bins));
     const int64_t max_piece = opt.kv_chunk > 0 ? ceil_div(opt.kv_chunk, kNarrowKvTile) : ((int64_t)1 << 40);
-
-    // Narrow and wide kernels side by side when both parts are worth more than the
-    // extra stream packets (about 10 us): the narrow kernel is bound by HBM, the
-    // wide one by the matrix and vector pipes, and a CU holds a workgroup of each.
-    bool concurrent = false;
-    if (any_narrow && any_wide && opt.mixed_overlap != 1) {
-        const double narrow_bytes = (double)total_tiles * kNarrowKvTile * s.num_kv_heads * s.head_dim * 4.0;
-        const double wide_flops = (double)work_wide * wide_q_tokens(hg, wide_rows) * 4.0 * s.num_q_heads * s.head_dim;
-        concurrent = opt.mixed_overlap == 2 || (narrow_bytes >= 128e6 && wide_flops >= 2e10);
-    }
 
     int64_t chunk_w;
     if (opt.wide_kv_chunk > 0) {

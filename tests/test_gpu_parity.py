@@ -405,11 +405,51 @@ def test_fp8_cache_ragged(shape, ps):
     hq, hkv, d = shape
     wl = W.ragged(1700 + hq + d, num_seqs=9, hq=hq, hkv=hkv, d=d, ps=ps, max_q=70, max_ctx=500, p_decode=0.5)
     for chunk in (0, 48):
-        res = run_case(wl, kv_chunk=chunk, kv_scales=KV_SCALES, pad_tokens=5, pad_seqs=1)
+        res = run_case(wl, kv_chunk=chunk, wide_kv_chunk=64 if chunk else 0, kv_scales=KV_SCALES, pad_tokens=5,
+                       pad_seqs=1)
         check(wl, res)
-        assert res["info"]["num_wide_units"] == 0          # the 8-bit cache runs on the narrow kernel
+        if d != 128:                                       # a wide kernel for the 8-bit cache exists at head_dim 128 only
+            assert res["info"]["num_wide_units"] == 0
+        else:
+            assert res["info"]["num_wide_units"] > 0
     res = run_case(wl, kv_scales=KV_SCALES, causal=False)
     check(wl, res)
+
+
+@pytest.mark.parametrize("wide_rows", [128, 256])
+@pytest.mark.parametrize("hq,hkv", [(32, 8), (16, 2), (8, 8), (16, 1)])
+def test_fp8_cache_wide_kernel(wide_rows, hq, hkv):
+    """head_dim 128: prefill and chunked prefill over the 8-bit cache, both tile
+    heights, cached context and new tokens mixed in one tile, KV splits."""
+    wl = W.ragged(1900 + hq + hkv, num_seqs=7, hq=hq, hkv=hkv, d=128, ps=16, max_q=300, max_ctx=500, p_decode=0.1)
+    for variant, chunk in ((rpa.VARIANT_PREFILL, 0), (rpa.VARIANT_PREFILL, 64), (rpa.VARIANT_AUTO, 0)):
+        res = run_case(wl, variant=variant, wide_kv_chunk=chunk, wide_rows=wide_rows, kv_scales=KV_SCALES)
+        check(wl, res)
+        assert res["info"]["num_wide_units"] > 0
+    res = run_case(wl, variant=rpa.VARIANT_PREFILL, wide_rows=wide_rows, kv_scales=KV_SCALES, causal=False)
+    check(wl, res)
+
+
+def test_fp8_cache_mixed_batch_side_by_side():
+    wl = W.ragged(1950, num_seqs=24, hq=32, hkv=8, d=128, ps=16, max_q=200, max_ctx=700, p_decode=0.5)
+    for overlap in (2, 1):
+        res = run_case(wl, kv_scales=KV_SCALES, mixed_overlap=overlap, calls=5)
+        check(wl, res)
+        assert res["info"]["concurrent"] == (1 if overlap == 2 else 0)
+
+
+def test_fp8_cache_full_size_prefill_and_mixed():
+    wl = W.config(3)
+    res = run_case(wl, poison=False, kv_scales=KV_SCALES, seqs=[1, 6])
+    check(wl, res, seqs=[1, 6])
+    assert res["info"]["variant"] == rpa.VARIANT_PREFILL
+    wl = W.config(4)
+    chunks = np.nonzero(wl.q_lens > 1)[0].tolist()
+    dec = np.nonzero(wl.q_lens == 1)[0]
+    sample = chunks[:2] + dec[[0, -1]].tolist()
+    res = run_case(wl, kv_scales=KV_SCALES, seqs=sample)
+    check(wl, res, seqs=sample)
+    assert res["info"]["variant"] == rpa.VARIANT_MIXED and res["info"]["concurrent"] == 1
 
 
 @pytest.mark.parametrize("scales", [(1.0, 1.0), (0.37, 0.011), (1.0 / 1024, 2.0)])
