@@ -32,6 +32,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+KV_SCALES = (1.0 / 64.0, 1.0 / 32.0)   # 8-bit cache block: N(0,1) / scale stays inside +-448
+
+
 def time_steps(ctx, x, table, wl, steps, warmup):
     """Returns (seconds for `steps` whole steps, per-kernel milliseconds of a
     second pass of `steps` steps).  The first pass is the throughput figure and
@@ -136,6 +139,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-mixed", action="store_true")
+    ap.add_argument("--no-fp8", action="store_true")
     ap.add_argument("--copy-bytes", type=int, default=1 << 30,
                     help="size of the plain copy that calibrates HBM counters (0 = skip)")
     args = ap.parse_args()
@@ -259,6 +263,28 @@ def main():
                           "combine": round(prof4["combine_ms"] / n4, 5)},
         }
         del x4, table4
+        torch.cuda.empty_cache()
+
+    # ---- decode over the 8-bit (E4M3, per-tensor scale) cache ---------------------------
+    if not args.no_fp8:
+        x8 = W.materialize(wl, dev, poison=False, kv_scales=KV_SCALES)
+        table8 = torch.from_numpy(wl.page_table).to(dev)
+        ctx8 = rpa.RaggedPagedAttention.for_workload(wl, kv_scales=KV_SCALES)
+        dt8, prof8, _ = time_steps(ctx8, x8, table8, wl, args.steps, args.warmup)
+        ctx8.close()
+        n8 = max(1, prof8["calls"])
+        b8 = wl.algorithmic_bytes(kv_fp8=True)
+        log(f"decode, 8-bit cache: {dt8 / args.steps * 1e6:.1f} us/step, kernel {prof8['narrow_ms'] / n8 * 1e3:.1f} us")
+        result["decode_fp8_cache"] = {
+            "metric": "decode HBM GB/s, KV cache of E4M3 bytes", "value": round(b8 / (dt8 / args.steps) / 1e9, 1),
+            "unit": "GB/s", "steps": args.steps, "ms_per_step": round(dt8 / args.steps * 1e3, 5),
+            "config": {"workload": "the headline decode workload with rpa_shape.kv_fp8 = 1 (k_new / v_new bf16, "
+                                   "quantised on the way in)", "algorithmic_bytes_per_step": b8,
+                       "k_scale": KV_SCALES[0], "v_scale": KV_SCALES[1]},
+            "speedup_over_bf16_cache": round(dt / dt8, 3),
+            "kernel_ms": {"narrow": round(prof8["narrow_ms"] / n8, 5), "combine": round(prof8["combine_ms"] / n8, 5)},
+        }
+        del x8, table8
         torch.cuda.empty_cache()
 
     # ---- CPU oracle baseline ---------------------------------------------------------
