@@ -17,7 +17,7 @@ constexpr int kWideRows = 128;    // default query rows per wide tile = (128 / h
 constexpr int kWideKvTile = 64;   // KV positions per wide pipeline stage
 constexpr int kMaxWaves = 8;      // waves per narrow workgroup (one KV head each)
 constexpr int kNarrowWavesPerCu = 4; // resident narrow waves per CU: enough to saturate HBM (measured), leaves LDS for a wide workgroup
-constexpr int kNarrowStages = 2;   // LDS ring depth of a narrow wave
+constexpr int kNarrowStages = 2;   // LDS ring depth of a narrow wave (twice that with the 8-bit cache: same bytes)
 constexpr int kWideStages = 3;     // LDS ring depth of a 256-row wide workgroup
 constexpr int kWideStagesHalf = 2; // ... of a 128-row one (64 KB: two workgroups per CU)
 constexpr int kLdsBytesPerCu = 160 * 1024;

@@ -474,7 +474,9 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 // heads of one KV head (the paper's stacking of a group's heads against one K/V
 // operand, Sec. 3.1.2).  Every wave owns 32 rows; 32x32x16 MFMA.  Two shapes are
 // built: 8 waves (256 rows, one workgroup per CU, ring of 3 stages) and 4 waves
-// (128 rows, two independent workgroups per CU, ring of 2 stages).  K/V tiles of
+// (128 rows, two independent workgroups per CU, ring of 2 stages); head_dim 256
+// has the 4-wave shape only, one workgroup per CU, each wave alone on its SIMD
+// with the whole register file.  K/V tiles of
 // 64 positions are staged once per workgroup in LDS by asynchronous 16-byte
 // loads (every wave brings its share), one barrier per tile.  Used for prefill
 // and chunked prefill; bound by the MFMA and vector pipes together (they do not
@@ -844,18 +846,12 @@ rpa_wide_kernel(KernelArgs a) {
                             __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[kh][jb].v, pop[nt][kh], o[nt][jb], 0, 0, 0);
         }
     };
-    // The eight-wave shape runs the two halves through one copy of the code (a real
-    // loop), the four-wave shape through two copies (the LDS offsets of a half are
-    // then immediates); which is faster was measured, not derived.
+    // The two halves run through two copies of the code, so that the half's offset
+    // is a compile-time constant in every LDS read; the second half is skipped when
+    // it lies above the diagonal of every row of the wave.
     auto compute_tile = [&](uint32_t ldsK, uint32_t ldsV, int pos0) __attribute__((always_inline)) {
-        const int nh = (pos0 + 32 <= wave_limit) ? 2 : 1;
-        if constexpr (WAVES == 4 || D <= 128) {
-            compute_half(ldsK, ldsV, pos0, 0);
-            if (nh == 2) compute_half(ldsK, ldsV, pos0, 1);
-        } else {
-#pragma unroll 1
-            for (int mt = 0; mt < nh; ++mt) compute_half(ldsK, ldsV, pos0, mt);
-        }
+        compute_half(ldsK, ldsV, pos0, 0);
+        if (pos0 + 32 <= wave_limit) compute_half(ldsK, ldsV, pos0, 1);
     };
 
     // Ring of NST stages: tile t+NST-1 is requested before tile t is consumed, so
