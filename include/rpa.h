@@ -219,8 +219,18 @@ const char* rpa_last_error(const rpa_ctx* ctx);
 int rpa_plan_info(const rpa_ctx* ctx, rpa_plan_stats* out);
 
 /* Set the tuning knobs for later calls (tests and tuning); NULL restores the
- * defaults.                                                                   */
+ * defaults.  The set applies to every batch, whatever its regime, and replaces
+ * any per-regime sets.                                                         */
 int rpa_set_options(rpa_ctx* ctx, const rpa_options* opt);
+
+/* One set of knobs per regime (Sec. 3.1.4 / 3.4: separate block sizes for
+ * decode-only, prefill-only and mixed batches, tuned offline and applied at
+ * bring-up).  `regime` is RPA_VARIANT_DECODE, _PREFILL or _MIXED: the regime a
+ * batch is classified into from its lengths; `opt` is then used for the batches
+ * of that regime (NULL: the defaults); opt->variant must be RPA_VARIANT_AUTO or
+ * equal to `regime`.  Regimes never set keep the set of rpa_set_options().
+ * python -m paper_2604_15464_amd.tune writes such a table for a shape.          */
+int rpa_set_regime_options(rpa_ctx* ctx, int32_t regime, const rpa_options* opt);
 
 /* Kernel timing for benchmarks (not part of the paper's method).  While enabled,
  * every call attaches a start and a stop HIP event to each kernel it launches

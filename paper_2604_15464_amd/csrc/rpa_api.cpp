@@ -43,7 +43,9 @@ struct rpa_ctx {
     std::vector<ProfEvents> prof;
     int prof_count = 0;
     rpa_shape shape{};
-    rpa_options opt{};
+    rpa_options opt{};             // set of rpa_set_options()
+    rpa_options regime_opt[4]{};   // per-regime sets, indexed by rpa_variant
+    bool regime_set[4] = {false, false, false, false};
     int device = 0;
     int num_cus = 0;
     int max_units = 0;
@@ -198,6 +200,28 @@ extern "C" int rpa_set_options(rpa_ctx* c, const rpa_options* opt) {
         o.mixed_overlap < 0 || o.mixed_overlap > 2 || !options_fit_shape(c->shape, o))
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: bad value");
     c->opt = o;
+    for (bool& b : c->regime_set) b = false;
+    return RPA_OK;
+}
+
+extern "C" int rpa_set_regime_options(rpa_ctx* c, int32_t regime, const rpa_options* opt) {
+    if (!c) return RPA_ERR_INVALID_ARG;
+    if (regime < RPA_VARIANT_DECODE || regime > RPA_VARIANT_MIXED)
+        return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_regime_options: regime must be decode, prefill or mixed");
+    rpa_options o{};
+    if (opt) o = *opt;
+    if (o.variant != RPA_VARIANT_AUTO && o.variant != regime)
+        return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_regime_options: variant must be auto or the regime itself");
+    // the same checks as rpa_set_options
+    const rpa_options keep = c->opt;
+    bool keep_set[4];
+    for (int i = 0; i < 4; ++i) keep_set[i] = c->regime_set[i];
+    const int rc = rpa_set_options(c, &o);
+    c->opt = keep;
+    for (int i = 0; i < 4; ++i) c->regime_set[i] = keep_set[i];
+    if (rc != RPA_OK) return rc;
+    c->regime_opt[regime] = o;
+    c->regime_set[regime] = true;
     return RPA_OK;
 }
 
@@ -308,7 +332,13 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_update_and_attend: sm_scale must be finite and positive");
 
     std::string msg;
-    int rc = build_plan(c->shape, cu_q_lens, kv_lens, num_seqs, c->opt, c->num_cus, c->partial_row_cap, c->plan, msg);
+    if (num_seqs < 0 || num_seqs > c->shape.max_seqs || !cu_q_lens || !kv_lens)
+        return fail(c, num_seqs < 0 || num_seqs > c->shape.max_seqs ? RPA_ERR_BAD_LENGTHS : RPA_ERR_INVALID_ARG,
+                    "rpa_update_and_attend: num_seqs outside [0, max_seqs] or a length array is null");
+    // the regime's own set of knobs, if one was given (Sec. 3.1.4)
+    const int regime = classify_batch(c->shape, cu_q_lens, num_seqs);
+    const rpa_options& opt_used = c->regime_set[regime] ? c->regime_opt[regime] : c->opt;
+    int rc = build_plan(c->shape, cu_q_lens, kv_lens, num_seqs, opt_used, c->num_cus, c->partial_row_cap, c->plan, msg);
     if (rc != RPA_OK) return fail(c, rc, msg);
     Plan& plan = c->plan;
     const size_t n_narrow = plan.narrow.size(), n_wide = plan.wide.size(), n_items = plan.items.size();
@@ -368,7 +398,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     a.num_pages = c->shape.num_pages;
     a.wide_tq_log2 = __builtin_ctz((unsigned)wide_q_tokens(a.hg, plan.stats.wide_rows));
     a.scale_log2 = sm_scale * 1.4426950408889634f;
-    a.ablate = c->opt.ablate;
+    a.ablate = opt_used.ablate;
     a.causal = c->shape.non_causal ? 0 : 1;
     a.kv_fp8 = c->shape.kv_fp8;
     a.out_scale = 1.f;

@@ -33,6 +33,11 @@ struct Plan {
 // Validates shape; returns RPA_OK or an error with a message.
 int check_shape(const rpa_shape& s, std::string& err);
 
+// Regime of a batch from its query lengths alone (what AUTO would report):
+// DECODE if no sequence is long enough for the wide kernel, PREFILL if all
+// non-empty ones are, else MIXED.  Lengths are not validated here.
+int classify_batch(const rpa_shape& s, const int32_t* cu_q_lens, int32_t num_seqs);
+
 // Validates the lengths and builds the work partition.
 int build_plan(const rpa_shape& s, const int32_t* cu_q_lens, const int32_t* kv_lens,
                int32_t num_seqs, const rpa_options& opt, int num_cus, int64_t partial_row_cap,

@@ -61,6 +61,19 @@ int check_shape(const rpa_shape& s, std::string& err) {
     return RPA_OK;
 }
 
+int classify_batch(const rpa_shape& s, const int32_t* cu, int32_t n) {
+    const int hg = s.num_q_heads / s.num_kv_heads;
+    const int64_t narrow_max_q = 2 * (int64_t)narrow_q_tokens(hg);
+    const bool narrow_only = s.kv_fp8 && s.head_dim != 128;
+    bool any_narrow = false, any_wide = false;
+    for (int32_t r = 0; r < n; ++r) {
+        const int64_t lq = (int64_t)cu[r + 1] - cu[r];
+        if (lq <= 0) continue;
+        ((!narrow_only && lq > narrow_max_q) ? any_wide : any_narrow) = true;
+    }
+    return any_wide ? (any_narrow ? RPA_VARIANT_MIXED : RPA_VARIANT_PREFILL) : RPA_VARIANT_DECODE;
+}
+
 namespace {
 
 struct Tile {

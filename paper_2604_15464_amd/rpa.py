@@ -62,7 +62,8 @@ class RpaError(RuntimeError):
 _lib = None
 
 EXPORTS = ("rpa_create", "rpa_destroy", "rpa_update_and_attend", "rpa_last_error", "rpa_plan_info",
-           "rpa_set_options", "rpa_plan_host", "rpa_profile_enable", "rpa_profile_read", "rpa_copy_probe")
+           "rpa_set_options", "rpa_set_regime_options", "rpa_plan_host", "rpa_profile_enable", "rpa_profile_read",
+           "rpa_copy_probe")
 
 
 def lib():
@@ -87,6 +88,8 @@ def lib():
     l.rpa_plan_info.restype = C.c_int
     l.rpa_set_options.argtypes = [C.c_void_p, C.POINTER(Options)]
     l.rpa_set_options.restype = C.c_int
+    l.rpa_set_regime_options.argtypes = [C.c_void_p, C.c_int32, C.POINTER(Options)]
+    l.rpa_set_regime_options.restype = C.c_int
     l.rpa_profile_enable.argtypes = [C.c_void_p, C.c_int]
     l.rpa_profile_enable.restype = C.c_int
     l.rpa_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float),
@@ -113,6 +116,12 @@ def make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_s
     k_scale, v_scale = kv_scales if kv_scales is not None else (0.0, 0.0)
     return Shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs, max_pages_per_seq,
                  num_pages, 0 if causal else 1, 0 if kv_scales is None else 1, k_scale, v_scale)
+
+
+def shape_key(shape: Shape) -> str:
+    """Key of a shape in a tuning table: what the launch shapes depend on."""
+    return (f"hq{shape.num_q_heads}_hkv{shape.num_kv_heads}_d{shape.head_dim}_ps{shape.page_size}"
+            f"_{'fp8' if shape.kv_fp8 else 'bf16'}{'_nomask' if shape.non_causal else ''}")
 
 
 def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUTO, kv_chunk=0,
@@ -179,6 +188,35 @@ class RaggedPagedAttention:
         rc = self._lib.rpa_set_options(self._ctx, C.byref(opt))
         if rc != RPA_OK:
             raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())
+
+    def set_regime_options(self, regime, **knobs):
+        """Knobs used for the batches of one regime (VARIANT_DECODE / _PREFILL /
+        _MIXED); no knobs = that regime's defaults.  See rpa_set_regime_options."""
+        names = [n for n, _ in Options._fields_]
+        opt = Options(*[int(knobs.pop(n, 0)) for n in names])
+        if knobs:
+            raise TypeError(f"unknown knobs {sorted(knobs)}")
+        rc = self._lib.rpa_set_regime_options(self._ctx, int(regime), C.byref(opt))
+        if rc != RPA_OK:
+            raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())
+
+    def load_tuning(self, table):
+        """Apply a table written by `python -m paper_2604_15464_amd.tune` (a dict or a
+        JSON file path): the entry for this context's shape, one set of knobs per
+        regime.  Returns the entry's key, or None if the table has none."""
+        import json
+
+        if not isinstance(table, dict):
+            with open(table) as f:
+                table = json.load(f)
+        key = shape_key(self.shape)
+        entry = table.get("shapes", {}).get(key)
+        if entry is None:
+            return None
+        for name, regime in (("decode", VARIANT_DECODE), ("prefill", VARIANT_PREFILL), ("mixed", VARIANT_MIXED)):
+            if name in entry:
+                self.set_regime_options(regime, **entry[name]["knobs"])
+        return key
 
     def plan_info(self) -> dict:
         st = PlanStats()

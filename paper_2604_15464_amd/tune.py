@@ -1,0 +1,134 @@
+"""Offline tuning of the launch knobs, one set per regime (paper Sec. 3.1.4:
+block sizes are tuned offline for decode-only, prefill-only and mixed batches,
+stored in a lookup table and applied at bring-up).
+
+    python -m paper_2604_15464_amd.tune [--hq 32] [--hkv 8] [--head-dim 128] [--page-size 16]
+                                        [--kv-fp8] [--steps 30] [--out tuning.json]
+
+For the given attention shape it times a small grid of rpa_options on a
+synthetic batch of each regime (the length recipes of the decode, prefill and
+mixed evaluation workloads) and writes, or extends, a JSON table:
+
+    {"shapes": {"hq32_hkv8_d128_ps16_bf16": {"decode": {"knobs": {...}, "us": t, "default_us": t0}, ...}}}
+
+RaggedPagedAttention.load_tuning(path) applies the entry of its shape through
+rpa_set_regime_options.  The knobs change speed only, never results.
+"""
+from __future__ import annotations
+
+import argparse
+import itertools
+import json
+import os
+import sys
+import time
+
+from . import rpa
+from . import workloads as W
+
+KV_SCALES = (1.0 / 64.0, 1.0 / 32.0)
+
+
+def candidates(regime: str, hkv: int, head_dim: int, kv_fp8: bool):
+    """The grid of one regime; the empty dict (all defaults) always comes first."""
+    out = [{}]
+    lds_per_wave = head_dim * 128
+    waves = [w for w in (1, 2, 4, 8) if hkv % w == 0 and w * lds_per_wave <= 160 * 1024]
+    rows = (128, 256) if head_dim <= 128 and (not kv_fp8 or head_dim == 128) else (128,)
+    if regime == "decode":
+        for w, u in itertools.product(waves, (1, 2)):
+            out.append({"narrow_waves": w, "units_per_cu": u})
+    elif regime == "prefill":
+        for r, order, chunk in itertools.product(rows, (1, 2), (0, 1024)):
+            out.append({"wide_rows": r, "wide_order": order, "wide_kv_chunk": chunk})
+    else:
+        for r, ov in itertools.product(rows, (1, 2)):
+            out.append({"wide_rows": r, "mixed_overlap": ov})
+        for w in waves:
+            out.append({"narrow_waves": w, "mixed_overlap": 2})
+    return out
+
+
+def time_knobs(wl, x, table, knobs, kv_scales, steps, warmup):
+    import torch
+
+    ctx = rpa.RaggedPagedAttention.for_workload(wl, kv_scales=kv_scales)
+    try:
+        ctx.set_options(**knobs)
+        out = torch.empty_like(x["q"])
+
+        def call():
+            ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], table, wl.cu_q_lens,
+                                  wl.kv_lens, wl.sm_scale, out=out)
+
+        best = float("inf")
+        for _ in range(2):
+            for _ in range(warmup):
+                call()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                call()
+            torch.cuda.synchronize()
+            best = min(best, (time.perf_counter() - t0) / steps)
+        return best * 1e6
+    finally:
+        ctx.close()
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--hq", type=int, default=32)
+    ap.add_argument("--hkv", type=int, default=8)
+    ap.add_argument("--head-dim", type=int, default=128)
+    ap.add_argument("--page-size", type=int, default=16)
+    ap.add_argument("--kv-fp8", action="store_true")
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the regime workloads (quick runs)")
+    ap.add_argument("--out", default="tuning.json")
+    args = ap.parse_args()
+
+    import torch
+
+    dev = torch.device("cuda:0")
+    kv_scales = KV_SCALES if args.kv_fp8 else None
+    entry = {}
+    key = None
+    for regime in ("decode", "prefill", "mixed"):
+        wl = W.regime(regime, args.hq, args.hkv, args.head_dim, args.page_size, args.scale)
+        x = W.materialize(wl, dev, poison=False, kv_scales=kv_scales)
+        table = torch.from_numpy(wl.page_table).to(dev)
+        results = []
+        for knobs in candidates(regime, args.hkv, args.head_dim, args.kv_fp8):
+            try:
+                us = time_knobs(wl, x, table, knobs, kv_scales, args.steps, args.warmup)
+            except rpa.RpaError as e:      # a knob the shape has no kernel for
+                print(f"  {regime:8s} {knobs}: rejected ({e})", file=sys.stderr)
+                continue
+            results.append((us, knobs))
+            print(f"  {regime:8s} {us:9.1f} us  {knobs}", file=sys.stderr, flush=True)
+        default_us = results[0][0]
+        best_us, best = min(results, key=lambda r: r[0])
+        if best_us > 0.99 * default_us:    # within noise of the defaults: keep the defaults
+            best_us, best = default_us, {}
+        entry[regime] = {"knobs": best, "us": round(best_us, 1), "default_us": round(default_us, 1)}
+        ctx = rpa.RaggedPagedAttention.for_workload(wl, kv_scales=kv_scales)
+        key = rpa.shape_key(ctx.shape)
+        ctx.close()
+        del x, table
+        torch.cuda.empty_cache()
+
+    table_json = {"shapes": {}}
+    if os.path.exists(args.out):
+        with open(args.out) as f:
+            table_json = json.load(f)
+    table_json["device"] = torch.cuda.get_device_name(0)
+    table_json.setdefault("shapes", {})[key] = entry
+    with open(args.out, "w") as f:
+        json.dump(table_json, f, indent=1, sort_keys=True)
+    print(json.dumps({key: entry}))
+
+
+if __name__ == "__main__":
+    main()

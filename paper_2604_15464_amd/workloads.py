@@ -173,6 +173,31 @@ def config(index: int, scale: float = 1.0) -> Workload:
     raise ValueError("config index must be 1..5")
 
 
+def regime(name: str, hq: int = 32, hkv: int = 8, d: int = 128, ps: int = 16, scale: float = 1.0) -> Workload:
+    """The length recipes of configs 2 ("decode"), 3 ("prefill") and 4 ("mixed") at
+    any attention shape: the three regimes a set of launch knobs is tuned for."""
+    if name == "decode":
+        rng = np.random.default_rng(2)
+        n = max(2, int(round(256 * scale)))
+        kv = rng.integers(max(2, int(512 * scale)), max(4, int(4096 * scale)) + 1, size=n)
+        return _finish("regime_decode", 2, hq, hkv, d, ps, np.ones(n, dtype=np.int64), kv, rng)
+    if name == "prefill":
+        rng = np.random.default_rng(3)
+        q = np.full(max(1, int(round(8 * min(1.0, scale * 4)))), max(16, int(2048 * scale)), dtype=np.int64)
+        return _finish("regime_prefill", 3, hq, hkv, d, ps, q, q.copy(), rng)
+    if name == "mixed":
+        rng = np.random.default_rng(4)
+        nd = max(2, int(round(128 * scale)))
+        kv_d = rng.integers(max(2, int(256 * scale)), max(4, int(8192 * scale)) + 1, size=nd)
+        chunk = max(4, int(512 * scale))
+        ctxs = [max(1, int(c * scale)) for c in (1024, 2048, 4096, 8192)]
+        q = np.concatenate([np.ones(nd, dtype=np.int64), np.full(4, chunk, dtype=np.int64)])
+        kv = np.concatenate([kv_d, np.asarray(ctxs, dtype=np.int64) + chunk])
+        order = rng.permutation(q.shape[0])
+        return _finish("regime_mixed", 4, hq, hkv, d, ps, q[order], kv[order], rng)
+    raise ValueError("regime must be decode, prefill or mixed")
+
+
 def ragged(seed: int, num_seqs: int = 5, hq: int = 4, hkv: int = 2, d: int = 64, ps: int = 16,
            max_q: int = 40, max_ctx: int = 100, spare_pages: int = 3,
            p_decode: float = 0.4, p_empty: float = 0.1) -> Workload:

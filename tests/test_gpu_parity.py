@@ -326,6 +326,72 @@ def test_small_mixed_batch_stays_on_one_stream():
 
 
 # ---------------------------------------------------------------------------
+# One set of knobs per regime (Sec. 3.1.4: block sizes tuned offline for
+# decode-only, prefill-only and mixed batches, applied at bring-up).
+# ---------------------------------------------------------------------------
+def test_regime_options_follow_the_batch():
+    dev = torch.device("cuda:0")
+    shape = dict(hq=32, hkv=8, d=128, ps=16)
+    batches = {rpa.VARIANT_DECODE: W.regime("decode", scale=0.05, **shape),
+               rpa.VARIANT_PREFILL: W.regime("prefill", scale=0.125, **shape),
+               rpa.VARIANT_MIXED: W.regime("mixed", scale=0.0625, **shape)}
+    max_tokens = max(w.num_tokens for w in batches.values())
+    max_seqs = max(w.num_seqs for w in batches.values())
+    pages = max(w.num_pages for w in batches.values())
+    width = max(w.max_pages_per_seq for w in batches.values())
+    ctx = rpa.RaggedPagedAttention(32, 8, 128, 16, max_tokens, max_seqs, width, pages)
+    table = {"shapes": {rpa.shape_key(ctx.shape): {
+        "decode": {"knobs": {"narrow_waves": 2, "units_per_cu": 2}},
+        "prefill": {"knobs": {"wide_rows": 256, "wide_kv_chunk": 64}},
+        "mixed": {"knobs": {"wide_rows": 128, "mixed_overlap": 2, "narrow_waves": 8}}}}}
+    assert ctx.load_tuning(table) == rpa.shape_key(ctx.shape)
+    assert ctx.load_tuning({"shapes": {"some_other_shape": {}}}) is None
+    expect = {rpa.VARIANT_DECODE: dict(narrow_waves=2), rpa.VARIANT_PREFILL: dict(wide_rows=256),
+              rpa.VARIANT_MIXED: dict(wide_rows=128, concurrent=1, narrow_waves=8)}
+    for _ in range(2):                       # the sets stay in force from call to call
+        for regime, wl in batches.items():
+            x = W.materialize(wl, dev, max_tokens=max_tokens)
+            host = {k: W.bits(v) for k, v in x.items()}
+            pool = lambda t: torch.cat([t, torch.zeros((pages - t.shape[0],) + tuple(t.shape[1:]), dtype=t.dtype,
+                                                       device=dev)])
+            kp, vp = pool(x["k_pages"]), pool(x["v_pages"])
+            tbl = np.full((max_seqs, width), -1, dtype=np.int32)
+            tbl[:wl.num_seqs, :wl.page_table.shape[1]] = wl.page_table
+            out = ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], kp, vp, torch.from_numpy(tbl).to(dev),
+                                        wl.cu_q_lens, wl.kv_lens, wl.sm_scale)
+            torch.cuda.synchronize()
+            info = ctx.plan_info()
+            assert info["variant"] == regime
+            for k, v in expect[regime].items():
+                assert info[k] == v, (regime, k, info)
+            ref, kref, vref = O.update_and_attend(host["q"], host["k_new"], host["v_new"], host["k_pages"],
+                                                  host["v_pages"], wl.page_table, wl.cu_q_lens, wl.kv_lens,
+                                                  wl.num_seqs, wl.sm_scale)
+            assert np.array_equal(W.bits(kp)[:wl.num_pages], kref) and np.array_equal(W.bits(vp)[:wl.num_pages], vref)
+            err = np.abs(to_f64(out)[:wl.num_tokens] - ref[:wl.num_tokens])
+            assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
+    # rpa_set_options replaces the per-regime sets; bad regimes and variants are refused
+    ctx.set_options(narrow_waves=4)
+    wl = batches[rpa.VARIANT_DECODE]
+    x = W.materialize(wl, dev, max_tokens=max_tokens)
+    tbl = np.full((max_seqs, width), -1, dtype=np.int32)
+    tbl[:wl.num_seqs, :wl.page_table.shape[1]] = wl.page_table
+    kp = torch.zeros((pages, 16, 8, 128), dtype=torch.bfloat16, device=dev)
+    kp[:wl.num_pages] = x["k_pages"]
+    ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], kp, kp.clone(), torch.from_numpy(tbl).to(dev), wl.cu_q_lens,
+                          wl.kv_lens, wl.sm_scale)
+    assert ctx.plan_info()["narrow_waves"] == 4
+    for regime, knobs in ((rpa.VARIANT_AUTO, {}), (7, {}), (rpa.VARIANT_DECODE, {"variant": rpa.VARIANT_PREFILL}),
+                          (rpa.VARIANT_MIXED, {"wide_rows": 100})):
+        with pytest.raises(rpa.RpaError) as e:
+            ctx.set_regime_options(regime, **knobs)
+        assert e.value.code == rpa.ERR_INVALID_ARG
+    with pytest.raises(TypeError):
+        ctx.set_regime_options(rpa.VARIANT_DECODE, no_such_knob=1)
+    ctx.close()
+
+
+# ---------------------------------------------------------------------------
 # head_dim 256, the second head size of the paper's evaluation (Sec. 4).
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("seed", range(4))
