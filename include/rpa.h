@@ -163,7 +163,12 @@ typedef struct {
 typedef struct rpa_ctx rpa_ctx;
 
 /* Create a context on HIP device `device` for `shape`; allocates the workspace
- * (work lists, pinned staging, split partials).  *out is set on success only. */
+ * (work lists, pinned staging, split partials; with kv_fp8 a staging copy of
+ * the new K/V rows) and two streams of default priority.  *out is set on
+ * success only.  A context is used by one host thread at a time; calls on one
+ * context are ordered by the streams they are given, and the workspace (split
+ * partials, staging copy) is shared by them, so calls that may overlap on the
+ * GPU (different streams without an ordering between them) need a context each. */
 int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device);
 
 /* Free the workspace.  The caller must have synchronised the stream last used

@@ -14,10 +14,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 F = {n: i for i, n in enumerate(rpa.UNIT_FIELDS)}
 
 
-def shape_of(wl, max_tokens=None, max_seqs=None, causal=True):
+def shape_of(wl, max_tokens=None, max_seqs=None, causal=True, kv_scales=None):
     return rpa.make_shape(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size,
                           max_tokens or max(1, wl.num_tokens), max_seqs or max(1, wl.num_seqs),
-                          wl.max_pages_per_seq, wl.num_pages, causal)
+                          wl.max_pages_per_seq, wl.num_pages, causal, kv_scales)
 
 
 def test_library_exports_every_declared_symbol():
@@ -135,6 +135,32 @@ def test_mixed_batches_run_side_by_side_when_large_enough():
         assert rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, mixed_overlap=2)[2]["concurrent"] == 0
     with pytest.raises(rpa.RpaError):
         rpa.plan_host(shape_of(c1), c1.cu_q_lens, c1.kv_lens, mixed_overlap=3)
+
+
+def test_plan_with_8bit_cache():
+    """The 8-bit cache has a wide kernel at head_dim 128 only (elsewhere every tile is
+    narrow, whatever variant is asked for), keeps eight narrow waves per CU unless a
+    wide workgroup is to run beside them, and refuses unusable scales."""
+    sc = (1 / 64, 1 / 32)
+    for d in (64, 256):
+        wl = W.ragged(1700 + d, num_seqs=9, hq=8, hkv=2, d=d, ps=16, max_q=150, max_ctx=400)
+        for variant in (rpa.VARIANT_AUTO, rpa.VARIANT_PREFILL):
+            units, items, stats = rpa.plan_host(shape_of(wl, kv_scales=sc), wl.cu_q_lens, wl.kv_lens, variant=variant)
+            check_plan(wl, units, items, stats, narrow_tq=4)
+            assert stats["num_wide_units"] == 0 and stats["variant"] == rpa.VARIANT_DECODE
+    wl = W.ragged(1828, num_seqs=9, hq=32, hkv=8, d=128, ps=16, max_q=150, max_ctx=400)
+    units, items, stats = rpa.plan_host(shape_of(wl, kv_scales=sc), wl.cu_q_lens, wl.kv_lens)
+    check_plan(wl, units, items, stats, narrow_tq=4)
+    assert stats["num_wide_units"] > 0
+    c2, c4 = W.config(2), W.config(4)
+    assert rpa.plan_host(shape_of(c2), c2.cu_q_lens, c2.kv_lens)[2]["num_narrow_bins"] == 128
+    assert rpa.plan_host(shape_of(c2, kv_scales=sc), c2.cu_q_lens, c2.kv_lens)[2]["num_narrow_bins"] == 256
+    s4 = rpa.plan_host(shape_of(c4, kv_scales=sc), c4.cu_q_lens, c4.kv_lens)[2]
+    assert s4["concurrent"] == 1 and s4["num_narrow_bins"] == 128
+    for bad in ((0.0, 1.0), (1.0, -2.0), (float("nan"), 1.0), (1.0, float("inf")), (1e-45, 1.0)):
+        with pytest.raises(rpa.RpaError) as e:
+            rpa.plan_host(shape_of(c2, kv_scales=bad), c2.cu_q_lens, c2.kv_lens)
+        assert e.value.code == rpa.ERR_INVALID_ARG
 
 
 def test_auto_variant_follows_distribution():
