@@ -559,6 +559,43 @@ def test_fp8_cache_full_size_decode():
 
 
 # ---------------------------------------------------------------------------
+# Seeded random draws over shapes, page sizes, modes and launch knobs together
+# (the cases above vary them one or two at a time).
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("block", range(4))
+def test_random_combinations(block):
+    import random
+    rng = random.Random(900 + block)
+    done = 0
+    for i in range(16):
+        hkv = rng.choice([1, 2, 4, 8])
+        hg = rng.choice([1, 2, 4, 8, 16])
+        hq = hkv * hg if hkv * hg <= 64 else hkv * 4
+        d = rng.choice([64, 128, 128, 256])
+        kw = dict(variant=rng.choice([0, 0, 1, 2, 3]), kv_chunk=rng.choice([0, 0, 48, 160]),
+                  wide_kv_chunk=rng.choice([0, 0, 64, 192]), pad_tokens=rng.choice([0, 3]), pad_seqs=rng.choice([0, 2]),
+                  narrow_waves=rng.choice([0, 0, 1, 2]) if hkv % 2 == 0 else 0, units_per_cu=rng.choice([0, 2]),
+                  wide_rows=rng.choice([0, 128, 256]) if d <= 128 else 0, causal=rng.random() < 0.8,
+                  mixed_overlap=rng.choice([0, 1, 2]), calls=rng.choice([1, 2]))
+        if rng.random() < 0.35:
+            kw["kv_scales"] = rng.choice([(1 / 64, 1 / 32), (0.05, 0.02), (1.0, 1.0)])
+        wl = W.ragged(6000 + 100 * block + i, num_seqs=rng.randint(1, 24), hq=hq, hkv=hkv, d=d,
+                      ps=rng.choice([16, 32, 64, 128, 256]), max_q=rng.choice([5, 40, 200, 500]),
+                      max_ctx=rng.choice([0, 50, 700, 2500]), p_decode=rng.choice([0.1, 0.5, 0.9]),
+                      p_empty=rng.choice([0.0, 0.1]))
+        if wl.num_tokens == 0:
+            continue
+        try:
+            res = run_case(wl, **kw)
+        except rpa.RpaError as e:            # forced small chunks on a big batch: the partials do not fit
+            assert e.code == rpa.ERR_WORKSPACE and (kw["kv_chunk"] or kw["wide_kv_chunk"]), (kw, str(e))
+            continue
+        check(wl, res)
+        done += 1
+    assert done >= 12
+
+
+# ---------------------------------------------------------------------------
 # Full-size configs, in the launch configuration bench.py times (AUTO variant,
 # default chunking).  The cache is compared in full, bit for bit; outputs are
 # compared on a sample of sequences that the oracle computes one by one.
