@@ -17,9 +17,14 @@
  *     throws or aborts across this boundary.  On error nothing is enqueued and
  *     no tensor is touched; rpa_last_error() gives a message.
  *   - The library allocates only its own workspace, in rpa_create(); the call
- *     path performs no allocation, creates no stream and does not synchronise.
+ *     path performs no allocation, creates no stream and synchronises neither
+ *     the device nor the caller's stream.  The host does wait, a few
+ *     microseconds, for the call's own work list (tens of KB) to reach the
+ *     device on a stream of the context, and, when it has run eight calls
+ *     ahead of the GPU, for the oldest of them to finish.
  *   - A context serves one stream at a time: calls on one context must be
- *     issued in stream order (the work lists it uploads are reused).
+ *     issued in stream order (the work lists it uploads are reused); a caller
+ *     that moves a context between streams orders those streams itself.
  */
 #ifndef RPA_H
 #define RPA_H

@@ -15,15 +15,17 @@ using namespace rpa;
 
 namespace {
 
-constexpr int kRing = 4; // staging slots: the host may run this many calls ahead of the GPU
+constexpr int kRing = 8;  // staging slots: the host may run this many calls ahead of the GPU
+constexpr int kGroup = 4; // calls that share one completion event (an event record is a stream
+                          // packet of its own and costs the GPU about 5 us of idle time)
 
 thread_local std::string g_err; // errors without a context
 
 struct Staging {
     void* host = nullptr;        // pinned
     void* dev = nullptr;         // device copy of the same blob
-    hipEvent_t copied = nullptr; // upload finished (recorded on the upload stream)
-    hipEvent_t done = nullptr;   // kernels that read `dev` finished (recorded on the caller's stream)
+    hipEvent_t done = nullptr;   // recorded on the caller's stream after a group of calls
+    hipEvent_t* cover = nullptr; // the recorded event that tells that the kernels reading `dev` finished
     hipEvent_t fork = nullptr;   // caller's stream has reached this call (side stream waits for it)
     hipEvent_t join = nullptr;   // side stream's kernel finished (caller's stream waits for it)
     bool used = false;
@@ -54,6 +56,9 @@ struct rpa_ctx {
     size_t blob_bytes = 0;
     Staging ring[kRing];
     int ring_pos = 0;
+    int pending[kGroup];          // slots of the calls since the last completion event
+    int num_pending = 0;
+    hipStream_t last_stream = nullptr; // stream of those calls
     hipStream_t upload = nullptr; // work lists are uploaded here, ahead of the caller's stream
     hipStream_t side = nullptr;   // the wide kernel of a mixed batch runs here, beside the narrow one
     float* part_o = nullptr;
@@ -121,8 +126,6 @@ extern "C" int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device) {
         if (e != hipSuccess) return cleanup("hipHostMalloc", e);
         e = hipMalloc(&c->ring[i].dev, c->blob_bytes);
         if (e != hipSuccess) return cleanup("hipMalloc", e);
-        e = hipEventCreateWithFlags(&c->ring[i].copied, hipEventDisableTiming);
-        if (e != hipSuccess) return cleanup("hipEventCreate", e);
         e = hipEventCreateWithFlags(&c->ring[i].done, hipEventDisableTiming);
         if (e != hipSuccess) return cleanup("hipEventCreate", e);
         e = hipEventCreateWithFlags(&c->ring[i].fork, hipEventDisableTiming);
@@ -161,7 +164,6 @@ extern "C" int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device) {
 extern "C" void rpa_destroy(rpa_ctx* c) {
     if (!c) return;
     for (int i = 0; i < kRing; ++i) {
-        if (c->ring[i].copied) (void)hipEventDestroy(c->ring[i].copied);
         if (c->ring[i].done) (void)hipEventDestroy(c->ring[i].done);
         if (c->ring[i].fork) (void)hipEventDestroy(c->ring[i].fork);
         if (c->ring[i].join) (void)hipEventDestroy(c->ring[i].join);
@@ -352,13 +354,37 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     hipError_t e = hipSetDevice(c->device);
     if (e != hipSuccess) return hip_fail(c, "hipSetDevice", e);
     hipStream_t st = (hipStream_t)stream;
+    // Completion events are shared by groups of kGroup calls on one stream.  A call
+    // on another stream closes the group of the calls before it.
+    auto close_group = [&](hipStream_t on) -> hipError_t {
+        if (c->num_pending == 0) return hipSuccess;
+        Staging& last = c->ring[c->pending[c->num_pending - 1]];
+        const hipError_t r = hipEventRecord(last.done, on);
+        if (r != hipSuccess) return r;
+        for (int i = 0; i < c->num_pending; ++i) c->ring[c->pending[i]].cover = &last.done;
+        c->num_pending = 0;
+        return hipSuccess;
+    };
+    if (c->num_pending > 0 && st != c->last_stream) {
+        e = close_group(c->last_stream);
+        if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
+    }
     // The work list goes up on the library's own stream so that it overlaps the
-    // previous call's kernels; the caller's stream only waits for the event.
+    // previous call's kernels.  The slot is reused once the kernels of the call
+    // that used it kRing calls ago are done: its group's event was recorded at
+    // least kRing - kGroup calls ago, so this wait does not stall in steady state.
     Staging& slot = c->ring[c->ring_pos];
     if (slot.used) {
-        e = hipEventSynchronize(slot.done);
+        if (!slot.cover) {
+            // only after a call that failed half way (its slot never joined a group)
+            e = close_group(c->last_stream);
+            if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
+        }
+        e = slot.cover ? hipEventSynchronize(*slot.cover) : hipDeviceSynchronize();
         if (e != hipSuccess) return hip_fail(c, "hipEventSynchronize", e);
+        slot.cover = nullptr;
     }
+    const int slot_index = c->ring_pos;
     char* h = (char*)slot.host;
     const size_t units_bytes = (n_narrow + n_wide) * sizeof(rpa_work_unit);
     const size_t items_off = (units_bytes + 15) & ~(size_t)15;
@@ -372,10 +398,13 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     std::memcpy(h + bins_off, plan.bins.data(), plan.bins.size() * sizeof(int32_t));
     e = hipMemcpyAsync(slot.dev, h, total_bytes, hipMemcpyHostToDevice, c->upload);
     if (e != hipSuccess) return hip_fail(c, "hipMemcpyAsync", e);
-    e = hipEventRecord(slot.copied, c->upload);
-    if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
-    e = hipStreamWaitEvent(st, slot.copied, 0);
-    if (e != hipSuccess) return hip_fail(c, "hipStreamWaitEvent", e);
+    // The host waits for its own small copy (tens of KB on the library's stream)
+    // instead of making the caller's stream wait for an event: a wait packet costs
+    // the GPU about 5 us of idle time per call, this costs the host a few us while
+    // the GPU still works on the previous call.  The caller's stream is not
+    // synchronised.
+    e = hipStreamSynchronize(c->upload);
+    if (e != hipSuccess) return hip_fail(c, "hipStreamSynchronize", e);
     slot.used = true;
     c->ring_pos = (c->ring_pos + 1) % kRing;
 
@@ -450,8 +479,12 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
                          (uint16_t*)out, a.num_q_heads, a.head_dim, max_rows, stream,
                          pe ? (void**)&pe->ev[4] : nullptr);
     if (hrc != 0) return hip_fail(c, "combine kernel launch", (hipError_t)hrc);
-    e = hipEventRecord(slot.done, st);
-    if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
+    c->pending[c->num_pending++] = slot_index;
+    c->last_stream = st;
+    if (c->num_pending == kGroup) {
+        e = close_group(st);
+        if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
+    }
     if (pe) {
         pe->narrow = n_narrow > 0;
         pe->wide = n_wide > 0;

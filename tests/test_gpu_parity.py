@@ -318,6 +318,43 @@ def test_mixed_batch_kernels_side_by_side(shape, wide_rows):
         assert res["info"]["concurrent"] == (1 if overlap == 2 else 0)
 
 
+def test_many_calls_on_alternating_streams():
+    """More calls than staging slots, the caller switching between two streams that it
+    orders itself with events: completion events are shared by groups of calls on one
+    stream, and a call on another stream has to close the group before it."""
+    dev = torch.device("cuda:0")
+    wl = W.ragged(2100, num_seqs=12, hq=32, hkv=8, d=128, ps=16, max_q=120, max_ctx=500, p_decode=0.5)
+    x = W.materialize(wl, dev)
+    host = {k: W.bits(v) for k, v in x.items()}
+    table = torch.from_numpy(wl.page_table).to(dev)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl)
+    ctx.set_options(mixed_overlap=2)
+    ref, kp, vp = O.update_and_attend(host["q"], host["k_new"], host["v_new"], host["k_pages"], host["v_pages"],
+                                      wl.page_table, wl.cu_q_lens, wl.kv_lens, wl.num_seqs, wl.sm_scale)
+    streams = [torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)]
+    torch.cuda.synchronize()
+    outs = []
+    prev = None
+    pattern = [0, 0, 1, 0, 0, 0, 0, 0, 1, 1, 1, 0, 1, 0, 1, 1, 1, 1, 1, 1, 0, 0, 0]
+    for i, si in enumerate(pattern):
+        st = streams[si]
+        if prev is not None:
+            st.wait_event(prev)                      # the caller's own ordering between its streams
+        out = torch.full_like(x["q"], float("nan"))
+        ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], table, wl.cu_q_lens,
+                              wl.kv_lens, wl.sm_scale, out=out, stream=st)
+        prev = torch.cuda.Event()
+        prev.record(st)
+        outs.append(out)
+    torch.cuda.synchronize()
+    ctx.close()
+    assert np.array_equal(W.bits(x["k_pages"]), kp) and np.array_equal(W.bits(x["v_pages"]), vp)
+    t = wl.num_tokens
+    for out in outs:
+        err = np.abs(to_f64(out)[:t] - ref[:t])
+        assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
+
+
 def test_small_mixed_batch_stays_on_one_stream():
     wl = W.config(1)
     res = run_case(wl)
