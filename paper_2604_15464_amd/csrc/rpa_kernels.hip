@@ -479,8 +479,9 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 // with the whole register file.  K/V tiles of
 // 64 positions are staged once per workgroup in LDS by asynchronous 16-byte
 // loads (every wave brings its share), one barrier per tile.  Used for prefill
-// and chunked prefill; bound by the MFMA and vector pipes together (they do not
-// overlap on this part).
+// and chunked prefill; bound by the MFMA, vector and LDS pipes together (every
+// wave reads the whole K/V tile from LDS, which loads that pipe as much as the
+// MFMAs load theirs).
 // ---------------------------------------------------------------------------
 //
 // KV8 (head_dim 128 only): K/V tiles of E4M3 bytes (Sec. 3.6), see the narrow
