@@ -14,14 +14,18 @@
  *   - All tensors are dense, row-major, 16-byte aligned; the 16-bit element
  *     type is bfloat16.
  *   - Every function returns RPA_OK (0) or a negative rpa_status.  Nothing
- *     throws or aborts across this boundary.  On error nothing is enqueued and
- *     no tensor is touched; rpa_last_error() gives a message.
+ *     throws or aborts across this boundary.  On an argument, length, shape or
+ *     workspace error (every code but RPA_ERR_HIP) nothing is enqueued and no
+ *     tensor is touched.  RPA_ERR_HIP means a HIP runtime call failed part way:
+ *     kernels of the call launched before the failure stay enqueued, and out
+ *     and the cache are then undefined.  rpa_last_error() gives a message.
  *   - The library allocates only its own workspace, in rpa_create(); the call
  *     path performs no allocation, creates no stream and synchronises neither
  *     the device nor the caller's stream.  The host does wait, a few
  *     microseconds, for the call's own work list (tens of KB) to reach the
- *     device on a stream of the context, and, when it has run eight calls
- *     ahead of the GPU, for the oldest of them to finish.
+ *     device on a stream of the context (rpa_options.stream_ordered_upload
+ *     replaces that wait by an event the caller's stream waits for), and, when
+ *     it has run eight calls ahead of the GPU, for the oldest of them to finish.
  *   - A context serves one stream at a time: calls on one context must be
  *     issued in stream order (the work lists it uploads are reused); a caller
  *     that moves a context between streams orders those streams itself.
@@ -142,9 +146,16 @@ typedef struct {
     int32_t units_per_cu;  /* narrow bins per resident workgroup slot (1 = exactly one
                               wave of workgroups); 0 = default                        */
     int32_t ablate;        /* measurement only (ablation by leaving a stage out, as in
-                              the paper's kernel analysis, Sec. 4); outputs are then
-                              meaningless, every access stays in bounds.  Bits:
-                                1   narrow kernel: loads and stores only, no math
+                              the paper's kernel analysis, Sec. 4.1 / 4.2 ablation
+                              tables).  The switches are compiled into a separate
+                              measurement build of the library only; the product
+                              library returns RPA_ERR_UNSUPPORTED for any value but
+                              0.  Outputs are then meaningless (and the cache is not
+                              updated where the write is left out); every access
+                              stays in bounds.  Bits:
+                                1   narrow kernel: loads and stores only, no math ("w/o FA")
+                                2   narrow kernel: no cache write ("w/o KV update")
+                                4   narrow kernel: no K/V loads ("w/o DMA")
                                 64  wide kernel: no K/V loads (compute runs on stale LDS)
                                 128 wide kernel: K/V loads only, no compute
                                 256 wide kernel: no output store
@@ -163,6 +174,12 @@ typedef struct {
                               parts are large enough to repay the two extra stream
                               packets; 1 = always one after the other on the caller's
                               stream; 2 = always side by side                          */
+    int32_t stream_ordered_upload; /* 0 = the host waits (a few microseconds) until the
+                              call's work list has reached the device before it
+                              enqueues the kernels; 1 = the host never waits: the
+                              caller's stream is made to wait for the copy with an
+                              event (one more packet on the stream, about 5 us of
+                              GPU idle time per call)                                  */
 } rpa_options;
 
 typedef struct rpa_ctx rpa_ctx;

@@ -3,11 +3,15 @@ ablation tables, Sec. 4.3), on the two benchmark workloads.
 
     python -m paper_2604_15464_amd.ablation [--steps K]
 
-Decode (256 seqs, kv_len ~ U[512, 4096]): the narrow kernel as is and with the
-attention math removed (loads and stores stay).  Prefill (8 x 2048): the wide
-kernel as is, without K/V loads, with loads only, without the output store,
-without the cache write.  Outputs of ablated runs are meaningless; every access
-stays in bounds.  Prints one JSON line per variant and a table on stderr.
+Decode (256 seqs, kv_len ~ U[512, 4096]): the narrow kernel as is, without the
+cache write, without the attention math (loads and stores stay) and without the
+K/V loads: the three columns of the paper's decode ablation table.  Prefill
+(8 x 2048): the wide kernel as is, without K/V loads, with loads only, without
+the output store, without the cache write.  The switches exist only in the
+measurement build of the library (librpa_ablate.so, the same sources compiled
+with -DRPA_ABLATE), which this script loads; the product library has none.
+Outputs of ablated runs are meaningless; every access stays in bounds.  Prints
+one JSON line per variant and a table on stderr.
 """
 from __future__ import annotations
 
@@ -19,7 +23,8 @@ import time
 from . import rpa
 from . import workloads as W
 
-DECODE = (("full", 0), ("without attention math", 1))
+DECODE = (("full", 0), ("without cache write (w/o KV update)", 2), ("without attention math (w/o FA)", 1),
+          ("without K/V loads (w/o DMA)", 4))
 PREFILL = (("full", 0), ("without K/V loads", 64), ("K/V loads only (no compute)", 128),
            ("without output store", 256), ("without cache write", 512),
            ("launch, Q fetch and barriers only", 64 + 128 + 256 + 512))
@@ -31,7 +36,7 @@ def run(wl, variants, kernel_key, steps, warmup):
     dev = torch.device("cuda:0")
     x = W.materialize(wl, dev, poison=False)
     table = torch.from_numpy(wl.page_table).to(dev)
-    ctx = rpa.RaggedPagedAttention.for_workload(wl)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl, library=rpa.load_library(rpa.ABLATE_LIB_PATH))
     out = torch.empty_like(x["q"])
 
     def call():

@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librpa.so")
+LIB_ABLATE = os.path.join(HERE, "librpa_ablate.so")  # measurement build, loaded by ablation.py only
 
 SOURCES = ["rpa_api.cpp", "rpa_partition.cpp", "rpa_kernels.hip"]
 
@@ -21,6 +22,9 @@ FLAGS = [
     # compiler copies the whole output accumulator between the two files on every
     # tile.  The other kernels compile identically with and without it.
     "-mllvm", "-amdgpu-mfma-vgpr-form",
+    # symbols bind inside the library: the product and the measurement build can
+    # be loaded into one process
+    "-Wl,-Bsymbolic", "-fvisibility-inlines-hidden",
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
 ]
 
@@ -32,10 +36,10 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose: bool = True, extra_flags=()) -> str:
+def build_library(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
     cmd = [hipcc(), *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-x", "hip", *srcs, "-o", LIB]
+           "-x", "hip", *srcs, "-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -45,8 +49,17 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed:\n" + res.stdout + "\n" + res.stderr)
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB
+    return out
+
+
+def build_ablation_library(verbose: bool = True) -> str:
+    """The same sources with the measurement switches compiled in (rpa_options.ablate)."""
+    return build_library(verbose, extra_flags=("-DRPA_ABLATE",), out=LIB_ABLATE)
+
+
+def build_all(verbose: bool = True):
+    return [build_library(verbose), build_ablation_library(verbose)]
 
 
 if __name__ == "__main__":
-    print(build_library())
+    print(*build_all(), sep="\n")

@@ -28,6 +28,7 @@ struct Staging {
     hipEvent_t* cover = nullptr; // the recorded event that tells that the kernels reading `dev` finished
     hipEvent_t fork = nullptr;   // caller's stream has reached this call (side stream waits for it)
     hipEvent_t join = nullptr;   // side stream's kernel finished (caller's stream waits for it)
+    hipEvent_t uploaded = nullptr; // the work list has reached `dev` (stream-ordered upload only)
     bool used = false;
 };
 
@@ -132,6 +133,8 @@ extern "C" int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device) {
         if (e != hipSuccess) return cleanup("hipEventCreate", e);
         e = hipEventCreateWithFlags(&c->ring[i].join, hipEventDisableTiming);
         if (e != hipSuccess) return cleanup("hipEventCreate", e);
+        e = hipEventCreateWithFlags(&c->ring[i].uploaded, hipEventDisableTiming);
+        if (e != hipSuccess) return cleanup("hipEventCreate", e);
         c->workspace_bytes += (int64_t)c->blob_bytes;
     }
     e = hipStreamCreateWithFlags(&c->upload, hipStreamNonBlocking);
@@ -167,6 +170,7 @@ extern "C" void rpa_destroy(rpa_ctx* c) {
         if (c->ring[i].done) (void)hipEventDestroy(c->ring[i].done);
         if (c->ring[i].fork) (void)hipEventDestroy(c->ring[i].fork);
         if (c->ring[i].join) (void)hipEventDestroy(c->ring[i].join);
+        if (c->ring[i].uploaded) (void)hipEventDestroy(c->ring[i].uploaded);
         if (c->ring[i].host) (void)hipHostFree(c->ring[i].host);
         if (c->ring[i].dev) (void)hipFree(c->ring[i].dev);
     }
@@ -199,8 +203,17 @@ extern "C" int rpa_set_options(rpa_ctx* c, const rpa_options* opt) {
         o.units_per_cu < 0 || o.narrow_waves < 0 || o.narrow_waves > kMaxWaves ||
         (o.narrow_waves > 0 && c->shape.num_kv_heads % o.narrow_waves != 0) ||
         (o.wide_rows != 0 && o.wide_rows != 128 && o.wide_rows != 256) || o.wide_order < 0 || o.wide_order > 2 ||
-        o.mixed_overlap < 0 || o.mixed_overlap > 2 || !options_fit_shape(c->shape, o))
+        o.mixed_overlap < 0 || o.mixed_overlap > 2 || o.stream_ordered_upload < 0 || o.stream_ordered_upload > 1 ||
+        !options_fit_shape(c->shape, o))
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: bad value");
+#ifdef RPA_ABLATE
+    if (o.ablate & ~(1 | 2 | 4 | 64 | 128 | 256 | 512))
+        return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: unknown ablation bit");
+#else
+    if (o.ablate != 0)
+        return fail(c, RPA_ERR_UNSUPPORTED,
+                    "rpa_set_options: this library is built without the measurement switches (the ablation build has them)");
+#endif
     c->opt = o;
     for (bool& b : c->regime_set) b = false;
     return RPA_OK;
@@ -398,13 +411,22 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     std::memcpy(h + bins_off, plan.bins.data(), plan.bins.size() * sizeof(int32_t));
     e = hipMemcpyAsync(slot.dev, h, total_bytes, hipMemcpyHostToDevice, c->upload);
     if (e != hipSuccess) return hip_fail(c, "hipMemcpyAsync", e);
-    // The host waits for its own small copy (tens of KB on the library's stream)
-    // instead of making the caller's stream wait for an event: a wait packet costs
-    // the GPU about 5 us of idle time per call, this costs the host a few us while
-    // the GPU still works on the previous call.  The caller's stream is not
-    // synchronised.
-    e = hipStreamSynchronize(c->upload);
-    if (e != hipSuccess) return hip_fail(c, "hipStreamSynchronize", e);
+    // By default the host waits for its own small copy (tens of KB on the library's
+    // stream) instead of making the caller's stream wait for an event: a wait packet
+    // costs the GPU about 5 us of idle time per call, this costs the host a few us
+    // while the GPU still works on the previous call.  The caller's stream is not
+    // synchronised.  With stream_ordered_upload the host never waits: the caller's
+    // stream is ordered after the copy by an event.
+    if (opt_used.stream_ordered_upload) {
+        e = hipEventRecord(slot.uploaded, c->upload);
+        if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
+        e = hipStreamWaitEvent(st, slot.uploaded, 0);
+        if (e != hipSuccess) return hip_fail(c, "hipStreamWaitEvent", e);
+    } else {
+        e = hipStreamSynchronize(c->upload);
+        if (e != hipSuccess) return hip_fail(c, "hipStreamSynchronize", e);
+    }
+    (void)hipGetLastError(); // a stale error of an earlier HIP call is not a launch failure of this call
     slot.used = true;
     c->ring_pos = (c->ring_pos + 1) % kRing;
 

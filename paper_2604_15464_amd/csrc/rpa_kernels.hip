@@ -32,6 +32,15 @@ typedef const __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 typedef __attribute__((ext_vector_type(2))) int int2v;
 typedef __attribute__((address_space(3))) int2v lds_int2;
 
+// Measurement switches (the paper's ablation by leaving a stage out, Sec. 4):
+// compiled in only with -DRPA_ABLATE, i.e. in the separate library the ablation
+// script loads.  In the product library the conditions are compile-time false.
+#ifdef RPA_ABLATE
+#define RPA_ABLATED(a, bits) (((a).ablate & (bits)) != 0)
+#else
+#define RPA_ABLATED(a, bits) false
+#endif
+
 // The wide kernel lets softmax weights grow to 2^kRescaleGap before it moves a
 // row's reference maximum and rescales the accumulator.
 constexpr float kRescaleGap = 8.0f;
@@ -43,12 +52,17 @@ constexpr float kRescaleGap = 8.0f;
 // 16-byte asynchronous global -> LDS copy: lane i's 16 bytes land at
 // lds_byte_off + 16 * i.  Completion is tracked by vmcnt only; the compiler
 // does not know about the LDS write, so every consumer waits explicitly with
-// wait_vmcnt<N>() before reading the stage.
+// wait_vmcnt<N>() before reading the stage.  The LDS address goes through m0,
+// which the asm declares as written, so that the compiler never assumes a value
+// of its own survives there (it reserves m0 and warns about the clobber; the
+// declaration is what keeps its own m0 uses correct).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void async_load16(const void* gptr, uint32_t lds_byte_off) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  :
                  : "v"(gptr), "s"(lds_byte_off)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // 16-byte store of data that this call will not read again (outputs, cache
@@ -68,7 +82,7 @@ __device__ __forceinline__ void async_load16_stream(const void* gptr, uint32_t l
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
                  :
                  : "v"(gptr), "s"(lds_byte_off)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // The same with the address split into a wave-uniform 64-bit base (scalar
@@ -77,8 +91,10 @@ __device__ __forceinline__ void async_load16_base(const void* sbase, uint32_t vo
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
                  :
                  : "s"(sbase), "v"(voff), "s"(lds_byte_off)
-                 : "memory");
+                 : "memory", "m0");
 }
+
+#pragma clang diagnostic pop
 
 // A pointer whose value is the same in every lane, moved to scalar registers in
 // case the compiler did not prove that on its own (the "s" operand of the asm
@@ -239,6 +255,7 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     const int ntiles = max(0, (kv_end - kv_begin + kNarrowKvTile - 1) / kNarrowKvTile);
 
     auto issue_tile = [&](int t) {
+        if (RPA_ABLATED(a, 4)) return; // measurement: no K/V traffic (the math runs on whatever the LDS holds)
         const int pos0 = kv_begin + t * kNarrowKvTile;
         const int slot = t % NST;
         const int pidx = __builtin_amdgcn_readfirstlane(pos0 >> ps_log2);
@@ -299,7 +316,7 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         const char* ldsK = lds_wave_ptr + (t % NST) * STAGEB;
         const char* ldsV = ldsK + TILEB;
         const int pos0 = kv_begin + t * kNarrowKvTile;
-        if (a.ablate & 1) { // measurement: loads only
+        if (RPA_ABLATED(a, 1)) { // measurement: loads and stores only
             acc[0][0] += __uint_as_float(*(const uint32_t*)(ldsK + lane * 4)) + __uint_as_float(*(const uint32_t*)(ldsV + lane * 4));
             continue;
         }
@@ -404,7 +421,7 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     // Readers never take positions >= ctx from the pages (they read k_new / v_new),
     // so this store races with nothing; it sits after the loop so that only loads
     // are in flight while the ring's vmcnt bookkeeping runs.
-    if (u.flags & 1) {
+    if ((u.flags & 1) && !RPA_ABLATED(a, 2)) {
         const int c = lane % NC;
         for (int t = lane / NC; t < u.n_q; t += TPI) {
             const int pos = ctx + u.q_pos0 + t;
@@ -593,7 +610,7 @@ rpa_wide_kernel(KernelArgs a) {
     // 16 positions), and so do they after clamping to the end of the range.
     static_assert(WPOS <= 16 && 16 % WPOS == 0, "a wave's share of a tile must lie in one page");
     auto issue_tile = [&](int t) __attribute__((always_inline)) {
-        if (a.ablate & 64) return; // measurement: no KV traffic
+        if (RPA_ABLATED(a, 64)) return; // measurement: no K/V traffic
         const int p0w = kv_begin + t * KT + WPOS * wave; // this wave's positions
         const int slot = t % NST;
         const uint32_t ldsK = lds_base + slot * STAGEB + (WPOS * wave) * ROWB;
@@ -884,7 +901,7 @@ rpa_wide_kernel(KernelArgs a) {
         const uint32_t ldsV = ldsK + TILEB;
         const int pos0 = kv_begin + t * KT;
         // tiles wholly above the wave's diagonal are skipped
-        if (pos0 <= wave_limit && !(a.ablate & 128)) compute_tile(ldsK, ldsV, pos0);
+        if (pos0 <= wave_limit && !RPA_ABLATED(a, 128)) compute_tile(ldsK, ldsV, pos0);
         // tile t+1 must have landed; tiles t+2 .. may still be in flight
         const int behind = min(NST - 2, ntiles - 2 - t);
         if (NST >= 4 && behind >= 2) wait_vmcnt<(NST >= 4 ? 2 : 0) * LPT>();
@@ -913,7 +930,7 @@ rpa_wide_kernel(KernelArgs a) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
-        if (a.ablate & 256) continue;
+        if (RPA_ABLATED(a, 256)) continue;
         if (!row_ok[nt] && u.part_row >= 0) continue;
         if (u.part_row < 0) {
             // Rows go through this wave's slice of the (now idle) LDS ring so that
@@ -951,7 +968,7 @@ rpa_wide_kernel(KernelArgs a) {
         }
     }
 
-    if (u.part_row < 0 && !(a.ablate & 256)) {
+    if (u.part_row < 0 && !RPA_ABLATED(a, 256)) {
         constexpr int SROW = OROWB + 16;
         constexpr int RPI = 64 / ONC; // rows per wave-wide 16-byte store
 #pragma unroll
@@ -970,7 +987,7 @@ rpa_wide_kernel(KernelArgs a) {
     }
 
     // ---- fused cache update for the tile's new tokens (see the narrow kernel)
-    if ((u.flags & 1) && !(a.ablate & 512)) {
+    if ((u.flags & 1) && !RPA_ABLATED(a, 512)) {
         const int c = threadIdx.x % NC;
         for (int t = threadIdx.x / NC; t < u.n_q; t += (64 * WAVES) / NC) {
             const int pos = ctx + u.q_pos0 + t;

@@ -50,7 +50,8 @@ class PlanStats(C.Structure):
 class Options(C.Structure):
     _fields_ = [("variant", C.c_int32), ("kv_chunk", C.c_int32), ("wide_kv_chunk", C.c_int32),
                 ("narrow_waves", C.c_int32), ("units_per_cu", C.c_int32), ("ablate", C.c_int32),
-                ("wide_rows", C.c_int32), ("wide_order", C.c_int32), ("mixed_overlap", C.c_int32)]
+                ("wide_rows", C.c_int32), ("wide_order", C.c_int32), ("mixed_overlap", C.c_int32),
+                ("stream_ordered_upload", C.c_int32)]
 
 
 class RpaError(RuntimeError):
@@ -66,15 +67,26 @@ EXPORTS = ("rpa_create", "rpa_destroy", "rpa_update_and_attend", "rpa_last_error
            "rpa_copy_probe")
 
 
+ABLATE_LIB_PATH = os.path.join(_HERE, "librpa_ablate.so")   # measurement build: the same code with -DRPA_ABLATE
+_loaded = {}
+
+
 def lib():
     """Load librpa.so (built in-tree by paper_2604_15464_amd/build.py)."""
     global _lib
-    if _lib is not None:
-        return _lib
-    if not os.path.exists(LIB_PATH):
-        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_15464_amd.build` "
+    if _lib is None:
+        _lib = load_library(LIB_PATH)
+    return _lib
+
+
+def load_library(path):
+    """Load a build of the library and declare its entry points."""
+    if path in _loaded:
+        return _loaded[path]
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2604_15464_amd.build` "
                            "(there is no fallback path)")
-    l = C.CDLL(LIB_PATH)
+    l = C.CDLL(path)
     l.rpa_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(Shape), C.c_int]
     l.rpa_create.restype = C.c_int
     l.rpa_destroy.argtypes = [C.c_void_p]
@@ -101,7 +113,7 @@ def lib():
     l.rpa_plan_host.restype = C.c_int
     l.rpa_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
     l.rpa_copy_probe.restype = C.c_int
-    _lib = l
+    _loaded[path] = l
     return l
 
 
@@ -135,7 +147,7 @@ def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUT
     units = (WorkUnit * max_units)()
     items = (CombineItem * max_units)()
     stats = PlanStats()
-    opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, 0, 0, wide_rows, 0, mixed_overlap)
+    opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, 0, 0, wide_rows, 0, mixed_overlap, 0)
     rc = l.rpa_plan_host(C.byref(shape), cu_p, kv_p, n, C.byref(opt), num_cus, units, max_units, items,
                          max_units, C.byref(stats))
     if rc != RPA_OK:
@@ -154,8 +166,8 @@ class RaggedPagedAttention:
     """One context = one static shape on one GPU."""
 
     def __init__(self, num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs,
-                 max_pages_per_seq, num_pages, device=0, causal=True, kv_scales=None):
-        self._lib = lib()
+                 max_pages_per_seq, num_pages, device=0, causal=True, kv_scales=None, library=None):
+        self._lib = lib() if library is None else library
         self.shape = make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs,
                                 max_pages_per_seq, num_pages, causal, kv_scales)
         self._ctx = C.c_void_p()
@@ -165,10 +177,10 @@ class RaggedPagedAttention:
         self.device = int(device)
 
     @classmethod
-    def for_workload(cls, wl, max_tokens=None, max_seqs=None, device=0, causal=True, kv_scales=None):
+    def for_workload(cls, wl, max_tokens=None, max_seqs=None, device=0, causal=True, kv_scales=None, library=None):
         return cls(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size,
                    max(1, max_tokens or wl.num_tokens), max(1, max_seqs or wl.num_seqs),
-                   wl.max_pages_per_seq, wl.num_pages, device, causal, kv_scales)
+                   wl.max_pages_per_seq, wl.num_pages, device, causal, kv_scales, library)
 
     def close(self):
         if getattr(self, "_ctx", None) is not None and self._ctx.value:
@@ -182,9 +194,9 @@ class RaggedPagedAttention:
             pass
 
     def set_options(self, variant=VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, narrow_waves=0, units_per_cu=0,
-                    ablate=0, wide_rows=0, wide_order=0, mixed_overlap=0):
+                    ablate=0, wide_rows=0, wide_order=0, mixed_overlap=0, stream_ordered_upload=0):
         opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, units_per_cu, ablate, wide_rows, wide_order,
-                      mixed_overlap)
+                      mixed_overlap, stream_ordered_upload)
         rc = self._lib.rpa_set_options(self._ctx, C.byref(opt))
         if rc != RPA_OK:
             raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())

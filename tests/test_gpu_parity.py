@@ -669,3 +669,58 @@ def test_full_config4_mixed():
 def test_full_config5_long_decode():
     wl, res = _full_case(5, lambda wl: [0, int(np.argmax(wl.kv_lens)), int(np.argmin(wl.kv_lens))])
     assert res["info"]["max_splits"] >= 4       # the long sequences are cut into many KV ranges
+
+
+# ---------------------------------------------------------------------------
+# Measurement switches (ablation by leaving a stage out, Sec. 4): they exist in
+# the measurement build of the library only.  Every switch once on a small mixed
+# batch: the call completes, nothing outside `out` and the cache is touched, and
+# switches that leave the cache write in give the oracle's cache bit for bit.
+# ---------------------------------------------------------------------------
+def test_product_library_has_no_ablation_switches():
+    wl = W.config(1)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl)
+    with pytest.raises(rpa.RpaError) as e:
+        ctx.set_options(ablate=1)
+    assert e.value.code == rpa.ERR_UNSUPPORTED
+    ctx.close()
+
+
+@pytest.mark.parametrize("bits", [0, 1, 2, 4, 64, 128, 256, 512, 1 | 2 | 4, 64 | 128 | 256 | 512])
+def test_ablation_build_switches(bits):
+    lib = rpa.load_library(rpa.ABLATE_LIB_PATH)
+    dev = torch.device("cuda:0")
+    wl = W.ragged(3100, num_seqs=14, hq=32, hkv=8, d=128, ps=16, max_q=200, max_ctx=600, p_decode=0.5)
+    pad = 4
+    x = W.materialize(wl, dev, poison=True, max_tokens=wl.num_tokens + pad)
+    host = {k: W.bits(v) for k, v in x.items()}
+    table = torch.from_numpy(wl.page_table).to(dev)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl, max_tokens=wl.num_tokens + pad, library=lib)
+    with pytest.raises(rpa.RpaError):
+        ctx.set_options(ablate=8)                      # not a switch
+    ctx.set_options(ablate=bits, kv_chunk=128, wide_kv_chunk=128)
+    out = torch.full_like(x["q"], float("nan"))
+    keep = out.clone()
+    guard = {k: v.clone() for k, v in x.items() if k in ("q", "k_new", "v_new")}
+    for _ in range(2):
+        ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], table, wl.cu_q_lens,
+                              wl.kv_lens, wl.sm_scale, out=out)
+    torch.cuda.synchronize()
+    info = ctx.plan_info()
+    ctx.close()
+    assert info["num_narrow_units"] > 0 and info["num_wide_units"] > 0 and info["max_splits"] > 1
+    for k, v in guard.items():                          # inputs untouched
+        assert torch.equal(v.view(torch.int16), x[k].view(torch.int16))
+    t = wl.num_tokens
+    assert torch.equal(out[t:].view(torch.int16), keep[t:].view(torch.int16))   # padding rows never written
+    ref, kp, vp = O.update_and_attend(host["q"], host["k_new"], host["v_new"], host["k_pages"], host["v_pages"],
+                                      wl.page_table, wl.cu_q_lens, wl.kv_lens, wl.num_seqs, wl.sm_scale)
+    if not bits & (2 | 512):
+        assert np.array_equal(W.bits(x["k_pages"]), kp) and np.array_equal(W.bits(x["v_pages"]), vp)
+    else:
+        # the cache write of one kernel is left out: slots are either still as before or the oracle's
+        for got, before, want in ((W.bits(x["k_pages"]), host["k_pages"], kp), (W.bits(x["v_pages"]), host["v_pages"], vp)):
+            assert ((got == before) | (got == want)).all()
+    if bits == 0:
+        err = np.abs(to_f64(out)[:t] - ref[:t])
+        assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
