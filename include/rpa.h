@@ -237,6 +237,29 @@ int rpa_update_and_attend(rpa_ctx* ctx, void* out, const void* q, const void* k_
                           const int32_t* kv_lens, int32_t num_seqs, float sm_scale,
                           void* stream);
 
+/* The hot call for callers that cannot allocate device memory: code under HIP
+ * stream capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and error codes as rpa_update_and_attend, with the shape
+ * and the HIP device index in place of a context.  It calls no hipMalloc /
+ * hipFree and creates no stream or event: the device work list and the split
+ * partials live in one static device array of 8 MiB + 64 KiB that each GPU the
+ * library runs on holds until the process ends; the work list reaches it inside
+ * kernel arguments.  Limits, beyond which RPA_ERR_WORKSPACE (work list of the
+ * batch above 64 KiB, about 1300 units) or RPA_ERR_UNSUPPORTED (kv_fp8, whose
+ * staging copy of the new rows has no room here) is returned and nothing is
+ * enqueued; split partials that would not fit 8 MiB make the partitioner cut
+ * less instead.  The kernels of a mixed batch run one after the other on
+ * `stream`.  Every call on a GPU uses that GPU's one array: calls that may
+ * overlap on one GPU (different streams without an ordering between them) race;
+ * calls in stream order are safe, and nothing in the array has to be cleared
+ * between calls (every word read by a call is written by the same call first).
+ * rpa_noalloc_last_error() gives the message of this thread's last failure.  */
+int rpa_update_and_attend_noalloc(const rpa_shape* shape, int device, void* out, const void* q,
+                                  const void* k_new, const void* v_new, void* k_pages, void* v_pages,
+                                  const int32_t* page_table, const int32_t* cu_q_lens,
+                                  const int32_t* kv_lens, int32_t num_seqs, float sm_scale, void* stream);
+const char* rpa_noalloc_last_error(void);
+
 /* Message of the last failed call on this context (never NULL; "" if none).
  * With ctx == NULL: the message of the last failed rpa_create / rpa_plan_host
  * on this thread.                                                             */

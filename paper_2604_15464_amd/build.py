@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librpa.so")
 LIB_ABLATE = os.path.join(HERE, "librpa_ablate.so")  # measurement build, loaded by ablation.py only
 
-SOURCES = ["rpa_api.cpp", "rpa_partition.cpp", "rpa_kernels.hip"]
+SOURCES = ["rpa_api.cpp", "rpa_partition.cpp", "rpa_kernels.hip", "rpa_noalloc.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

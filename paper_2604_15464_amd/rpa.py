@@ -64,7 +64,7 @@ _lib = None
 
 EXPORTS = ("rpa_create", "rpa_destroy", "rpa_update_and_attend", "rpa_last_error", "rpa_plan_info",
            "rpa_set_options", "rpa_set_regime_options", "rpa_plan_host", "rpa_profile_enable", "rpa_profile_read",
-           "rpa_copy_probe")
+           "rpa_copy_probe", "rpa_update_and_attend_noalloc", "rpa_noalloc_last_error")
 
 
 ABLATE_LIB_PATH = os.path.join(_HERE, "librpa_ablate.so")   # measurement build: the same code with -DRPA_ABLATE
@@ -113,6 +113,11 @@ def load_library(path):
     l.rpa_plan_host.restype = C.c_int
     l.rpa_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
     l.rpa_copy_probe.restype = C.c_int
+    l.rpa_update_and_attend_noalloc.argtypes = [C.POINTER(Shape), C.c_int] + [C.c_void_p] * 7 + [
+        C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
+    l.rpa_update_and_attend_noalloc.restype = C.c_int
+    l.rpa_noalloc_last_error.argtypes = []
+    l.rpa_noalloc_last_error.restype = C.c_char_p
     _loaded[path] = l
     return l
 
@@ -156,6 +161,20 @@ def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUT
     u = np.frombuffer(units, dtype=np.int32).reshape(max_units, 12)[:nu].copy()
     it = np.frombuffer(items, dtype=np.int32).reshape(max_units, 4)[:stats.num_combine_items].copy()
     return u, it, stats.as_dict()
+
+
+def update_and_attend_noalloc(shape: Shape, device, out_ptr, q_ptr, k_new_ptr, v_new_ptr, k_pages_ptr, v_pages_ptr,
+                              page_table_ptr, cu_q_lens, kv_lens, sm_scale, stream_ptr):
+    """rpa_update_and_attend_noalloc: pointers in, status out (no context, no
+    allocation in the library); cu_q_lens / kv_lens are host int32 arrays."""
+    l = lib()
+    cu, cu_p = _i32(cu_q_lens)
+    kv, kv_p = _i32(kv_lens)
+    rc = l.rpa_update_and_attend_noalloc(C.byref(shape), int(device), out_ptr, q_ptr, k_new_ptr, v_new_ptr,
+                                         k_pages_ptr, v_pages_ptr, page_table_ptr, cu_p, kv_p, len(kv),
+                                         float(sm_scale), stream_ptr)
+    if rc != RPA_OK:
+        raise RpaError(rc, l.rpa_noalloc_last_error().decode())
 
 
 UNIT_FIELDS = ("seq", "q_start", "q_pos0", "n_q", "kv_begin", "kv_end", "ctx", "seq_q0", "part_row", "flags",
