@@ -312,3 +312,149 @@ def bits(t):
     if t.dtype == torch.uint8:
         return t.detach().to("cpu").contiguous().numpy()
     return t.detach().to("cpu").contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+# ---------------------------------------------------------------------------
+# Discriminating inputs.  With N(0,1) data a long softmax averages thousands of
+# rows and an output moves by O(1/kv_len) when one K/V row is wrong, far below
+# any tolerance.  The "needle" recipe makes every output row depend on ONE chosen
+# position: keys are random sign vectors (entries +-1, so two different keys are
+# nearly orthogonal), and the query of (token, head) is twice the key of its
+# target position.  The target's score is then sm_scale * 2 * head_dim (22.6 at
+# head_dim 128) against N(0, 4 * sm_scale^2 * head_dim) ~ N(0, 2^2) elsewhere, its
+# softmax weight is 1 to within 1e-5, and the output row is the target's V row
+# (N(0,1), distinct per position): a row gathered from a wrong slot, a dropped or
+# repeated position or a mask that hides the target changes that output by O(1).
+# Only data is built here; which position a query "should" find is decided by
+# the softmax of whoever consumes the data.
+# ---------------------------------------------------------------------------
+def slot_of_position(wl: Workload, r: int, pos):
+    """Flat slot index (page * page_size + offset) of positions of sequence r."""
+    pos = np.asarray(pos, dtype=np.int64)
+    return wl.page_table[r].astype(np.int64)[pos // wl.page_size] * wl.page_size + pos % wl.page_size
+
+
+def interesting_positions(wl: Workload, r: int, cuts=()):
+    """Positions of sequence r where indexing mistakes live: both ends, both sides
+    of the first and last page boundary and of every 16- and 64-position tile
+    boundary next to them, both sides of the cached/new boundary, both sides of
+    every cut in `cuts` (the KV range boundaries a work plan reports)."""
+    kv, ql, ps = int(wl.kv_lens[r]), int(wl.q_lens[r]), wl.page_size
+    ctx = kv - ql
+    cand = {0, 1, 15, 16, 17, 63, 64, 65, ps - 1, ps, ps + 1, kv - 1, kv - 2, ctx - 1, ctx, ctx + 1}
+    last_page = ((kv - 1) // ps) * ps
+    cand |= {last_page - 1, last_page, last_page + 1, (kv - 1) // 16 * 16 - 1, (kv - 1) // 16 * 16,
+             (kv - 1) // 64 * 64 - 1, (kv - 1) // 64 * 64, (ctx // 64) * 64 - 1, (ctx // 64) * 64,
+             (ctx // 16) * 16 - 1, (ctx // 16) * 16}
+    for c in cuts:
+        cand |= {int(c) - 1, int(c)}
+    return np.array(sorted(p for p in cand if 0 <= p < kv), dtype=np.int64)
+
+
+def needle_targets(wl: Workload, mode: str = "spread", seed: int = 0, cuts=None, causal: bool = True) -> np.ndarray:
+    """int64 [T, Hq]: the position each (query token, head) is aimed at, always one
+    it may see.  mode "spread": the queries of a sequence together visit as many different positions
+    of every KV head as they can (all of them once there are kv_len / h_g tokens);
+    "boundaries": cycled through interesting_positions(); "random": uniform."""
+    rng = np.random.default_rng(7919 * seed + wl.seed)
+    hq = wl.num_q_heads
+    out = np.zeros((wl.num_tokens, hq), dtype=np.int64)
+    cu = wl.cu_q_lens
+    for r in range(wl.num_seqs):
+        ql, kv = int(wl.q_lens[r]), int(wl.kv_lens[r])
+        if ql == 0:
+            continue
+        ctx = kv - ql
+        tok = np.repeat(np.arange(ql, dtype=np.int64), hq)
+        visible = (ctx + tok + 1) if causal else np.full(ql * hq, kv, dtype=np.int64)
+        k = np.arange(ql * hq, dtype=np.int64)
+        if mode == "random":
+            t = (rng.random(ql * hq) * visible).astype(np.int64)
+        elif mode == "spread":
+            # Per KV head: the probes (token, head of the group), taken from the last
+            # token backwards, walk down the positions one by one from the last, so
+            # that as many different positions as there are probes get visited (each
+            # stays visible: the position falls by one per probe, the limit by one per
+            # h_g probes); probes left over when position 0 is reached go anywhere.
+            hg = hq // wl.num_kv_heads
+            j = (k % hq) % hg                                    # head inside its group
+            kk = (ql - 1 - tok) * hg + (j + seed) % hg           # probe index inside the KV head
+            t = np.where(kk < kv, kv - 1 - kk, (rng.random(ql * hq) * visible).astype(np.int64))
+            t = np.minimum(t, visible - 1)
+        elif mode == "boundaries":
+            pts = interesting_positions(wl, r, cuts[r] if cuts is not None else ())
+            shift = int(rng.integers(0, len(pts)))
+            t = pts[(k + shift) % len(pts)]
+            hidden = t >= visible                       # aimed past the token's own position: take its last one
+            t = np.where(hidden, visible - 1 - (k % np.minimum(visible, 3)), t)
+        else:
+            raise ValueError("mode must be spread, boundaries or random")
+        out[cu[r]:cu[r + 1]] = np.minimum(t, visible - 1).reshape(ql, hq)
+    return out
+
+
+def materialize_needles(wl: Workload, targets: np.ndarray, device="cpu", poison: bool = True,
+                        max_tokens: int | None = None, kv_scales=None):
+    """Like materialize(), with sign-vector keys and queries aimed at `targets`
+    (needle_targets()).  V, and everything about poison and padding, as there."""
+    import torch
+
+    dev = torch.device(device)
+    x = materialize(wl, dev, poison=False, max_tokens=max_tokens, kv_scales=None)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1000003 * wl.seed + 29)
+
+    def signs(like):
+        flat = like.view(-1)
+        step = 1 << 26
+        for s in range(0, flat.numel(), step):
+            n = min(step, flat.numel() - s)
+            flat[s:s + n] = (torch.randint(0, 2, (n,), generator=gen, device=dev, dtype=torch.int8) * 2 - 1).to(like.dtype)
+        return like
+
+    signs(x["k_pages"])
+    signs(x["k_new"])
+    hq, hkv, d, ps = wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size
+    hg = hq // hkv
+    t_total = wl.num_tokens
+    if t_total:
+        # source row of every (token, head): a slot of the page pool or a row of k_new
+        cu = wl.cu_q_lens
+        is_new = np.zeros((t_total, hq), dtype=bool)
+        row = np.zeros((t_total, hq), dtype=np.int64)
+        for r in range(wl.num_seqs):
+            ql = int(wl.q_lens[r])
+            if ql == 0:
+                continue
+            ctx = int(wl.kv_lens[r]) - ql
+            t = targets[cu[r]:cu[r + 1]]
+            new = t >= ctx
+            is_new[cu[r]:cu[r + 1]] = new
+            row[cu[r]:cu[r + 1]] = np.where(new, cu[r] + t - ctx, slot_of_position(wl, r, np.where(new, 0, t)))
+        g_of_h = torch.arange(hq, device=dev) // hg
+        row_t = torch.from_numpy(row).to(dev)
+        new_t = torch.from_numpy(is_new).to(dev)
+        pool = x["k_pages"].view(wl.num_pages * ps, hkv, d)
+        from_pool = pool[row_t.clamp(max=wl.num_pages * ps - 1), g_of_h[None, :]]        # [T, Hq, D]
+        from_new = x["k_new"][row_t.clamp(max=x["k_new"].shape[0] - 1), g_of_h[None, :]]
+        x["q"][:t_total] = 2.0 * torch.where(new_t[..., None], from_new, from_pool)
+    if kv_scales is not None:
+        def to_bytes(pool, scale):
+            v = (pool.float() / float(scale)).clamp_(-448.0, 448.0)
+            return v.to(torch.float8_e4m3fn).view(torch.uint8)
+        x["k_pages"] = to_bytes(x["k_pages"], kv_scales[0])
+        x["v_pages"] = to_bytes(x["v_pages"], kv_scales[1])
+    if poison:
+        bad = torch.tensor([POISON_BITS], dtype=torch.int16, device=dev).view(torch.bfloat16)
+        dead = torch.from_numpy(~live_slot_mask(wl)).to(dev)
+        if kv_scales is not None:
+            x["k_pages"][dead] = 0x7F
+            x["v_pages"][dead] = 0x7F
+        else:
+            x["k_pages"][dead] = bad
+            x["v_pages"][dead] = bad
+        tmax = x["q"].shape[0]
+        if tmax > t_total:
+            for name in ("q", "k_new", "v_new"):
+                x[name][t_total:] = bad
+    return x

@@ -20,14 +20,37 @@ def to_f64(t):
     return t.detach().to("cpu").to(torch.float64).numpy()
 
 
+def plan_cuts(wl, causal=True, kv_scales=None, **knobs):
+    """Per sequence, the KV range boundaries of the work plan the library would use on
+    a 256-CU device (host-only planning call): where its tiles are cut into splits."""
+    shape = rpa.make_shape(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, max(1, wl.num_tokens),
+                           max(1, wl.num_seqs), wl.max_pages_per_seq, wl.num_pages, causal, kv_scales)
+    units, _, _ = rpa.plan_host(shape, wl.cu_q_lens, wl.kv_lens, 256, **knobs)
+    cuts = [set() for _ in range(wl.num_seqs)]
+    for u in units:
+        cuts[u[0]] |= {int(u[4]), int(u[5])}
+    return [sorted(c) for c in cuts]
+
+
 def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=True, pad_tokens=0,
              pad_seqs=0, seqs=None, calls=1, narrow_waves=0, units_per_cu=0, wide_rows=0, causal=True,
-             mixed_overlap=0, kv_scales=None):
-    """Run the HIP path and the oracle on the workload; returns a dict of results."""
+             mixed_overlap=0, kv_scales=None, needles=None):
+    """Run the HIP path and the oracle on the workload; returns a dict of results.
+    needles = (mode, seed): the discriminating inputs of workloads.materialize_needles
+    (every output row is the V row of one chosen position) instead of N(0,1) q and K."""
     dev = torch.device("cuda:0")
     max_tokens = wl.num_tokens + pad_tokens
     max_seqs = wl.num_seqs + pad_seqs
-    x = W.materialize(wl, dev, poison=poison, max_tokens=max(1, max_tokens), kv_scales=kv_scales)
+    if needles is None:
+        x = W.materialize(wl, dev, poison=poison, max_tokens=max(1, max_tokens), kv_scales=kv_scales)
+    else:
+        mode, nseed = needles
+        cuts = None
+        if mode == "boundaries":
+            cuts = plan_cuts(wl, causal, kv_scales, variant=variant, kv_chunk=kv_chunk, wide_kv_chunk=wide_kv_chunk,
+                             narrow_waves=narrow_waves, wide_rows=wide_rows, mixed_overlap=mixed_overlap)
+        targets = W.needle_targets(wl, mode, nseed, cuts, causal)
+        x = W.materialize_needles(wl, targets, dev, poison=poison, max_tokens=max(1, max_tokens), kv_scales=kv_scales)
     host = {k: W.bits(v) for k, v in x.items()}
     table = np.full((max(1, max_seqs), wl.max_pages_per_seq), -1, dtype=np.int32)
     table[:wl.num_seqs] = wl.page_table
@@ -66,6 +89,7 @@ def check(wl, res, seqs=None):
         assert np.isfinite(got[rows]).all(), "non-finite output"
         assert err.max() <= MAX_ABS, f"max abs err {err.max():.4g}"
         assert err.mean() <= MEAN_ABS, f"mean abs err {err.mean():.4g}"
+        res["err"] = (float(err.max()), float(err.mean()), float(np.sqrt((res["ref"][rows] ** 2).mean())))
     # padding rows are never written
     if got.shape[0] > t:
         assert torch.equal(res["out"][t:].view(torch.int16), res["sentinel"][t:].view(torch.int16))
@@ -634,41 +658,89 @@ def test_random_combinations(block):
 
 # ---------------------------------------------------------------------------
 # Full-size configs, in the launch configuration bench.py times (AUTO variant,
-# default chunking).  The cache is compared in full, bit for bit; outputs are
-# compared on a sample of sequences that the oracle computes one by one.
+# default chunking).  The cache is compared in full, bit for bit; the outputs of
+# EVERY sequence are compared element by element (config 5: every second
+# sequence with N(0,1) inputs, all of them with needle inputs).  Each config runs
+# on the N(0,1) recipe and on needle inputs (workloads.materialize_needles), whose
+# output rows each depend on one position: "boundaries" aims them at both sides of
+# every page, tile, cached/new and KV-split boundary of the plan in use, "spread"
+# visits as many different positions as there are queries.
 # ---------------------------------------------------------------------------
-def _full_case(idx, sample):
+def _full_case(idx, needles=None, seqs=None, **kw):
     wl = W.config(idx)
-    res = run_case(wl, seqs=sample(wl))
-    check(wl, res, seqs=sample(wl))
-    # every row of the batch must at least be finite
+    res = run_case(wl, seqs=seqs, needles=needles, **kw)
+    check(wl, res, seqs=seqs)
     t = wl.num_tokens
     assert torch.isfinite(res["out"][:t].float()).all()
+    print(f"\n[parity] config {idx} {'N(0,1)' if needles is None else 'needles ' + needles[0]} {kw or ''}: "
+          f"max abs err {res['err'][0]:.3e}, mean abs err {res['err'][1]:.3e}, output rms {res['err'][2]:.3f}")
+    if needles is not None:
+        # the inputs are what they claim: outputs are O(1), not averages that hide a wrong row
+        rows = np.isfinite(res["ref"][:t]).all(axis=(1, 2))
+        assert np.sqrt((res["ref"][:t][rows] ** 2).mean()) > 0.5
     return wl, res
 
 
-def test_full_config2_decode():
-    wl, res = _full_case(2, lambda wl: [0, 1, 17, 100, int(np.argmax(wl.kv_lens)), int(np.argmin(wl.kv_lens)), 255])
+@pytest.mark.parametrize("needles", [None, ("boundaries", 0), ("spread", 1)])
+def test_full_config2_decode(needles):
+    wl, res = _full_case(2, needles)
     assert res["info"]["variant"] == rpa.VARIANT_DECODE and res["info"]["max_splits"] > 1
 
 
-def test_full_config3_prefill():
-    wl, res = _full_case(3, lambda wl: [0, 5])
+@pytest.mark.parametrize("needles", [None, ("boundaries", 0), ("spread", 1)])
+def test_full_config3_prefill(needles):
+    wl, res = _full_case(3, needles)
     assert res["info"]["variant"] == rpa.VARIANT_PREFILL
 
 
-def test_full_config4_mixed():
-    def sample(wl):
-        chunks = np.nonzero(wl.q_lens > 1)[0].tolist()
-        dec = np.nonzero(wl.q_lens == 1)[0]
-        return chunks + dec[[0, 7, -1]].tolist() + [int(dec[np.argmax(wl.kv_lens[dec])])]
-    wl, res = _full_case(4, sample)
+@pytest.mark.parametrize("needles", [None, ("boundaries", 0), ("spread", 1)])
+def test_full_config4_mixed(needles):
+    wl, res = _full_case(4, needles)
     assert res["info"]["variant"] == rpa.VARIANT_MIXED and res["info"]["concurrent"] == 1
 
 
-def test_full_config5_long_decode():
-    wl, res = _full_case(5, lambda wl: [0, int(np.argmax(wl.kv_lens)), int(np.argmin(wl.kv_lens))])
+@pytest.mark.parametrize("needles,seqs", [(None, list(range(0, 32, 2))), (("boundaries", 0), None)])
+def test_full_config5_long_decode(needles, seqs):
+    wl, res = _full_case(5, needles, seqs=seqs)
     assert res["info"]["max_splits"] >= 4       # the long sequences are cut into many KV ranges
+
+
+@pytest.mark.parametrize("needles", [("boundaries", 2), ("spread", 3)])
+def test_full_configs_fp8_cache_needles(needles):
+    """Configs 2 and 4 over the 8-bit cache with needle inputs, every sequence."""
+    for idx in (2, 4):
+        wl = W.config(idx)
+        res = run_case(wl, kv_scales=KV_SCALES, needles=needles)
+        check(wl, res)
+
+
+# ---------------------------------------------------------------------------
+# Needle inputs on small batches: both kernels, forced splits, page sizes 16 and
+# 64, bf16 and 8-bit cache, with and without the mask.  "spread" on a prefill or a
+# long chunk visits every position of every KV head.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("mode", ["boundaries", "spread", "random"])
+@pytest.mark.parametrize("ps", [16, 64])
+@pytest.mark.parametrize("variant", [rpa.VARIANT_AUTO, rpa.VARIANT_DECODE, rpa.VARIANT_PREFILL])
+def test_needles_ragged(mode, ps, variant):
+    wl = W.ragged(5000 + ps, num_seqs=8, hq=32, hkv=8, d=128, ps=ps, max_q=600, max_ctx=2500, p_decode=0.3)
+    for chunk, scales in ((0, None), (192, None), (128, KV_SCALES)):
+        res = run_case(wl, variant=variant, kv_chunk=chunk, wide_kv_chunk=chunk, kv_scales=scales, needles=(mode, chunk),
+                       pad_tokens=3)
+        check(wl, res)
+
+
+@pytest.mark.parametrize("shape", [(4, 2, 64), (8, 8, 128), (16, 1, 128), (8, 2, 256)])
+@pytest.mark.parametrize("wide_rows", [128, 256])
+def test_needles_shapes_and_tile_heights(shape, wide_rows):
+    hq, hkv, d = shape
+    if d == 256 and wide_rows == 256:
+        pytest.skip("head_dim 256 has the 128-row wide shape only")
+    wl = W.ragged(5100 + hq + d, num_seqs=7, hq=hq, hkv=hkv, d=d, ps=16, max_q=500, max_ctx=1500, p_decode=0.3)
+    for mode in ("boundaries", "spread"):
+        for causal in (True, False):
+            res = run_case(wl, wide_rows=wide_rows, wide_kv_chunk=256, kv_chunk=160, needles=(mode, 5), causal=causal)
+            check(wl, res)
 
 
 # ---------------------------------------------------------------------------
