@@ -32,6 +32,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+MIN_WARMUP_CALLS = 100
+MIN_WARMUP_S = 0.05
+FLOOR = {"calls": MIN_WARMUP_CALLS}
 KV_SCALES = (1.0 / 64.0, 1.0 / 32.0)   # 8-bit cache block: N(0,1) / scale stays inside +-448
 
 
@@ -49,8 +52,17 @@ def time_steps(ctx, x, table, wl, steps, warmup):
 
     cu, kv = wl.cu_q_lens, wl.kv_lens
     out = torch.empty_like(x["q"])
-    for _ in range(warmup):
+    # The requested warm-up, then more until the GPU has been busy for at least
+    # MIN_WARMUP_CALLS calls and MIN_WARMUP_S seconds: the clocks of an idle GPU take
+    # some tens of milliseconds of load to settle, and the first calls of a short
+    # warm-up run up to 10 % slower than the steady state that is being measured.
+    t_w = time.perf_counter()
+    done = 0
+    while done < warmup or (FLOOR["calls"] > 0 and (done < FLOOR["calls"] or time.perf_counter() - t_w < MIN_WARMUP_S)):
         call()
+        done += 1
+        if done % 32 == 0:
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -82,12 +94,29 @@ def stream_copy(ctx, nbytes, reps):
 
 
 def load_traffic(workload, kernel):
+    """HBM bytes per launch from the tracked counter summary (two rocprofv3 --pmc
+    runs, FETCH_SIZE and WRITE_SIZE): a figure of those runs, not of this one."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
             return json.load(f)[workload][kernel]["hbm_bytes_per_launch"]
     except Exception:
         return None
+
+
+TRAFFIC_SOURCE = ("profiles/hbm_traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of the same workloads, "
+                  "scaled by the plain copy kernel; replayed from that file, not measured by this run")
+
+
+def narrow_part(wl):
+    """The sequences of a batch that the narrow kernel serves by default (at most
+    two narrow tiles of query tokens), as a workload of their own: only its
+    lengths are used, for byte counts."""
+    from paper_2604_15464_amd import workloads as W
+    hg = wl.num_q_heads // wl.num_kv_heads
+    keep = wl.q_lens <= 2 * (16 // hg)
+    return W.Workload(wl.name + "[narrow]", wl.seed, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size,
+                      wl.num_pages, wl.q_lens[keep], wl.kv_lens[keep], wl.page_table[keep])
 
 
 def cpu_baseline(wl, budget_s=15.0):
@@ -131,37 +160,8 @@ def cpu_baseline(wl, budget_s=15.0):
     return sub, sum(times) / len(times), len(times), cores
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-prefill", action="store_true")
-    ap.add_argument("--no-mixed", action="store_true")
-    ap.add_argument("--no-fp8", action="store_true")
-    ap.add_argument("--copy-bytes", type=int, default=1 << 30,
-                    help="size of the plain copy that calibrates HBM counters (0 = skip)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding in this path).")
-        sys.exit(2)
-    if args.steps < 1 or args.steps > 1024:
-        log("bench.py: --steps must be in 1..1024")
-        sys.exit(2)
-
-    import torch
-    from paper_2604_15464_amd import rpa
-    from paper_2604_15464_amd import workloads as W
-
-    if not torch.cuda.is_available():
-        log("bench.py: no GPU visible")
-        sys.exit(1)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    # ---- decode (headline) ----------------------------------------------------
-    wl = W.config(2)
+def decode_block(args, rpa, W, torch, dev, wl):
+    """The headline block: config 2, decode-only."""
     x = W.materialize(wl, dev, poison=False)
     table = torch.from_numpy(wl.page_table).to(dev)
     ctx = rpa.RaggedPagedAttention.for_workload(wl)
@@ -197,16 +197,77 @@ def main():
         "pct_of_peak_hbm": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "roofline": {"kernel": "rpa_narrow_kernel<128>", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": load_traffic(wl.name, "rpa_narrow_kernel"),
+                     "traffic": load_traffic(wl.name, "rpa_narrow_kernel"), "traffic_source": TRAFFIC_SOURCE,
                      "avg_kernel_ms": round(narrow_ms, 5)},
+        "warmup_effective": f"max(--warmup, {FLOOR['calls']} calls, {MIN_WARMUP_S} s) before every timed block",
     }
+    return result, dt, copy
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true",
+                    help="profiling runs only: skip the headline decode block (value is then null), so that every "
+                         "dispatch of a kernel in the run belongs to one block")
+    ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-mixed", action="store_true")
+    ap.add_argument("--no-fp8", action="store_true")
+    ap.add_argument("--min-warmup-calls", type=int, default=MIN_WARMUP_CALLS,
+                    help="floor on the warm-up calls of every timed block (counter-collection runs lower it)")
+    ap.add_argument("--only", default="", help="comma list of blocks to run besides the headline decode block: "
+                    "prefill,mixed,fp8,long_decode (default: all)")
+    ap.add_argument("--copy-bytes", type=int, default=1 << 30,
+                    help="size of the plain copy that calibrates HBM counters (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding in this path).")
+        sys.exit(2)
+    if args.steps < 1 or args.steps > 1024:
+        log("bench.py: --steps must be in 1..1024")
+        sys.exit(2)
+
+    import torch
+    from paper_2604_15464_amd import rpa
+    from paper_2604_15464_amd import workloads as W
+
+    FLOOR["calls"] = max(0, args.min_warmup_calls)
+    only = set(filter(None, args.only.split(",")))
+    if only - {"prefill", "mixed", "fp8", "long_decode", "none"}:
+        log("bench.py: --only takes prefill, mixed, fp8, long_decode, none")
+        sys.exit(2)
+
+    def wanted(block, off):
+        return not off and (not only or block in only)
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- decode (headline) ----------------------------------------------------
+    wl = W.config(2)
+    copy = None
+    if args.no_decode:
+        ctx0 = rpa.RaggedPagedAttention.for_workload(W.config(1))
+        copy = stream_copy(ctx0, args.copy_bytes - args.copy_bytes % 16, 4) if args.copy_bytes >= 16 else None
+        ctx0.close()
+        dt = float("nan")
+        result = {"metric": "decode HBM GB/s", "value": None, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+                  "warmup": args.warmup, "higher_is_better": True, "data": "synthetic", "dtype": "bf16",
+                  "config": {"workload": "headline decode block skipped (--no-decode)", "name": None}}
+    else:
+        result, dt, copy = decode_block(args, rpa, W, torch, dev, wl)
     if copy is not None:
         result["stream_copy"] = copy
-    del x, table
     torch.cuda.empty_cache()
 
     # ---- prefill (second half of the metric) -------------------------------------
-    if not args.no_prefill:
+    if wanted("prefill", args.no_prefill):
         wl3 = W.config(3)
         x3 = W.materialize(wl3, dev, poison=False)
         table3 = torch.from_numpy(wl3.page_table).to(dev)
@@ -230,14 +291,14 @@ def main():
             "roofline": {"kernel": "rpa_wide_kernel<128>", "bound": "mfma", "achieved": round(tf_k, 1),
                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": round(tf_k / MFMA_BF16_PEAK_TFLOPS, 4),
-                         "traffic": load_traffic(wl3.name, "rpa_wide_kernel"),
+                         "traffic": load_traffic(wl3.name, "rpa_wide_kernel"), "traffic_source": TRAFFIC_SOURCE,
                          "avg_kernel_ms": round(wide_ms, 5)},
         }
         del x3, table3
         torch.cuda.empty_cache()
 
     # ---- mixed batch (decode + chunked prefill in one call) ---------------------------
-    if not args.no_mixed:
+    if wanted("mixed", args.no_mixed):
         wl4 = W.config(4)
         x4 = W.materialize(wl4, dev, poison=False)
         table4 = torch.from_numpy(wl4.page_table).to(dev)
@@ -262,11 +323,25 @@ def main():
             "kernel_ms": {"narrow": round(prof4["narrow_ms"] / n4, 5), "wide": round(prof4["wide_ms"] / n4, 5),
                           "combine": round(prof4["combine_ms"] / n4, 5)},
         }
+        # The call's roof: its bytes at the HBM peak or its FLOPs at the MFMA peak,
+        # whichever takes longer (the two kernels run side by side).  The dominant
+        # kernel is the narrow one: its own bytes (the short-query sequences) over
+        # its own duration.
+        b4, f4 = wl4.algorithmic_bytes(), wl4.algorithmic_flops()
+        t_roof = max(b4 / (HBM_PEAK_GBPS * 1e9), f4 / (MFMA_BF16_PEAK_TFLOPS * 1e12))
+        nb4 = narrow_part(wl4).algorithmic_bytes()
+        ach4 = nb4 / (prof4["narrow_ms"] / n4 * 1e-3) / 1e9
+        result["mixed"]["roofline"] = {
+            "kernel": "rpa_narrow_kernel<128>", "bound": "hbm", "achieved": round(ach4, 1), "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": round(ach4 / HBM_PEAK_GBPS, 4), "algorithmic_bytes_of_kernel": nb4,
+            "traffic": load_traffic(wl4.name, "call"), "traffic_source": TRAFFIC_SOURCE,
+            "avg_kernel_ms": round(prof4["narrow_ms"] / n4, 5),
+            "call_roof_us": round(t_roof * 1e6, 1), "call_frac_of_roof": round(t_roof / (dt4 / args.steps), 4)}
         del x4, table4
         torch.cuda.empty_cache()
 
     # ---- decode over the 8-bit (E4M3, per-tensor scale) cache ---------------------------
-    if not args.no_fp8:
+    if wanted("fp8", args.no_fp8):
         x8 = W.materialize(wl, dev, poison=False, kv_scales=KV_SCALES)
         table8 = torch.from_numpy(wl.page_table).to(dev)
         ctx8 = rpa.RaggedPagedAttention.for_workload(wl, kv_scales=KV_SCALES)
@@ -281,15 +356,46 @@ def main():
             "config": {"workload": "the headline decode workload with rpa_shape.kv_fp8 = 1 (k_new / v_new bf16, "
                                    "quantised on the way in)", "algorithmic_bytes_per_step": b8,
                        "k_scale": KV_SCALES[0], "v_scale": KV_SCALES[1]},
-            "speedup_over_bf16_cache": round(dt / dt8, 3),
+            "speedup_over_bf16_cache": None if args.no_decode else round(dt / dt8, 3),
             "kernel_ms": {"narrow": round(prof8["narrow_ms"] / n8, 5), "combine": round(prof8["combine_ms"] / n8, 5)},
         }
         del x8, table8
         torch.cuda.empty_cache()
 
+    # ---- long-context skewed decode (32 sequences of 32 K - 128 K positions, page 64) ------
+    if wanted("long_decode", False):
+        wl5 = W.config(5)
+        x5 = W.materialize(wl5, dev, poison=False)
+        table5 = torch.from_numpy(wl5.page_table).to(dev)
+        ctx5 = rpa.RaggedPagedAttention.for_workload(wl5)
+        dt5, prof5, _ = time_steps(ctx5, x5, table5, wl5, args.steps, args.warmup)
+        info5 = ctx5.plan_info()
+        ctx5.close()
+        n5 = max(1, prof5["calls"])
+        b5 = wl5.algorithmic_bytes()
+        k5 = prof5["narrow_ms"] / n5
+        log(f"long decode: {dt5 / args.steps * 1e6:.1f} us/step, kernel {k5 * 1e3:.1f} us, combine "
+            f"{prof5['combine_ms'] / n5 * 1e3:.1f} us, plan {info5}")
+        result["long_decode"] = {
+            "metric": "decode HBM GB/s", "value": round(b5 / (dt5 / args.steps) / 1e9, 1), "unit": "GB/s",
+            "steps": args.steps, "ms_per_step": round(dt5 / args.steps * 1e3, 5),
+            "pct_of_peak_hbm": round(100.0 * b5 / (dt5 / args.steps) / 1e9 / HBM_PEAK_GBPS, 2),
+            "config": {"workload": "long-context skewed decode: 32 seqs, q_len 1, kv_len log-uniform in [32768, 131072], "
+                                   "Hq32 Hkv8 D128 page64", "name": wl5.name, "algorithmic_bytes_per_step": b5,
+                       "units": info5["num_narrow_units"], "bins": info5["num_narrow_bins"],
+                       "max_splits": info5["max_splits"]},
+            "roofline": {"kernel": "rpa_narrow_kernel<128>", "bound": "hbm", "achieved": round(b5 / (k5 * 1e-3) / 1e9, 1),
+                         "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(b5 / (k5 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                         "traffic": load_traffic(wl5.name, "rpa_narrow_kernel"), "traffic_source": TRAFFIC_SOURCE,
+                         "avg_kernel_ms": round(k5, 5)},
+            "kernel_ms": {"narrow": round(k5, 5), "combine": round(prof5["combine_ms"] / n5, 5)},
+        }
+        del x5, table5
+        torch.cuda.empty_cache()
+
     # ---- CPU oracle baseline ---------------------------------------------------------
     if not args.no_cpu_baseline:
-        sub, t_cpu, reps, cores = cpu_baseline(wl)
+        sub, t_cpu, reps, cores = cpu_baseline(wl)   # on the headline workload, whether or not its GPU block ran
         result["cpu_baseline"] = {
             "value": round(sub.algorithmic_bytes() / t_cpu / 1e9, 4), "unit": "GB/s", "cores": cores,
             "kind": "oracle",

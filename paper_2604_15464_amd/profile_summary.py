@@ -68,6 +68,9 @@ def kernels(src: str, out: str, command: str) -> None:
         r = rs[-1]
         lines.append(f"  {name:32s} n={len(rs):4d} steady_avg_us={avg:9.2f} grid_threads=({r[3]},{r[4]}) wg={r[5]} "
                      f"lds={r[6]} vgpr={r[7]} agpr={r[8]} scratch={r[9]}")
+        if len(rs) >= 8:
+            # the first launches in order: how long the kernel takes while the clocks settle
+            lines.append("    first launches (us): " + " ".join(f"{(q[2] - q[1]) / 1e3:.1f}" for q in rs[:25]))
     text = "\n".join(lines) + "\n"
     with open(out, "w") as f:
         f.write(text)
@@ -104,35 +107,59 @@ def traffic(fetch_dir: str, write_dir: str, out_json: str, out_txt: str, command
     kib = 1024.0
     cf = copy_bytes / (steady(fetch["rpa_copy_kernel"]) * kib)
     cw = copy_bytes / (steady(write["rpa_copy_kernel"]) * kib)
-    workloads = {
-        bench["config"]["name"]: {"rpa_narrow_kernel": bench["config"]["algorithmic_bytes_per_step"]},
-    }
+    # Which kernels a block of the bench line launches.  A run must be made so that
+    # every dispatch of a kernel belongs to one block (bench.py --only / --no-decode);
+    # "call" adds up all kernels of a block that launches several.
+    blocks = []
+    if bench.get("value") is not None:
+        blocks.append((bench["config"], ("rpa_narrow_kernel",)))
     if "prefill" in bench:
-        workloads[bench["prefill"]["config"]["name"]] = {
-            "rpa_wide_kernel": bench["prefill"]["config"]["algorithmic_bytes_per_step"]}
-    out = {"command": command,
-           "calibration": {"copy_bytes": copy_bytes, "fetch_scale": cf, "write_scale": cw,
-                           "note": "scale = known bytes of the plain copy kernel / (counter * 1024)"}}
+        blocks.append((bench["prefill"]["config"], ("rpa_wide_kernel",)))
+    if "mixed" in bench:
+        blocks.append((bench["mixed"]["config"], ("rpa_narrow_kernel", "rpa_wide_kernel", "rpa_combine_kernel")))
+    if "long_decode" in bench:
+        blocks.append((bench["long_decode"]["config"], ("rpa_narrow_kernel",)))
+    used = collections.Counter(k for _, ks in blocks for k in ks if k != "rpa_combine_kernel")
+    if any(n > 1 for n in used.values()):
+        raise SystemExit(f"a kernel is launched by several blocks of this run ({dict(used)}): profile them apart")
+    try:
+        with open(out_json) as f:
+            out = json.load(f)
+    except Exception:
+        out = {}
+    out.setdefault("runs", {})
     lines = [f"command: {command}",
              "source: two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), csv output",
              f"calibration: rpa_copy_kernel moves {copy_bytes} B each way; FETCH_SIZE reads "
              f"{steady(fetch['rpa_copy_kernel']):.0f} KiB -> scale {cf:.4f}; WRITE_SIZE reads "
              f"{steady(write['rpa_copy_kernel']):.0f} KiB -> scale {cw:.4f}", "",
-             f"{'workload':16s} {'kernel':28s} {'fetch_B':>14s} {'write_B':>14s} {'hbm_B/launch':>14s} "
+             f"{'workload':28s} {'kernel':20s} {'fetch_B':>14s} {'write_B':>14s} {'hbm_B/launch':>14s} "
              f"{'algorithmic_B':>14s} {'ratio':>6s}"]
-    for wname, ks in workloads.items():
+    for cfg, ks in blocks:
+        wname, alg = cfg["name"], cfg["algorithmic_bytes_per_step"]
         out[wname] = {}
-        for kname, alg in ks.items():
-            # the decode workload launches only the narrow kernel and the prefill
-            # workload only the wide one, so every dispatch of a kernel belongs to one workload
-            grids = collections.Counter(g for _, g in fetch[kname])
+        out["runs"][wname] = {"command": command, "calibration": {"copy_bytes": copy_bytes, "fetch_scale": cf,
+                                                                   "write_scale": cw}}
+        tot_f = tot_w = 0.0
+        for kname in ks:
+            if kname not in fetch:
+                continue
             fb = steady(fetch[kname]) * kib * cf
             wb = steady(write[kname]) * kib * cw
+            tot_f += fb
+            tot_w += wb
             out[wname][kname] = {"hbm_bytes_per_launch": round(fb + wb), "fetch_bytes": round(fb),
-                                               "write_bytes": round(wb), "algorithmic_bytes": alg,
-                                               "launches": len(fetch[kname]), "grids": dict(grids)}
-            lines.append(f"{wname:16s} {kname:28s} {fb:14.0f} {wb:14.0f} {fb + wb:14.0f} {alg:14d} "
-                         f"{(fb + wb) / alg:6.3f}")
+                                 "write_bytes": round(wb), "launches": len(fetch[kname]),
+                                 "grids": dict(collections.Counter(g for _, g in fetch[kname]))}
+            if len(ks) == 1:
+                out[wname][kname]["algorithmic_bytes"] = alg
+            lines.append(f"{wname:28s} {kname:20s} {fb:14.0f} {wb:14.0f} {fb + wb:14.0f} "
+                         + (f"{alg:14d} {(fb + wb) / alg:6.3f}" if len(ks) == 1 else ""))
+        if len(ks) > 1:
+            out[wname]["call"] = {"hbm_bytes_per_launch": round(tot_f + tot_w), "fetch_bytes": round(tot_f),
+                                  "write_bytes": round(tot_w), "algorithmic_bytes": alg}
+            lines.append(f"{wname:28s} {'call (all kernels)':20s} {tot_f:14.0f} {tot_w:14.0f} {tot_f + tot_w:14.0f} "
+                         f"{alg:14d} {(tot_f + tot_w) / alg:6.3f}")
     with open(out_json, "w") as f:
         json.dump(out, f, indent=1)
         f.write("\n")
