@@ -609,14 +609,15 @@ rpa_wide_kernel(KernelArgs a) {
     // starting at a multiple of WPOS: they lie in one page (a page holds at least
     // 16 positions), and so do they after clamping to the end of the range.
     static_assert(WPOS <= 16 && 16 % WPOS == 0, "a wave's share of a tile must lie in one page");
-    auto issue_tile = [&](int t) __attribute__((always_inline)) {
+    int page_pre = 0; // page id requested at the end of the previous step (see tile_step)
+    auto issue_tile = [&](int t, bool have_page) __attribute__((always_inline)) {
         if (RPA_ABLATED(a, 64)) return; // measurement: no K/V traffic
         const int p0w = kv_begin + t * KT + WPOS * wave; // this wave's positions
         const int slot = t % NST;
         const uint32_t ldsK = lds_base + slot * STAGEB + (WPOS * wave) * ROWB;
         const uint32_t ldsV = ldsK + TILEB;
         const int pidx = __builtin_amdgcn_readfirstlane(min(p0w, kv_end - 1) >> ps_log2);
-        const int page = clamp_page(pt_row[pidx], num_pages);
+        const int page = clamp_page(have_page ? page_pre : pt_row[pidx], num_pages);
         const bool all_cached = p0w + WPOS <= min(ctx, kv_end);
         const bool all_new = p0w >= ctx && p0w + WPOS <= kv_end;
         if (all_cached || all_new) {
@@ -878,7 +879,7 @@ rpa_wide_kernel(KernelArgs a) {
     constexpr int LPT = 2 * NLD; // loads per wave per tile
 #pragma unroll
     for (int s0 = 0; s0 < NST - 1; ++s0)
-        if (s0 < ntiles) issue_tile(s0);
+        if (s0 < ntiles) issue_tile(s0, false);
     // The Q rows are fetched behind the first tiles so that the two latencies
     // overlap; loads complete in order, hence waiting for Q waits for those tiles.
 #pragma unroll
@@ -895,13 +896,24 @@ rpa_wide_kernel(KernelArgs a) {
     __syncthreads();
 
     auto tile_step = [&](int t, auto slot) __attribute__((always_inline)) {
-        if (t + NST - 1 < ntiles) issue_tile(t + NST - 1);
+        // the page id requested at the end of the previous step has had the barrier's time to return
+        if (t > 0) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(page_pre));
+        if (t + NST - 1 < ntiles) issue_tile(t + NST - 1, t > 0);
         // relative to the ring: koff / voff carry the ring's own LDS address
         const uint32_t ldsK = (int)slot * STAGEB;
         const uint32_t ldsV = ldsK + TILEB;
         const int pos0 = kv_begin + t * KT;
         // tiles wholly above the wave's diagonal are skipped
         if (pos0 <= wave_limit && !RPA_ABLATED(a, 128)) compute_tile(ldsK, ldsV, pos0);
+        // The page id of the share this wave brings in the NEXT step is requested now,
+        // after the tile's last operand read and ahead of the waits below, so that its
+        // latency passes under them instead of stalling the wave at the start of the
+        // next step (a scalar load that is outstanding while operands are read from
+        // LDS would turn every wait for those into a full wait: both use one counter).
+        {
+            const int p_next = min(kv_begin + (t + NST) * KT + WPOS * wave, kv_end - 1);
+            asm volatile("s_load_dword %0, %1, %2" : "=s"(page_pre) : "s"(pt_row), "s"((p_next >> ps_log2) << 2));
+        }
         // tile t+1 must have landed; tiles t+2 .. may still be in flight
         const int behind = min(NST - 2, ntiles - 2 - t);
         if (NST >= 4 && behind >= 2) wait_vmcnt<(NST >= 4 ? 2 : 0) * LPT>();
