@@ -896,8 +896,6 @@ rpa_wide_kernel(KernelArgs a) {
     __syncthreads();
 
     auto tile_step = [&](int t, auto slot) __attribute__((always_inline)) {
-        // the page id requested at the end of the previous step has had the barrier's time to return
-        if (t > 0) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(page_pre));
         if (t + NST - 1 < ntiles) issue_tile(t + NST - 1, t > 0);
         // relative to the ring: koff / voff carry the ring's own LDS address
         const uint32_t ldsK = (int)slot * STAGEB;
@@ -920,6 +918,10 @@ rpa_wide_kernel(KernelArgs a) {
         else if (NST >= 3 && behind == 1) wait_vmcnt<(NST >= 3 ? 1 : 0) * LPT>();
         else wait_vmcnt<0>();
         __syncthreads();
+        // The page id has had the barrier's time to return.  It is waited for here, in
+        // the step that requested it, also when no step follows: the register it lands
+        // in belongs to it only until this statement.
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(page_pre));
     };
     if constexpr (D <= 128) {
         // Unrolled over the ring so that a tile's stage is a compile-time constant:
