@@ -204,7 +204,7 @@ extern "C" int rpa_set_options(rpa_ctx* c, const rpa_options* opt) {
         (o.narrow_waves > 0 && c->shape.num_kv_heads % o.narrow_waves != 0) ||
         (o.wide_rows != 0 && o.wide_rows != 128 && o.wide_rows != 256) || o.wide_order < 0 || o.wide_order > 2 ||
         o.mixed_overlap < 0 || o.mixed_overlap > 2 || o.stream_ordered_upload < 0 || o.stream_ordered_upload > 1 ||
-        !options_fit_shape(c->shape, o))
+        o.wide_persistent < 0 || o.wide_persistent > 1 || !options_fit_shape(c->shape, o))
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: bad value");
 #ifdef RPA_ABLATE
     if (o.ablate & ~(1 | 2 | 4 | 64 | 128 | 256 | 512))
@@ -453,6 +453,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     a.causal = c->shape.non_causal ? 0 : 1;
     a.kv_fp8 = c->shape.kv_fp8;
     a.out_scale = 1.f;
+    a.wide_persist_grid = opt_used.wide_persistent == 1 ? 0 : c->num_cus;
     if (a.kv_fp8) {
         // The new rows are quantised into the staging copy first; from there on the
         // kernels see bytes only.  K's scale folds into the softmax scale, V's is

@@ -505,10 +505,18 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 // kernel.  Rows are 128 bytes, operands are widened to bf16 after the LDS read
 // (the V^T fragment comes from the 8-bit transposing read), the MFMAs and the
 // softmax are the same.
-template <int D, int WAVES, int NST, bool KV8>
+//
+// PERSIST (the 8-wave bf16 shape): one workgroup per CU walks (unit, KV head)
+// items instead of ending after one.  The next item's Q tile arrives through the
+// ring slots that fall idle during the last steps of the current item, and its
+// first K/V tiles are requested before the current item's output rows are
+// stored, so that neither a workgroup launch, nor the Q fetch, nor the drain of
+// the output stores stands between two items.
+template <int D, int WAVES, int NST, bool KV8, bool PERSIST = false>
 __global__ void __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(D > 128 ? 1 : 2)))
 rpa_wide_kernel(KernelArgs a) {
     static_assert(!KV8 || D == 128, "the 8-bit wide kernel is built for head_dim 128");
+    static_assert(!PERSIST || (!KV8 && WAVES == 8 && NST == 3 && D <= 128), "shape the persistent loop is built for");
     constexpr int NT = 1; // 32-row groups per wave
     constexpr int ROWB = D * (KV8 ? 1 : 2); // bytes of a K/V row of one head
     constexpr int OROWB = D * 2;            // bytes of a q / out row of one head
@@ -528,25 +536,41 @@ rpa_wide_kernel(KernelArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int Hkv = a.num_kv_heads;
-    const int unit_idx = blockIdx.x / Hkv;
-    const int g = blockIdx.x - unit_idx * Hkv;
     const int n32 = lane & 31;
     const int h = lane >> 5;
 
-    const rpa_work_unit u = a.units[unit_idx];
+    // An item is a (unit, KV head) pair, in launch order.  A persistent workgroup
+    // takes item blockIdx.x of every round of gridDim.x items, rounds alternating in
+    // direction so that the long and the short items of the sorted list even out.
+    int round = 0;
+    auto item_of_round = [&](int r) {
+        const int idx = r * (int)gridDim.x + ((r & 1) ? (int)gridDim.x - 1 - (int)blockIdx.x : (int)blockIdx.x);
+        return (PERSIST && idx < a.num_wide_items) ? idx : -1;
+    };
+    // unit records are read through the constant address space: scalar loads, so
+    // that everything derived from them stays in scalar registers
+    auto load_unit = [&](int idx) {
+        const const_i32_ptr p = (const_i32_ptr)(uintptr_t)(a.units + idx);
+        rpa_work_unit r;
+        r.seq = p[0], r.q_start = p[1], r.q_pos0 = p[2], r.n_q = p[3], r.kv_begin = p[4], r.kv_end = p[5];
+        r.ctx = p[6], r.seq_q0 = p[7], r.part_row = p[8], r.flags = p[9], r.bin = p[10], r.reserved = p[11];
+        return r;
+    };
+    int g = (int)blockIdx.x % Hkv;
+    rpa_work_unit u = load_unit(blockIdx.x / Hkv);
     const int hg = a.hg;
     const int Hq = a.num_q_heads;
     const int ps_log2 = a.page_size_log2;
     const int ps_mask = (1 << ps_log2) - 1;
     const int num_pages = a.num_pages;
-    const int ctx = u.ctx;
+    int ctx = u.ctx;
     const int tq_log2 = a.wide_tq_log2;
     const int tq_mask = (1 << tq_log2) - 1;
     const char* const k_pages = (const char*)a.k_pages;
     const char* const v_pages = (const char*)a.v_pages;
     const char* const k_new = (const char*)a.k_new;
     const char* const v_new = (const char*)a.v_new;
-    const const_i32_ptr pt_row = (const_i32_ptr)(uintptr_t)(a.page_table + (size_t)u.seq * a.max_pages_per_seq);
+    const_i32_ptr pt_row = (const_i32_ptr)(uintptr_t)(a.page_table + (size_t)u.seq * a.max_pages_per_seq);
     const uint32_t tokstride = (uint32_t)Hkv * ROWB;
     const uint64_t k_delta = (uint64_t)k_pages - (uint64_t)k_new;
     const uint64_t v_delta = (uint64_t)v_pages - (uint64_t)v_new;
@@ -555,8 +579,33 @@ rpa_wide_kernel(KernelArgs a) {
     int tok[NT], head[NT], limit[NT];
     bool row_ok[NT];
     bf16x8 qreg[NT][KSTEPS];
+    // LDS swizzle: 16-byte chunk c of tile row r sits at chunk position c ^ swz(r).
+    // swz permutes the bits of r so that both kinds of operand read touch every
+    // bank once: a K read (ds_read_b128) takes one chunk from 16 consecutive rows,
+    // a transposing V read takes four adjacent chunks from four consecutive rows.
+    // LDS banks repeat every 256 bytes, i.e. every row at D = 128 (every half row at
+    // D = 256, where the swizzle leaves the chunk's top bit alone) and every second
+    // row at D = 64, where the row's parity already separates two rows.
+    // With 8-bit elements a row is 128 bytes (8 chunks, two rows per bank period)
+    // and operand reads are 8 bytes wide: the row's parity separates two rows, and
+    // bits 1..3 of the row index, permuted, spread the eight rows of a K read and
+    // the position pairs of a transposing V read over the eight chunk positions.
+    auto swz = [](int r) {
+        if (KV8) return (((r >> 1) & 1) << 1) | (((r >> 3) & 1) << 2) | ((r >> 2) & 1);
+        return D >= 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
+    };
     int wave_limit = -1;           // positions above it are hidden from every row of the wave
     int wave_min_limit = 1 << 30;  // positions up to it are visible to every live row of the wave
+    int kv_begin = 0, kv_end = 0, ntiles = 0;
+    const int ld_tok = lane / NC;
+    const int ld_chunk = lane % NC;
+    uint32_t lane_voff[NLD]; // byte offset of the lane's chunk of load i from the first token of the wave's share
+    // everything that depends on the item (u, g)
+    auto setup_item = [&]() __attribute__((always_inline)) {
+    ctx = u.ctx;
+    pt_row = (const_i32_ptr)(uintptr_t)(a.page_table + (size_t)u.seq * a.max_pages_per_seq);
+    wave_limit = -1;
+    wave_min_limit = 1 << 30;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int rho = 32 * (NT * wave + nt) + n32;
@@ -575,35 +624,19 @@ rpa_wide_kernel(KernelArgs a) {
         }
     }
     if (wave_limit < 0) wave_min_limit = -1;
-
-    const uint32_t lds_base = lds_offset(smem);
-    const int kv_begin = u.kv_begin, kv_end = u.kv_end;
-    const int ntiles = max(0, (kv_end - kv_begin + KT - 1) / KT);
-
-    // LDS swizzle: 16-byte chunk c of tile row r sits at chunk position c ^ swz(r).
-    // swz permutes the bits of r so that both kinds of operand read touch every
-    // bank once: a K read (ds_read_b128) takes one chunk from 16 consecutive rows,
-    // a transposing V read takes four adjacent chunks from four consecutive rows.
-    // LDS banks repeat every 256 bytes, i.e. every row at D = 128 (every half row at
-    // D = 256, where the swizzle leaves the chunk's top bit alone) and every second
-    // row at D = 64, where the row's parity already separates two rows.
-    // With 8-bit elements a row is 128 bytes (8 chunks, two rows per bank period)
-    // and operand reads are 8 bytes wide: the row's parity separates two rows, and
-    // bits 1..3 of the row index, permuted, spread the eight rows of a K read and
-    // the position pairs of a transposing V read over the eight chunk positions.
-    auto swz = [](int r) {
-        if (KV8) return (((r >> 1) & 1) << 1) | (((r >> 3) & 1) << 2) | ((r >> 2) & 1);
-        return D >= 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
-    };
-    const int ld_tok = lane / NC;
-    const int ld_chunk = lane % NC;
-    // byte offset of the lane's chunk of load i from the first token of the wave's share
-    uint32_t lane_voff[NLD];
+    kv_begin = u.kv_begin;
+    kv_end = u.kv_end;
+    ntiles = max(0, (kv_end - kv_begin + KT - 1) / KT);
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
         const int r = WPOS * wave + i * TPI + ld_tok; // row inside the 64-position tile
         lane_voff[i] = (uint32_t)(i * TPI + ld_tok) * tokstride + (uint32_t)g * ROWB + (uint32_t)((ld_chunk ^ swz(r)) * 16);
     }
+    };
+
+    const uint32_t lds_base = lds_offset(smem);
+
+    setup_item();
 
     // The positions a wave brings for one tile are WPOS <= 16 consecutive ones
     // starting at a multiple of WPOS: they lie in one page (a page holds at least
@@ -877,26 +910,106 @@ rpa_wide_kernel(KernelArgs a) {
     // a tile has NST-1 tile times to arrive.  Each wave waits for its own loads
     // of the next tile, the barrier then makes the whole tile visible.
     constexpr int LPT = 2 * NLD; // loads per wave per tile
+
+    // ---- persistent workgroups: the next item and its Q tile -------------------------
+    // The Q tile of the NEXT item travels through the ring as NST-1 more "tiles" of
+    // the current item (virtual tiles ntiles .. ntiles+NST-2, in the slots that fall
+    // idle once the item's last K/V tiles have been requested): part p holds the
+    // rows of the tile's tokens [p * TQH, (p+1) * TQH) for the h_g heads, in the
+    // order they lie in memory (a token's h_g head rows are contiguous there, so
+    // the loads are whole lines), LPT loads per wave like a K/V tile, which keeps
+    // the loop's vmcnt arithmetic unchanged.  Chunk c of a row sits at position
+    // c ^ (token % chunks-per-row), so that the operand reads below (32 consecutive
+    // tokens, one chunk each) spread over the banks.
+    constexpr int QROWS = STAGEB / OROWB;                 // rows of a Q part (one ring slot)
+    static_assert(!PERSIST || (ROWB == OROWB && (NST - 1) * QROWS == 32 * WAVES && QROWS % (WAVES * LPT) == 0 &&
+                               QROWS / (WAVES * LPT) == 64 / ONC),
+                  "a Q tile must fill the ring's idle slots with LPT loads per wave and slot");
+    const int hg_log2 = 31 - __builtin_clz((unsigned)hg);
+    const int tqh_log2 = tq_log2 - (NST == 3 ? 1 : 0);    // log2 of the tokens per Q part
+    int item_n = -1;        // the item after the current one, or -1
+    rpa_work_unit un = u;
+    int gn = g;
+    auto issue_q = [&](const rpa_work_unit& uq, int gq, int part, int slot) __attribute__((always_inline)) {
+        const uint32_t lds = lds_base + slot * STAGEB + wave * (LPT * 1024);
 #pragma unroll
-    for (int s0 = 0; s0 < NST - 1; ++s0)
-        if (s0 < ntiles) issue_tile(s0, false);
-    // The Q rows are fetched behind the first tiles so that the two latencies
-    // overlap; loads complete in order, hence waiting for Q waits for those tiles.
+        for (int i = 0; i < LPT; ++i) {
+            const int r_lin = (wave * LPT + i) * (64 / ONC) + lane / ONC;   // row inside the part
+            const int tk = (part << tqh_log2) + (r_lin >> hg_log2);
+            const int hh = r_lin & (hg - 1);
+            const int tkc = min(tk, uq.n_q - 1);                             // rows past the tile re-read its last token
+            const int c = (lane % ONC) ^ (tk & (ONC - 1));
+            const uint16_t* src = a.q + ((size_t)(uq.q_start + tkc) * Hq + gq * hg + hh) * D + c * 8;
+            async_load16(src, lds + i * 1024);
+        }
+    };
+    // Q operands of the current item from the parts that start in ring slot `slot0`.
+    auto read_q = [&](int slot0) __attribute__((always_inline)) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok[nt] ? tok[nt] : 0)) * Hq + head[nt]) * D;
+        for (int nt = 0; nt < NT; ++nt) {
+            const int rho = 32 * (NT * wave + nt) + n32;
+            const int hh = rho >> tq_log2, tk = rho & tq_mask;
+            const int part = tk >> tqh_log2;
+            const int r_lin = ((tk - (part << tqh_log2)) << hg_log2) + hh;
+            int slot = slot0 + part;
+            if (slot >= NST) slot -= NST;
+            const char* row = (const char*)smem + slot * STAGEB + r_lin * OROWB;
 #pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (row_ok[nt]) raw = *(const uint4*)(qrow + kk * 16 + h * 8);
-            qreg[nt][kk] = __builtin_bit_cast(bf16x8, raw);
+            for (int kk = 0; kk < KSTEPS; ++kk) {
+                uint4 raw = *(const uint4*)(row + (((2 * kk + h) ^ (tk & (ONC - 1))) * 16));
+                if (!row_ok[nt]) raw = make_uint4(0, 0, 0, 0);
+                qreg[nt][kk] = __builtin_bit_cast(bf16x8, raw);
+            }
+        }
+    };
+    // virtual tile T of the current item: a K/V tile, or a part of the next item's Q tile
+    auto issue_virtual = [&](int T, bool have_page) __attribute__((always_inline)) {
+        if (T < ntiles) {
+            issue_tile(T, have_page);
+        } else if (PERSIST && item_n >= 0 && T < ntiles + NST - 1) {
+            int slot = T % NST;
+            issue_q(un, gn, T - ntiles, slot);
+        }
+    };
+    auto fetch_next_item = [&]() __attribute__((always_inline)) {
+        item_n = item_of_round(round + 1);
+        if (item_n >= 0) {
+            un = load_unit(item_n / Hkv);
+            gn = item_n % Hkv;
+        }
+    };
+
+    if constexpr (PERSIST) {
+        // the first item's Q tile, through slots 0 .. NST-2
+#pragma unroll
+        for (int p0 = 0; p0 < NST - 1; ++p0) issue_q(u, g, p0, p0);
+        wait_vmcnt<0>();
+        __syncthreads();
+        read_q(0);
+        __syncthreads(); // every wave holds its operands before the slots take K/V tiles
+        fetch_next_item();
+    }
+#pragma unroll
+    for (int s0 = 0; s0 < NST - 1; ++s0) issue_virtual(s0, false);
+    if constexpr (!PERSIST) {
+        // The Q rows are fetched behind the first tiles so that the two latencies
+        // overlap; loads complete in order, hence waiting for Q waits for those tiles.
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok[nt] ? tok[nt] : 0)) * Hq + head[nt]) * D;
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) {
+                uint4 raw = make_uint4(0, 0, 0, 0);
+                if (row_ok[nt]) raw = *(const uint4*)(qrow + kk * 16 + h * 8);
+                qreg[nt][kk] = __builtin_bit_cast(bf16x8, raw);
+            }
         }
     }
     wait_vmcnt<0>();
     __syncthreads();
 
     auto tile_step = [&](int t, auto slot) __attribute__((always_inline)) {
-        if (t + NST - 1 < ntiles) issue_tile(t + NST - 1, t > 0);
+        issue_virtual(t + NST - 1, t > 0);
         // relative to the ring: koff / voff carry the ring's own LDS address
         const uint32_t ldsK = (int)slot * STAGEB;
         const uint32_t ldsV = ldsK + TILEB;
@@ -910,10 +1023,18 @@ rpa_wide_kernel(KernelArgs a) {
         // LDS would turn every wait for those into a full wait: both use one counter).
         {
             const int p_next = min(kv_begin + (t + NST) * KT + WPOS * wave, kv_end - 1);
-            asm volatile("s_load_dword %0, %1, %2" : "=s"(page_pre) : "s"(pt_row), "s"((p_next >> ps_log2) << 2));
+            // the table row's address is wave-uniform; it is made scalar for the operand below
+            // (the halves go through unsigned variables: the builtin returns a signed int)
+            const uint64_t pv = (uint64_t)(uintptr_t)pt_row;
+            const uint32_t pv_lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)pv);
+            const uint32_t pv_hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(pv >> 32));
+            const uint64_t ps = ((uint64_t)pv_hi << 32) | pv_lo;
+            const uint32_t poff = (uint32_t)__builtin_amdgcn_readfirstlane((p_next >> ps_log2) << 2);
+            asm volatile("s_load_dword %0, %1, %2" : "=s"(page_pre) : "s"(ps), "s"(poff));
         }
-        // tile t+1 must have landed; tiles t+2 .. may still be in flight
-        const int behind = min(NST - 2, ntiles - 2 - t);
+        // tile t+1 must have landed; virtual tiles t+2 .. may still be in flight
+        const int nvt = ntiles + ((PERSIST && item_n >= 0) ? NST - 1 : 0);
+        const int behind = min(NST - 2, nvt - 2 - t);
         if (NST >= 4 && behind >= 2) wait_vmcnt<(NST >= 4 ? 2 : 0) * LPT>();
         else if (NST >= 3 && behind == 1) wait_vmcnt<(NST >= 3 ? 1 : 0) * LPT>();
         else wait_vmcnt<0>();
@@ -923,96 +1044,210 @@ rpa_wide_kernel(KernelArgs a) {
         // in belongs to it only until this statement.
         asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(page_pre));
     };
-    if constexpr (D <= 128) {
-        // Unrolled over the ring so that a tile's stage is a compile-time constant:
-        // the stage base then sits in the offset field of every LDS read instead of
-        // costing a vector add per operand (-1.7 %; at D = 256 the doubled loop body
-        // costs more than that saves).
-        static_assert(NST == 2 || NST == 3, "ring depths the loop is unrolled for");
-        for (int t = 0; t < ntiles; t += NST) { // ntiles is the same for every wave: barriers stay matched
-            tile_step(t, std::integral_constant<int, 0>{});
-            if (t + 1 < ntiles) tile_step(t + 1, std::integral_constant<int, 1>{});
-            if constexpr (NST == 3) {
-                if (t + 2 < ntiles) tile_step(t + 2, std::integral_constant<int, 2>{});
-            }
-        }
-    } else {
-        for (int t = 0; t < ntiles; ++t) tile_step(t, t % NST);
-    }
 
-    // ---- finalize (Alg. 1: diag(l)^-1 B_o) or store the partial state ------------
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
-        if (RPA_ABLATED(a, 256)) continue;
-        if (!row_ok[nt] && u.part_row >= 0) continue;
-        if (u.part_row < 0) {
-            // Rows go through this wave's slice of the (now idle) LDS ring so that
-            // the global stores are whole 256-byte rows, 16 lanes per row.  The
-            // loop's last barrier guarantees nobody still reads the ring.
-            constexpr int SROW = OROWB + 16; // padded row: conflict-free 8-byte writes
-            char* stage = (char*)smem + (size_t)(NT * wave + nt) * 32 * SROW;
-            const float inv = l_tot > 0.f ? a.out_scale / l_tot : 0.f; // out_scale: V scale of an 8-bit cache, else 1
-            // accumulator element v of block jb is dim 32*jb + 8*(v/4) + 4*h + v%4
-#pragma unroll
-            for (int jb = 0; jb < DPL; ++jb)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    uint2 w;
-                    w.x = pack_bf16(o[nt][jb][4 * q4] * inv, o[nt][jb][4 * q4 + 1] * inv);
-                    w.y = pack_bf16(o[nt][jb][4 * q4 + 2] * inv, o[nt][jb][4 * q4 + 3] * inv);
-                    *(uint2*)(stage + n32 * SROW + (32 * jb + 8 * q4 + 4 * h) * 2) = w;
-                }
-        } else {
-            const size_t prow = (size_t)u.part_row + (size_t)tok[nt] * Hq + head[nt];
-            float* po = a.part_o + prow * D;
-#pragma unroll
-            for (int jb = 0; jb < DPL; ++jb)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const float os = KV8 ? a.out_scale : 1.f; // partial sums carry the V scale
-                    float4 w = make_float4(o[nt][jb][4 * q4] * os, o[nt][jb][4 * q4 + 1] * os, o[nt][jb][4 * q4 + 2] * os,
-                                           o[nt][jb][4 * q4 + 3] * os);
-                    *(float4*)(po + 32 * jb + 8 * q4 + 4 * h) = w;
-                }
-            if (h == 0) {
-                a.part_ml[prow * 2] = m_run[nt];
-                a.part_ml[prow * 2 + 1] = l_tot;
-            }
-        }
-    }
-
-    if (u.part_row < 0 && !RPA_ABLATED(a, 256)) {
-        constexpr int SROW = OROWB + 16;
-        constexpr int RPI = 64 / ONC; // rows per wave-wide 16-byte store
+    // What the second half of an item's epilogue needs once u, g and the row
+    // variables describe the next item (all wave-uniform).
+    struct Fin {
+        int q_start, n_q, part_row, g, flags, q_pos0, ctx;
+        const_i32_ptr pt_row;
+    };
+    // Output rows go through LDS so that the global stores are whole rows, 16 bytes
+    // per lane.  Non-persistent: this wave's slice of the (now idle) ring, rows
+    // padded by 16 bytes.  Persistent: a region of its own behind the ring (the ring
+    // already takes the next item's tiles then), rows unpadded, 16-byte chunk c of
+    // row r at position c ^ (r % chunks-per-row).  Either way a wave stages and
+    // reads back only its own rows.
+    constexpr int SROW = PERSIST ? OROWB : OROWB + 16;
+    // First half, for the CURRENT item (u, g, tok, head, row_ok): finalize
+    // (Alg. 1: diag(l)^-1 B_o) into the staging rows, or store the partial state.
+    // The accumulators are free afterwards.
+    auto finalize_stage = [&]() __attribute__((always_inline)) {
+        // lane-dependent terms are taken through an opaque copy: in the persistent loop
+        // the compiler would otherwise compute every address of this block once, ahead
+        // of the item loop, and keep them all in registers across it
+        int n32v = n32, hv = h;
+        if constexpr (PERSIST) asm volatile("" : "+v"(n32v), "+v"(hv));
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            const char* stage = (const char*)smem + (size_t)(NT * wave + nt) * 32 * SROW;
+            const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
+            if (RPA_ABLATED(a, 256)) continue;
+            if (!row_ok[nt] && u.part_row >= 0) continue;
+            if (u.part_row < 0) {
+                char* stage = (char*)smem + (PERSIST ? NST * STAGEB : 0) + (size_t)(NT * wave + nt) * 32 * SROW;
+                const float inv = l_tot > 0.f ? a.out_scale / l_tot : 0.f; // out_scale: V scale of an 8-bit cache, else 1
+                // accumulator element v of block jb is dim 32*jb + 8*(v/4) + 4*h + v%4
 #pragma unroll
-            for (int i = 0; i < 32 / RPI; ++i) {
-                const int r = i * RPI + lane / ONC;
-                const int rho = 32 * (NT * wave + nt) + r;
-                const int t_r = rho & tq_mask, h_r = rho >> tq_log2;
-                const uint4 w = *(const uint4*)(stage + r * SROW + (lane % ONC) * 16);
-                if (t_r < u.n_q)
-                    store16_streaming(a.out + ((size_t)(u.q_start + t_r) * Hq + g * hg + h_r) * D + (lane % ONC) * 8, w);
+                for (int jb = 0; jb < DPL; ++jb)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        uint2 w;
+                        w.x = pack_bf16(o[nt][jb][4 * q4] * inv, o[nt][jb][4 * q4 + 1] * inv);
+                        w.y = pack_bf16(o[nt][jb][4 * q4 + 2] * inv, o[nt][jb][4 * q4 + 3] * inv);
+                        if constexpr (PERSIST)
+                            *(uint2*)(stage + n32v * SROW + (((4 * jb + q4) ^ (n32v & (ONC - 1))) * 16) + 8 * hv) = w;
+                        else
+                            *(uint2*)(stage + n32v * SROW + (32 * jb + 8 * q4 + 4 * hv) * 2) = w;
+                    }
+            } else {
+                const size_t prow = (size_t)u.part_row + (size_t)tok[nt] * Hq + head[nt];
+                float* po = a.part_o + prow * D;
+#pragma unroll
+                for (int jb = 0; jb < DPL; ++jb)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const float os = KV8 ? a.out_scale : 1.f; // partial sums carry the V scale
+                        float4 w = make_float4(o[nt][jb][4 * q4] * os, o[nt][jb][4 * q4 + 1] * os,
+                                               o[nt][jb][4 * q4 + 2] * os, o[nt][jb][4 * q4 + 3] * os);
+                        *(float4*)(po + 32 * jb + 8 * q4 + 4 * hv) = w;
+                    }
+                if (hv == 0) {
+                    a.part_ml[prow * 2] = m_run[nt];
+                    a.part_ml[prow * 2 + 1] = l_tot;
+                }
             }
         }
-    }
-
-    // ---- fused cache update for the tile's new tokens (see the narrow kernel)
-    if ((u.flags & 1) && !RPA_ABLATED(a, 512)) {
-        const int c = threadIdx.x % NC;
-        for (int t = threadIdx.x / NC; t < u.n_q; t += (64 * WAVES) / NC) {
-            const int pos = ctx + u.q_pos0 + t;
-            const int page = clamp_page(pt_row[pos >> ps_log2], num_pages);
-            const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * ROWB + c * 16; // bytes
-            const size_t dst = ((((size_t)page << ps_log2) + (pos & ps_mask)) * Hkv + g) * ROWB + c * 16;
-            const uint4 kk = *(const uint4*)(k_new + src);
-            const uint4 vv = *(const uint4*)(v_new + src);
-            store16_streaming((char*)a.k_pages + dst, kk);
-            store16_streaming((char*)a.v_pages + dst, vv);
+    };
+    // Second half: the staged rows go to global memory, whole rows, 16 bytes per lane.
+    auto store_rows = [&](const Fin& f) __attribute__((always_inline)) {
+        if (f.part_row < 0 && !RPA_ABLATED(a, 256)) {
+            constexpr int RPI = 64 / ONC; // rows per wave-wide 16-byte store
+            int lv = lane;
+            if constexpr (PERSIST) asm volatile("" : "+v"(lv));
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const char* stage = (const char*)smem + (PERSIST ? NST * STAGEB : 0) + (size_t)(NT * wave + nt) * 32 * SROW;
+#pragma unroll
+                for (int i = 0; i < 32 / RPI; ++i) {
+                    const int r = i * RPI + lv / ONC;
+                    const int rho = 32 * (NT * wave + nt) + r;
+                    const int t_r = rho & tq_mask, h_r = rho >> tq_log2;
+                    const int pos = PERSIST ? ((lv % ONC) ^ (r & (ONC - 1))) : (lv % ONC);
+                    const uint4 w = *(const uint4*)(stage + r * SROW + pos * 16);
+                    if (t_r < f.n_q)
+                        store16_streaming(a.out + ((size_t)(f.q_start + t_r) * Hq + f.g * hg + h_r) * D + (lv % ONC) * 8, w);
+                }
+            }
         }
+    };
+    // ---- fused cache update for the tile's new tokens (see the narrow kernel)
+    auto cache_write = [&](const Fin& f) __attribute__((always_inline)) {
+        if ((f.flags & 1) && !RPA_ABLATED(a, 512)) {
+            const int c = threadIdx.x % NC;
+            for (int t = threadIdx.x / NC; t < f.n_q; t += (64 * WAVES) / NC) {
+                const int pos = f.ctx + f.q_pos0 + t;
+                const int page = clamp_page(f.pt_row[pos >> ps_log2], num_pages);
+                const size_t src = ((size_t)(f.q_start + t) * Hkv + f.g) * ROWB + c * 16; // bytes
+                const size_t dst = ((((size_t)page << ps_log2) + (pos & ps_mask)) * Hkv + f.g) * ROWB + c * 16;
+                const uint4 kk = *(const uint4*)(k_new + src);
+                const uint4 vv = *(const uint4*)(v_new + src);
+                store16_streaming((char*)a.k_pages + dst, kk);
+                store16_streaming((char*)a.v_pages + dst, vv);
+            }
+        }
+    };
+
+    // The same in two halves for the switch between two items of a persistent
+    // workgroup: the rows are read before the next item's first tiles are requested
+    // and stored after the wait for those tiles, so that no wait for a cache row has
+    // to sit between them.  Two rows per thread at most (tiles of up to 64 tokens).
+    constexpr int CWI = 2;
+    constexpr int CW_STRIDE = (64 * WAVES) / NC;
+    auto cache_rows_load = [&](const Fin& f, uint4 (&kk)[CWI], uint4 (&vv)[CWI], size_t (&dst)[CWI]) __attribute__((always_inline)) {
+        const int c = threadIdx.x % NC;
+#pragma unroll
+        for (int i = 0; i < CWI; ++i) {
+            const int t = threadIdx.x / NC + i * CW_STRIDE;
+            kk[i] = vv[i] = make_uint4(0, 0, 0, 0);
+            dst[i] = 0;
+            if ((f.flags & 1) && t < f.n_q && !RPA_ABLATED(a, 512)) {
+                const int pos = f.ctx + f.q_pos0 + t;
+                const int page = clamp_page(f.pt_row[pos >> ps_log2], num_pages);
+                const size_t src = ((size_t)(f.q_start + t) * Hkv + f.g) * ROWB + c * 16;
+                dst[i] = ((((size_t)page << ps_log2) + (pos & ps_mask)) * Hkv + f.g) * ROWB + c * 16;
+                kk[i] = *(const uint4*)(k_new + src);
+                vv[i] = *(const uint4*)(v_new + src);
+            }
+        }
+    };
+    auto cache_rows_store = [&](const Fin& f, const uint4 (&kk)[CWI], const uint4 (&vv)[CWI], const size_t (&dst)[CWI]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < CWI; ++i) {
+            const int t = threadIdx.x / NC + i * CW_STRIDE;
+            if ((f.flags & 1) && t < f.n_q && !RPA_ABLATED(a, 512)) {
+                store16_streaming((char*)a.k_pages + dst[i], kk[i]);
+                store16_streaming((char*)a.v_pages + dst[i], vv[i]);
+            }
+        }
+    };
+
+    for (;;) {
+        if constexpr (D <= 128) {
+            // Unrolled over the ring so that a tile's stage is a compile-time constant:
+            // the stage base then sits in the offset field of every LDS read instead of
+            // costing a vector add per operand (-1.7 %; at D = 256 the doubled loop body
+            // costs more than that saves).
+            static_assert(NST == 2 || NST == 3, "ring depths the loop is unrolled for");
+            for (int t = 0; t < ntiles; t += NST) { // ntiles is the same for every wave: barriers stay matched
+                tile_step(t, std::integral_constant<int, 0>{});
+                if (t + 1 < ntiles) tile_step(t + 1, std::integral_constant<int, 1>{});
+                if constexpr (NST == 3) {
+                    if (t + 2 < ntiles) tile_step(t + 2, std::integral_constant<int, 2>{});
+                }
+            }
+        } else {
+            for (int t = 0; t < ntiles; ++t) tile_step(t, t % NST);
+        }
+
+        Fin f;
+        f.q_start = u.q_start, f.n_q = u.n_q, f.part_row = u.part_row, f.g = g, f.flags = u.flags, f.q_pos0 = u.q_pos0;
+        f.ctx = ctx, f.pt_row = pt_row;
+        finalize_stage(); // the accumulators and the running sums are free from here on
+        if (!PERSIST || item_n < 0) {
+            store_rows(f);
+            cache_write(f);
+            break;
+        }
+        // ---- on to the next item ---------------------------------------------------
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            m_run[nt] = -INFINITY;
+            l_run[nt] = 0.f;
+#pragma unroll
+            for (int j = 0; j < DPL; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[nt][j][v] = 0.f;
+        }
+        // Its Q parts sit in the slots of the virtual tiles ntiles .. ntiles+NST-2; the
+        // last of them may still be in flight.
+        const int q_slot0 = ntiles % NST;
+        wait_vmcnt<0>();
+        __syncthreads();
+        u = un;
+        g = gn;
+        ++round;
+        setup_item();
+        read_q(q_slot0);
+        __syncthreads(); // every wave holds its operands (and is done with the last tile) before the slots are reused
+        fetch_next_item();
+        // The new item's first tiles are requested BEFORE the old item's rows are
+        // stored: loads and stores of a wave complete in the order they were issued, so
+        // the wait below, which leaves the youngest stores outstanding, covers these
+        // loads without waiting for the stores to drain.
+        const bool split_cw = (CWI * CW_STRIDE) >= (1 << tq_log2); // every token of a tile within CWI rows per thread
+        uint4 cw_k[CWI], cw_v[CWI];
+        size_t cw_dst[CWI];
+        if (split_cw) cache_rows_load(f, cw_k, cw_v, cw_dst);
+#pragma unroll
+        for (int s0 = 0; s0 < NST - 1; ++s0) issue_virtual(s0, false);
+        store_rows(f);
+        // A full tile that writes its rows issues exactly 32 / (rows per store) row
+        // stores per wave after the loads above (each has active lanes); any other
+        // case waits for everything.
+        if (f.part_row < 0 && f.n_q == (1 << tq_log2) && !RPA_ABLATED(a, 256)) wait_vmcnt<32 / (64 / ONC)>();
+        else wait_vmcnt<0>();
+        __syncthreads();
+        if (split_cw) cache_rows_store(f, cw_k, cw_v, cw_dst);
+        else cache_write(f);
     }
 }
 
@@ -1121,6 +1356,12 @@ static size_t wide_lds_bytes(int stages) {
     return (size_t)stages * 2 * kWideKvTile * D * 2;
 }
 
+// persistent 8-wave shape: the ring plus a staging region for the output rows
+template <int D>
+static size_t wide_lds_bytes_persistent() {
+    return wide_lds_bytes<D>(kWideStages) + (size_t)8 * 32 * D * 2;
+}
+
 // 8-bit K/V rows: the ring is half the size and the output staging of the
 // epilogue (32 padded bf16 rows per wave) is what sizes the allocation.
 static size_t wide_lds_bytes_kv8(int stages, int waves) {
@@ -1149,6 +1390,12 @@ int kernels_init(int device, std::string& err) {
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 8, kWideStages, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<128>(kWideStages));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<128, 8, kWideStages, false, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes_persistent<128>());
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 8, kWideStages, false, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes_persistent<64>());
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void*)rpa_wide_kernel<64, 8, kWideStages, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<64>(kWideStages));
@@ -1227,8 +1474,10 @@ int launch_copy(void* dst, const void* src, size_t n16, int num_cus, void* strea
     return (int)hipGetLastError();
 }
 
-int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev) {
+int launch_wide(const KernelArgs& a_in, int num_units, void* stream, void** ev) {
     if (num_units <= 0) return 0;
+    KernelArgs a = a_in;
+    a.num_wide_items = num_units * a.num_kv_heads;
     dim3 grid((unsigned)num_units * a.num_kv_heads);
     hipStream_t st = (hipStream_t)stream;
     // One 32-row group per wave: with two, an operand read would feed two MFMAs,
@@ -1249,6 +1498,15 @@ int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev) {
         if (!half) return (int)hipErrorInvalidValue;
         RPA_LAUNCH((rpa_wide_kernel<256, 4, kWideStagesHalf, false>), grid, dim3(256), wide_lds_bytes<256>(kWideStagesHalf),
                    st, ev, a);
+    } else if (!half && a.wide_persist_grid > 0) {
+        // persistent: one workgroup per CU walks the (unit, KV head) items
+        dim3 pgrid((unsigned)std::min<int64_t>((int64_t)a.num_wide_items, (int64_t)a.wide_persist_grid));
+        if (a.head_dim == 128)
+            RPA_LAUNCH((rpa_wide_kernel<128, 8, kWideStages, false, true>), pgrid, dim3(512),
+                       wide_lds_bytes_persistent<128>(), st, ev, a);
+        else
+            RPA_LAUNCH((rpa_wide_kernel<64, 8, kWideStages, false, true>), pgrid, dim3(512),
+                       wide_lds_bytes_persistent<64>(), st, ev, a);
     } else if (a.head_dim == 128) {
         if (half)
             RPA_LAUNCH((rpa_wide_kernel<128, 4, kWideStagesHalf, false>), grid, dim3(256),

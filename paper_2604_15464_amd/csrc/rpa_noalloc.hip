@@ -184,6 +184,7 @@ extern "C" int rpa_update_and_attend_noalloc(const rpa_shape* shape, int device,
     a.causal = shape->non_causal ? 0 : 1;
     a.kv_fp8 = 0;
     a.out_scale = 1.f;
+    a.wide_persist_grid = s->num_cus;
     a.units = (const rpa_work_unit*)base;
     a.bins = (const int32_t*)(base + bins_off);
     int hrc = launch_narrow(a, (int)n_bins, plan.stats.narrow_waves, stream, nullptr);

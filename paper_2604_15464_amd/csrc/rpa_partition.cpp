@@ -131,7 +131,8 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         (opt.narrow_waves > 0 && s.num_kv_heads % opt.narrow_waves != 0) ||
         (opt.wide_rows != 0 && opt.wide_rows != 128 && opt.wide_rows != 256) || opt.wide_order < 0 ||
         opt.wide_order > 2 || opt.mixed_overlap < 0 || opt.mixed_overlap > 2 || opt.stream_ordered_upload < 0 ||
-        opt.stream_ordered_upload > 1 || !options_fit_shape(s, opt)) {
+        opt.stream_ordered_upload > 1 || opt.wide_persistent < 0 || opt.wide_persistent > 1 ||
+        !options_fit_shape(s, opt)) {
         err = "bad options";
         return RPA_ERR_INVALID_ARG;
     }

@@ -51,7 +51,7 @@ class Options(C.Structure):
     _fields_ = [("variant", C.c_int32), ("kv_chunk", C.c_int32), ("wide_kv_chunk", C.c_int32),
                 ("narrow_waves", C.c_int32), ("units_per_cu", C.c_int32), ("ablate", C.c_int32),
                 ("wide_rows", C.c_int32), ("wide_order", C.c_int32), ("mixed_overlap", C.c_int32),
-                ("stream_ordered_upload", C.c_int32)]
+                ("stream_ordered_upload", C.c_int32), ("wide_persistent", C.c_int32)]
 
 
 class RpaError(RuntimeError):
@@ -152,7 +152,7 @@ def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUT
     units = (WorkUnit * max_units)()
     items = (CombineItem * max_units)()
     stats = PlanStats()
-    opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, 0, 0, wide_rows, 0, mixed_overlap, 0)
+    opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, 0, 0, wide_rows, 0, mixed_overlap, 0, 0)
     rc = l.rpa_plan_host(C.byref(shape), cu_p, kv_p, n, C.byref(opt), num_cus, units, max_units, items,
                          max_units, C.byref(stats))
     if rc != RPA_OK:
@@ -213,9 +213,9 @@ class RaggedPagedAttention:
             pass
 
     def set_options(self, variant=VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, narrow_waves=0, units_per_cu=0,
-                    ablate=0, wide_rows=0, wide_order=0, mixed_overlap=0, stream_ordered_upload=0):
+                    ablate=0, wide_rows=0, wide_order=0, mixed_overlap=0, stream_ordered_upload=0, wide_persistent=0):
         opt = Options(variant, kv_chunk, wide_kv_chunk, narrow_waves, units_per_cu, ablate, wide_rows, wide_order,
-                      mixed_overlap, stream_ordered_upload)
+                      mixed_overlap, stream_ordered_upload, wide_persistent)
         rc = self._lib.rpa_set_options(self._ctx, C.byref(opt))
         if rc != RPA_OK:
             raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())

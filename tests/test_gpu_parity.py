@@ -34,7 +34,7 @@ def plan_cuts(wl, causal=True, kv_scales=None, **knobs):
 
 def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=True, pad_tokens=0,
              pad_seqs=0, seqs=None, calls=1, narrow_waves=0, units_per_cu=0, wide_rows=0, causal=True,
-             mixed_overlap=0, kv_scales=None, needles=None):
+             mixed_overlap=0, kv_scales=None, needles=None, wide_persistent=0):
     """Run the HIP path and the oracle on the workload; returns a dict of results.
     needles = (mode, seed): the discriminating inputs of workloads.materialize_needles
     (every output row is the V row of one chosen position) instead of N(0,1) q and K."""
@@ -58,7 +58,8 @@ def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=T
     ctx = rpa.RaggedPagedAttention.for_workload(wl, max_tokens=max(1, max_tokens), max_seqs=max(1, max_seqs),
                                                 causal=causal, kv_scales=kv_scales)
     ctx.set_options(variant=variant, kv_chunk=kv_chunk, wide_kv_chunk=wide_kv_chunk, narrow_waves=narrow_waves,
-                    units_per_cu=units_per_cu, wide_rows=wide_rows, mixed_overlap=mixed_overlap)
+                    units_per_cu=units_per_cu, wide_rows=wide_rows, mixed_overlap=mixed_overlap,
+                    wide_persistent=wide_persistent)
     out = torch.full_like(x["q"], float("nan"))
     sentinel = out.clone()
     for _ in range(calls):
@@ -245,9 +246,25 @@ def test_wide_tile_rows(wide_rows, shape):
     prefill-heavy ragged batches, forced through the wide kernel, with splits."""
     hq, hkv, d = shape
     wl = W.ragged(77 + hq, num_seqs=6, hq=hq, hkv=hkv, d=d, ps=16, max_q=300, max_ctx=500, p_decode=0.1)
-    res = run_case(wl, variant=rpa.VARIANT_PREFILL, wide_rows=wide_rows, wide_kv_chunk=192)
-    check(wl, res)
-    assert res["info"]["wide_rows"] == wide_rows
+    # 256 rows: once with persistent workgroups that walk the (tile, head) items, once with a workgroup per item
+    for persistent in ((0, 1) if wide_rows == 256 else (0,)):
+        res = run_case(wl, variant=rpa.VARIANT_PREFILL, wide_rows=wide_rows, wide_kv_chunk=192, wide_persistent=persistent)
+        check(wl, res)
+        assert res["info"]["wide_rows"] == wide_rows
+
+
+@pytest.mark.parametrize("persistent", [0, 1])
+@pytest.mark.parametrize("needles", [None, ("spread", 4), ("boundaries", 5)])
+def test_persistent_wide_workgroups_walk_many_items(persistent, needles):
+    """More (tile, KV head) items than compute units, of very different lengths, partial
+    tiles and KV splits among them: every persistent workgroup finishes several items
+    and switches between full tiles, partial tiles and split partials."""
+    wl = W.ragged(8800, num_seqs=14, hq=32, hkv=8, d=128, ps=16, max_q=900, max_ctx=1200, p_decode=0.0, p_empty=0.0)
+    for chunk in (0, 320):
+        res = run_case(wl, variant=rpa.VARIANT_PREFILL, wide_rows=256, wide_kv_chunk=chunk, wide_persistent=persistent,
+                       needles=needles, calls=2)
+        check(wl, res)
+        assert res["info"]["num_wide_units"] * 8 > 256
 
 
 def test_rejected_arguments_leave_everything_untouched():
