@@ -57,20 +57,29 @@ def kernels(src: str, out: str, command: str) -> None:
     rows = [r for r in cur.execute("select name,start,end,grid_x,grid_y,workgroup_x,lds_size,vgpr_count,"
                                    "accum_vgpr_count,scratch_size from kernels order by start")
             if any(k in r[0] for k in KERNELS)]
-    # per-kernel average over the second half of its launches (steady state, after warm-up)
+    # bench.py runs its blocks one after the other, with input generation and a context
+    # set-up in between: launches of one kernel that lie less than 5 ms apart form one
+    # burst, i.e. belong to one block of the bench line.  Per kernel and burst (in the order
+    # bench.py runs its blocks): the average over the second half of the launches (steady
+    # state, after warm-up), the launch shape, and the first launches in order (how long
+    # the kernel takes while the clocks settle).
     by = collections.defaultdict(list)
     for r in rows:
-        by[short_name(r[0])].append(r)
-    lines += ["", "this library's kernels: average over the last half of the launches of each, and launch shape"]
-    for name, rs in by.items():
-        tail = rs[len(rs) // 2:]
-        avg = sum(r[2] - r[1] for r in tail) / len(tail) / 1e3
-        r = rs[-1]
-        lines.append(f"  {name:32s} n={len(rs):4d} steady_avg_us={avg:9.2f} grid_threads=({r[3]},{r[4]}) wg={r[5]} "
-                     f"lds={r[6]} vgpr={r[7]} agpr={r[8]} scratch={r[9]}")
-        if len(rs) >= 8:
-            # the first launches in order: how long the kernel takes while the clocks settle
-            lines.append("    first launches (us): " + " ".join(f"{(q[2] - q[1]) / 1e3:.1f}" for q in rs[:25]))
+        name = short_name(r[0])
+        if not by[name] or r[1] - by[name][-1][-1][2] > 5e6:
+            by[name].append([])
+        by[name][-1].append(r)
+    lines += ["", "this library's kernels, per burst of launches (= per block of the bench line that launches the kernel, "
+              "in the order bench.py runs its blocks): steady average (last half of the burst) and launch shape"]
+    for name, groups in by.items():
+        for gi, rs in enumerate(groups):
+            tail = rs[len(rs) // 2:]
+            avg = sum(r[2] - r[1] for r in tail) / len(tail) / 1e3
+            r = rs[-1]
+            lines.append(f"  {name:40s} burst {gi + 1} n={len(rs):4d} steady_avg_us={avg:9.2f} grid_threads=({r[3]},{r[4]}) "
+                         f"wg={r[5]} lds={r[6]} vgpr={r[7]} agpr={r[8]} scratch={r[9]}")
+            if len(rs) >= 8:
+                lines.append("    first launches (us): " + " ".join(f"{(q[2] - q[1]) / 1e3:.1f}" for q in rs[:25]))
     text = "\n".join(lines) + "\n"
     with open(out, "w") as f:
         f.write(text)
