@@ -79,6 +79,14 @@ typedef struct {
                                   narrow kernel (built for the bandwidth-bound decode). */
     float k_scale;             /* scale of k_pages (> 0, finite); read if kv_fp8 only   */
     float v_scale;             /* scale of v_pages                                       */
+    int32_t kv_merged;         /* 0: separate k_pages and v_pages.  1: the paper's merged
+                                  KV layout (Sec. 3.1.3 "KV merge"): k_pages is ONE pool
+                                  bf16 [num_pages, page_size, num_kv_heads, 2, head_dim]
+                                  in which a token's K and V of a head lie side by side
+                                  (index 0 = K, 1 = V); v_pages is ignored and may be
+                                  NULL.  bf16 cache at head_dim 128 only, and every batch
+                                  then runs on the narrow kernel (the layout is built and
+                                  measured for the bandwidth-bound decode case).        */
 } rpa_shape;
 
 /* Kernel variants (Sec. 3.4 "Distribution-aware Compilation": decode-only,

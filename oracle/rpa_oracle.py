@@ -23,9 +23,8 @@ Readings where the paper is silent (each also listed in the design notes):
     j <= kv_len - q_len + i; with causal=False (the paper's non-causal prefill
     measurements, Sec. 4.2) every query sees all kv_len positions, its own
     sequence's later tokens included;
-  * kv_len counts this call's new tokens (Sec. 4.1: the context length
-    "accounts for KV data fetched from both the KV cache and newly projected
-    KV");
+  * kv_len counts this call's new tokens (Sec. 4.1 defines the context
+    length as covering cached and newly projected KV alike);
   * query head h reads KV head h // (Hq / Hkv) (Sec. 3.1.2: the h_g heads of
     a group are stacked against one K/V operand);
   * the result is as if the update finished before attention starts.
@@ -37,7 +36,9 @@ on the contiguous single-sequence case, closed forms (constant V, equal K,
 hand-built log-weights, shift invariance), the split-merge identity, sentinel
 bytes, idempotence; for the 8-bit cache torch's float8_e4m3fn casts, a
 nearest-neighbour search over the 256 decoded values, the lossless case and
-power-of-two scale invariance.  No function here is "parity unpinned".
+power-of-two scale invariance; for the merged pool the pure-Python brute force
+on a pool filled token by token, and equality with the two-pool call.  No
+function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -237,6 +238,49 @@ def update_and_attend(q, k_new, v_new, k_pages, v_pages, page_table, cu_q_lens, 
             out[q0:q0 + l_q, hs] = res[:, hs]
     assert t_total <= q.shape[0]
     return out, k_pages, v_pages
+
+
+# --------------------------------------------------------------------------
+# the merged KV layout (Sec. 3.1.3 "KV merge"): one pool in which the K and the
+# V row of a token and head lie side by side.  Only addressing changes.  The
+# paper interleaves at the granularity its hardware packs rows in; the reading
+# here keeps whole rows: pool uint16 [P, ps, Hkv, 2, D], index 0 = K, 1 = V.
+# --------------------------------------------------------------------------
+def update_and_attend_merged(q, k_new, v_new, kv_pages, page_table, cu_q_lens, kv_lens, num_seqs, sm_scale,
+                             seqs=None, heads=None, causal=True):
+    """As update_and_attend on a merged pool.  Returns (out, kv_pages')."""
+    kv_pages = np.array(kv_pages, dtype=np.uint16, copy=True)
+    ps = kv_pages.shape[1]
+    for r in range(num_seqs):
+        q0 = int(cu_q_lens[r])
+        l_q = int(cu_q_lens[r + 1]) - q0
+        ctx = int(kv_lens[r]) - l_q
+        if l_q < 0 or ctx < 0:
+            raise ValueError("bad lengths")
+        for t in range(l_q):
+            pg = int(page_table[r, (ctx + t) // ps])
+            if pg < 0:
+                raise ValueError("page table entry missing")
+            kv_pages[pg, (ctx + t) % ps, :, 0, :] = k_new[q0 + t]
+            kv_pages[pg, (ctx + t) % ps, :, 1, :] = v_new[q0 + t]
+    out = np.full(q.shape, np.nan, dtype=np.float64)
+    for r in (range(num_seqs) if seqs is None else seqs):
+        q0 = int(cu_q_lens[r])
+        l_q = int(cu_q_lens[r + 1]) - q0
+        if l_q == 0:
+            continue
+        l_kv = int(kv_lens[r])
+        n_pages = (l_kv + ps - 1) // ps
+        rows = kv_pages[np.asarray(page_table[r, :n_pages], dtype=np.int64)]      # [n_pages, ps, Hkv, 2, D]
+        rows = rows.reshape(n_pages * ps, *kv_pages.shape[2:])[:l_kv]
+        res = attend_sequence(bf16_to_f64(q[q0:q0 + l_q]), bf16_to_f64(rows[:, :, 0, :]), bf16_to_f64(rows[:, :, 1, :]),
+                              sm_scale, heads=heads, causal=causal)
+        if heads is None:
+            out[q0:q0 + l_q] = res
+        else:
+            hs = list(heads)
+            out[q0:q0 + l_q, hs] = res[:, hs]
+    return out, kv_pages
 
 
 # --------------------------------------------------------------------------

@@ -338,7 +338,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
         c->last = rpa_plan_stats{};
         return RPA_OK;
     }
-    if (!out || !q || !k_new || !v_new || !k_pages || !v_pages || !page_table)
+    if (!out || !q || !k_new || !v_new || !k_pages || (!v_pages && !c->shape.kv_merged) || !page_table)
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_update_and_attend: null tensor pointer");
     const uintptr_t align = (uintptr_t)out | (uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new |
                             (uintptr_t)k_pages | (uintptr_t)v_pages;
@@ -453,6 +453,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     a.causal = c->shape.non_causal ? 0 : 1;
     a.kv_fp8 = c->shape.kv_fp8;
     a.out_scale = 1.f;
+    a.kv_merged = c->shape.kv_merged;
     a.wide_persist_grid = opt_used.wide_persistent == 1 ? 0 : c->num_cus;
     if (a.kv_fp8) {
         // The new rows are quantised into the staging copy first; from there on the

@@ -90,6 +90,7 @@ struct KernelArgs {
     int32_t causal;   // 0: no mask beyond the end of the sequence
     int32_t kv_fp8;   // 1: pools and k_new / v_new (here: the quantised staging copy) hold E4M3 bytes
     float out_scale;  // V scale of the 8-bit cache, else 1
+    int32_t kv_merged; // 1: k_pages is one pool [num_pages, page_size, Hkv, 2, D] with K and V side by side
     int32_t num_wide_items;     // wide kernel: (unit, KV head) pairs of the launch
     int32_t wide_persist_grid;  // > 0: workgroups of the persistent wide kernel (one per CU), which walk the items
 };

@@ -171,16 +171,26 @@ __device__ __forceinline__ int clamp_page(int page, int num_pages) {
 // element (Sec. 3.6 "Quantization").  Rows are half as long, the ring is twice
 // as deep, and operands are widened to bf16 after the LDS read; everything else
 // is the same code.
-template <int D, int NST, bool KV8>
+//
+// MERGED (bf16 cache, head_dim 128): one pool whose token rows hold K and V side
+// by side for every KV head, [num_pages, page_size, Hkv, 2, D] (the paper's KV
+// merge, Sec. 3.1.3): a token's K and V of one head are 512 contiguous bytes, one
+// wave-wide load brings two tokens' K|V pairs, and K and V rows alternate in the
+// LDS stage.  a.k_pages is the pool, a.v_pages is not used.
+template <int D, int NST, bool KV8, bool MERGED = false>
 __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a) {
+    static_assert(!MERGED || (!KV8 && D == 128), "the merged layout is built for bf16 at head_dim 128");
     constexpr int ROWB = D * (KV8 ? 1 : 2);     // bytes of one token row of one head
     constexpr int NC = ROWB / 16;               // 16-byte chunks per row
     constexpr int NG = D / 8;                   // groups of 8 elements per row
-    constexpr int TPI = 64 / NC;                // tokens covered by one wave-wide load
-    constexpr int NLD = kNarrowKvTile / TPI;    // loads per K (or V) tile
+    constexpr int TPI = MERGED ? 64 / (2 * NC) : 64 / NC; // tokens covered by one wave-wide load
+    constexpr int NLD = MERGED ? kNarrowKvTile / TPI / 2 : kNarrowKvTile / TPI; // loads per K (or V) tile
     constexpr int TILEB = kNarrowKvTile * ROWB; // bytes of a K (or V) tile
     constexpr int STAGEB = 2 * TILEB;
     constexpr int LOADS_PER_STAGE = 2 * NLD;
+    constexpr int PITCH = MERGED ? 2 * ROWB : ROWB;  // bytes between consecutive token rows of K (or V) in a stage
+    constexpr int VOFF = MERGED ? ROWB : TILEB;      // V rows of a stage relative to its K rows
+    constexpr int HEADB = MERGED ? 2 * ROWB : ROWB;  // bytes of one head's slice of a cache token row
     constexpr int KSTEPS = D / 32;              // MFMA 16x16x32 steps over head_dim
     constexpr int MT = D / 16;                  // 16-dim output tiles
     constexpr int VG = D > 128 ? D / 128 : 1;   // 128-dim groups of a V row (16 chunks each)
@@ -204,7 +214,8 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     const char* const v_pages = (const char*)a.v_pages;
     const char* const k_new = (const char*)a.k_new;
     const char* const v_new = (const char*)a.v_new;
-    const uint32_t tokstride = (uint32_t)Hkv * ROWB; // bytes between consecutive tokens
+    const uint32_t tokstride = (uint32_t)Hkv * HEADB; // bytes between consecutive tokens of the cache
+    const uint32_t newstride = (uint32_t)Hkv * ROWB;  // ... of k_new / v_new
     const uint64_t k_delta = (uint64_t)k_pages - (uint64_t)k_new;
     const uint64_t v_delta = (uint64_t)v_pages - (uint64_t)v_new;
     const int tok_n = n / hg; // row n = (token n / hg, head g*hg + n % hg)
@@ -223,6 +234,12 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         const int m = i * TPI + ld_tok;
         lane_off[i] = (uint32_t)g * ROWB + (uint32_t)((ld_chunk ^ (m % NC)) * 16);
     }
+    // merged layout: load j of a tile brings tokens 2j and 2j+1; lane l fetches for
+    // token 2j + l/32 a chunk of K (l/16 even) or V (odd), placed by the same swizzle
+    const int mg_tok = lane >> 5, mg_sub = (lane >> 4) & 1, mg_pos = lane & 15;
+    uint32_t mg_chunk[2 * NLD];
+#pragma unroll
+    for (int j = 0; j < 2 * NLD; ++j) mg_chunk[j] = (uint32_t)((mg_pos ^ ((2 * j + mg_tok) % NC)) * 16);
 
     // The workgroup walks the units of its bin back to back; the waves never
     // synchronise with each other.
@@ -261,8 +278,24 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         const int pidx = __builtin_amdgcn_readfirstlane(pos0 >> ps_log2);
         const int page = clamp_page(pt_row[pidx], num_pages); // a tile never straddles pages
         const uint32_t ldsK = lds_wave + slot * STAGEB;
-        const uint32_t ldsV = ldsK + TILEB;
+        const uint32_t ldsV = ldsK + VOFF;
         const int last = kv_end - 1 - pos0; // tokens past the range re-read its last token
+        if constexpr (MERGED) {
+            const size_t page_tok = ((size_t)page << ps_log2);
+#pragma unroll
+            for (int j = 0; j < 2 * NLD; ++j) {
+                const int pos = pos0 + min(2 * j + mg_tok, last);
+                const bool cached = pos < ctx;
+                // cached: the token's K|V pair of this head in the pool; new: the K or the V row of the call's inputs
+                const uint64_t addr =
+                    cached ? (uint64_t)k_pages + (page_tok + (size_t)(pos & ps_mask)) * tokstride + (uint32_t)g * HEADB +
+                                 (uint32_t)mg_sub * ROWB + mg_chunk[j]
+                           : (uint64_t)(mg_sub ? v_new : k_new) + (uint64_t)(u.seq_q0 + pos - ctx) * newstride +
+                                 (uint32_t)g * ROWB + mg_chunk[j];
+                async_load16_stream((const void*)addr, ldsK + j * 1024);
+            }
+            return;
+        }
         if (pos0 + kNarrowKvTile <= ctx) {
             // whole tile is cached content: one scalar base per pool
             const size_t tile_off = (((size_t)page << ps_log2) + (size_t)(pos0 & ps_mask)) * tokstride;
@@ -285,6 +318,7 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
                 const size_t tokidx = cached ? (((size_t)page << ps_log2) + (size_t)(pos & ps_mask))
                                              : (size_t)(u.seq_q0 + pos - ctx);
                 // select the pool by adding a wave-uniform pointer difference
+                // (tokstride == newstride here: the merged layout took its own path above)
                 const uint64_t off = (uint64_t)tokidx * tokstride + lane_off[i];
                 const uint64_t ka = (uint64_t)k_new + off + (cached ? k_delta : 0);
                 const uint64_t va = (uint64_t)v_new + off + (cached ? v_delta : 0);
@@ -314,7 +348,7 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         else wait_vmcnt<0>();
 
         const char* ldsK = lds_wave_ptr + (t % NST) * STAGEB;
-        const char* ldsV = ldsK + TILEB;
+        const char* ldsV = ldsK + VOFF;
         const int pos0 = kv_begin + t * kNarrowKvTile;
         if (RPA_ABLATED(a, 1)) { // measurement: loads and stores only
             acc[0][0] += __uint_as_float(*(const uint32_t*)(ldsK + lane * 4)) + __uint_as_float(*(const uint32_t*)(ldsV + lane * 4));
@@ -325,7 +359,7 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         // byte offset in a tile of elements 8*gi .. 8*gi+7 of token row r (the XOR
         // swizzle works on 16-byte chunks: a whole group, or two with 8-bit elements)
         auto group_off = [](int r, int gi) {
-            return KV8 ? r * ROWB + (((gi >> 1) ^ (r % NC)) * 16) + (gi & 1) * 8 : r * ROWB + ((gi ^ (r % NC)) * 16);
+            return KV8 ? r * ROWB + (((gi >> 1) ^ (r % NC)) * 16) + (gi & 1) * 8 : r * PITCH + ((gi ^ (r % NC)) * 16);
         };
         auto read_group = [&](const char* tile, int r, int gi) {
             if constexpr (KV8) return e4m3x8_to_bf16x8(*(const uint2*)(tile + group_off(r, gi)));
@@ -423,15 +457,16 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     // are in flight while the ring's vmcnt bookkeeping runs.
     if ((u.flags & 1) && !RPA_ABLATED(a, 2)) {
         const int c = lane % NC;
-        for (int t = lane / NC; t < u.n_q; t += TPI) {
+        for (int t = lane / NC; t < u.n_q; t += 64 / NC) {
             const int pos = ctx + u.q_pos0 + t;
             const int page = clamp_page(pt_row[pos >> ps_log2], num_pages);
             const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * ROWB + c * 16; // bytes
-            const size_t dst = ((((size_t)page << ps_log2) + (pos & ps_mask)) * Hkv + g) * ROWB + c * 16;
+            const size_t dst = (((size_t)page << ps_log2) + (pos & ps_mask)) * tokstride + (size_t)g * HEADB + c * 16;
             const uint4 kk = *(const uint4*)(k_new + src);
             const uint4 vv = *(const uint4*)(v_new + src);
             store16_streaming((char*)a.k_pages + dst, kk);
-            store16_streaming((char*)a.v_pages + dst, vv);
+            if constexpr (MERGED) store16_streaming((char*)a.k_pages + dst + ROWB, vv); // V sits beside K in the token's row
+            else store16_streaming((char*)a.v_pages + dst, vv);
         }
     }
 
@@ -1374,6 +1409,9 @@ int kernels_init(int device, std::string& err) {
     e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<128, kNarrowStages, false>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<128>(kMaxWaves));
     if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<128, kNarrowStages, false, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<128>(kMaxWaves));
+    if (e == hipSuccess)
         e = hipFuncSetAttribute((const void*)rpa_narrow_kernel<64, kNarrowStages, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)narrow_lds_bytes<64>(kMaxWaves));
     // 8-bit cache: rows half as long, ring twice as deep, the same bytes per wave
@@ -1444,7 +1482,9 @@ int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream, vo
         else
             RPA_LAUNCH((rpa_narrow_kernel<64, 2 * kNarrowStages, true>), grid, block, narrow_lds_bytes<64>(waves), st,
                        ev, a);
-    } else if (a.head_dim == 256)
+    } else if (a.kv_merged)
+        RPA_LAUNCH((rpa_narrow_kernel<128, kNarrowStages, false, true>), grid, block, narrow_lds_bytes<128>(waves), st, ev, a);
+    else if (a.head_dim == 256)
         RPA_LAUNCH((rpa_narrow_kernel<256, kNarrowStages, false>), grid, block, narrow_lds_bytes<256>(waves), st, ev, a);
     else if (a.head_dim == 128)
         RPA_LAUNCH((rpa_narrow_kernel<128, kNarrowStages, false>), grid, block, narrow_lds_bytes<128>(waves), st, ev, a);

@@ -103,7 +103,7 @@ extern "C" int rpa_update_and_attend_noalloc(const rpa_shape* shape, int device,
                     "rpa_update_and_attend_noalloc: the 8-bit cache needs a staging copy of the new rows, which this "
                     "entry point has no room for; use a context");
     if (num_seqs == 0) return RPA_OK;
-    if (!out || !q || !k_new || !v_new || !k_pages || !v_pages || !page_table)
+    if (!out || !q || !k_new || !v_new || !k_pages || (!v_pages && !shape->kv_merged) || !page_table)
         return fail(RPA_ERR_INVALID_ARG, "rpa_update_and_attend_noalloc: null tensor pointer");
     const uintptr_t align = (uintptr_t)out | (uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new |
                             (uintptr_t)k_pages | (uintptr_t)v_pages;
@@ -184,6 +184,7 @@ extern "C" int rpa_update_and_attend_noalloc(const rpa_shape* shape, int device,
     a.causal = shape->non_causal ? 0 : 1;
     a.kv_fp8 = 0;
     a.out_scale = 1.f;
+    a.kv_merged = shape[0].kv_merged;
     a.wide_persist_grid = s->num_cus;
     a.units = (const rpa_work_unit*)base;
     a.bins = (const int32_t*)(base + bins_off);

@@ -54,6 +54,14 @@ int check_shape(const rpa_shape& s, std::string& err) {
         err = "k_scale and v_scale must be positive and finite, and so must their reciprocals";
         return RPA_ERR_INVALID_ARG;
     }
+    if (s.kv_merged != 0 && s.kv_merged != 1) {
+        err = "kv_merged must be 0 or 1";
+        return RPA_ERR_INVALID_ARG;
+    }
+    if (s.kv_merged && (s.kv_fp8 || s.head_dim != 128)) {
+        err = "the merged K|V pool is built for a bf16 cache at head_dim 128";
+        return RPA_ERR_UNSUPPORTED;
+    }
     if ((int64_t)s.num_pages * s.page_size * s.num_kv_heads * s.head_dim >= ((int64_t)1 << 40)) {
         err = "page pool too large";
         return RPA_ERR_UNSUPPORTED;
@@ -64,7 +72,7 @@ int check_shape(const rpa_shape& s, std::string& err) {
 int classify_batch(const rpa_shape& s, const int32_t* cu, int32_t n) {
     const int hg = s.num_q_heads / s.num_kv_heads;
     const int64_t narrow_max_q = 2 * (int64_t)narrow_q_tokens(hg);
-    const bool narrow_only = s.kv_fp8 && s.head_dim != 128;
+    const bool narrow_only = (s.kv_fp8 && s.head_dim != 128) || s.kv_merged;
     bool any_narrow = false, any_wide = false;
     for (int32_t r = 0; r < n; ++r) {
         const int64_t lq = (int64_t)cu[r + 1] - cu[r];
@@ -173,8 +181,9 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
 
     // ---- regime per sequence (Sec. 3.4) ---------------------------------
     const int64_t narrow_max_q = 2 * (int64_t)tq_narrow; // up to two narrow tiles
-    // the 8-bit cache has a wide kernel at head_dim 128 only; elsewhere every batch runs narrow
-    const bool narrow_only = s.kv_fp8 && s.head_dim != 128;
+    // the 8-bit cache has a wide kernel at head_dim 128 only; elsewhere, and with the
+    // merged K|V pool, every batch runs narrow
+    const bool narrow_only = (s.kv_fp8 && s.head_dim != 128) || s.kv_merged;
     // Wide tile height: 256 rows (half the K/V staging traffic per row, no stall
     // on the loads) when that still gives every CU several workgroups, else 128
     // rows (twice as many, independent workgroups).

@@ -23,7 +23,8 @@ VARIANT_NAMES = {0: "auto", 1: "decode", 2: "prefill", 3: "mixed"}
 class Shape(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "num_q_heads", "num_kv_heads", "head_dim", "page_size", "max_tokens", "max_seqs",
-        "max_pages_per_seq", "num_pages", "non_causal", "kv_fp8")] + [("k_scale", C.c_float), ("v_scale", C.c_float)]
+        "max_pages_per_seq", "num_pages", "non_causal", "kv_fp8")] + [("k_scale", C.c_float), ("v_scale", C.c_float),
+                                                                      ("kv_merged", C.c_int32)]
 
 
 class WorkUnit(C.Structure):
@@ -128,17 +129,20 @@ def _i32(a):
 
 
 def make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs, max_pages_per_seq,
-               num_pages, causal=True, kv_scales=None) -> Shape:
-    """kv_scales = (k_scale, v_scale) selects the 8-bit (E4M3) cache."""
+               num_pages, causal=True, kv_scales=None, kv_merged=False) -> Shape:
+    """kv_scales = (k_scale, v_scale) selects the 8-bit (E4M3) cache; kv_merged the
+    one-pool layout [num_pages, page_size, Hkv, 2, D] (K and V side by side)."""
     k_scale, v_scale = kv_scales if kv_scales is not None else (0.0, 0.0)
     return Shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs, max_pages_per_seq,
-                 num_pages, 0 if causal else 1, 0 if kv_scales is None else 1, k_scale, v_scale)
+                 num_pages, 0 if causal else 1, 0 if kv_scales is None else 1, k_scale, v_scale,
+                 1 if kv_merged else 0)
 
 
 def shape_key(shape: Shape) -> str:
     """Key of a shape in a tuning table: what the launch shapes depend on."""
     return (f"hq{shape.num_q_heads}_hkv{shape.num_kv_heads}_d{shape.head_dim}_ps{shape.page_size}"
-            f"_{'fp8' if shape.kv_fp8 else 'bf16'}{'_nomask' if shape.non_causal else ''}")
+            f"_{'fp8' if shape.kv_fp8 else 'bf16'}{'_nomask' if shape.non_causal else ''}"
+            f"{'_merged' if shape.kv_merged else ''}")
 
 
 def plan_host(shape: Shape, cu_q_lens, kv_lens, num_cus=256, variant=VARIANT_AUTO, kv_chunk=0,
@@ -185,10 +189,10 @@ class RaggedPagedAttention:
     """One context = one static shape on one GPU."""
 
     def __init__(self, num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs,
-                 max_pages_per_seq, num_pages, device=0, causal=True, kv_scales=None, library=None):
+                 max_pages_per_seq, num_pages, device=0, causal=True, kv_scales=None, library=None, kv_merged=False):
         self._lib = lib() if library is None else library
         self.shape = make_shape(num_q_heads, num_kv_heads, head_dim, page_size, max_tokens, max_seqs,
-                                max_pages_per_seq, num_pages, causal, kv_scales)
+                                max_pages_per_seq, num_pages, causal, kv_scales, kv_merged)
         self._ctx = C.c_void_p()
         rc = self._lib.rpa_create(C.byref(self._ctx), C.byref(self.shape), int(device))
         if rc != RPA_OK:
@@ -196,10 +200,11 @@ class RaggedPagedAttention:
         self.device = int(device)
 
     @classmethod
-    def for_workload(cls, wl, max_tokens=None, max_seqs=None, device=0, causal=True, kv_scales=None, library=None):
+    def for_workload(cls, wl, max_tokens=None, max_seqs=None, device=0, causal=True, kv_scales=None, library=None,
+                     kv_merged=False):
         return cls(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size,
                    max(1, max_tokens or wl.num_tokens), max(1, max_seqs or wl.num_seqs),
-                   wl.max_pages_per_seq, wl.num_pages, device, causal, kv_scales, library)
+                   wl.max_pages_per_seq, wl.num_pages, device, causal, kv_scales, library, kv_merged)
 
     def close(self):
         if getattr(self, "_ctx", None) is not None and self._ctx.value:
@@ -310,11 +315,15 @@ class RaggedPagedAttention:
         sh = self.shape
         pool_dtype = torch.uint8 if sh.kv_fp8 else torch.bfloat16     # 8-bit cache: E4M3 bytes
         pool_shape = (sh.num_pages, sh.page_size, sh.num_kv_heads, sh.head_dim)
-        for name, t, shape, dtype in (("q", q, (sh.max_tokens, sh.num_q_heads, sh.head_dim), torch.bfloat16),
-                                      ("k_new", k_new, (sh.max_tokens, sh.num_kv_heads, sh.head_dim), torch.bfloat16),
-                                      ("v_new", v_new, (sh.max_tokens, sh.num_kv_heads, sh.head_dim), torch.bfloat16),
-                                      ("k_pages", k_pages, pool_shape, pool_dtype),
-                                      ("v_pages", v_pages, pool_shape, pool_dtype)):
+        if sh.kv_merged:                    # one pool, K and V side by side; v_pages is not used
+            pool_shape = (sh.num_pages, sh.page_size, sh.num_kv_heads, 2, sh.head_dim)
+        checks = [("q", q, (sh.max_tokens, sh.num_q_heads, sh.head_dim), torch.bfloat16),
+                  ("k_new", k_new, (sh.max_tokens, sh.num_kv_heads, sh.head_dim), torch.bfloat16),
+                  ("v_new", v_new, (sh.max_tokens, sh.num_kv_heads, sh.head_dim), torch.bfloat16),
+                  ("k_pages", k_pages, pool_shape, pool_dtype)]
+        if not sh.kv_merged:
+            checks.append(("v_pages", v_pages, pool_shape, pool_dtype))
+        for name, t, shape, dtype in checks:
             if tuple(t.shape) != shape or t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
                 raise ValueError(f"{name}: expected contiguous cuda {dtype} tensor of shape {shape}, "
                                  f"got {tuple(t.shape)} {t.dtype}")
@@ -327,6 +336,6 @@ class RaggedPagedAttention:
             raise ValueError("out: wrong shape / dtype")
         st = torch.cuda.current_stream(q.device) if stream is None else stream
         self.update_and_attend_raw(out.data_ptr(), q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
-                                   k_pages.data_ptr(), v_pages.data_ptr(), page_table.data_ptr(), cu, kv, n,
-                                   float(sm_scale), st.cuda_stream)
+                                   k_pages.data_ptr(), None if sh.kv_merged else v_pages.data_ptr(), page_table.data_ptr(),
+                                   cu, kv, n, float(sm_scale), st.cuda_stream)
         return out

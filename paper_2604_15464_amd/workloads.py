@@ -304,6 +304,21 @@ def materialize(wl: Workload, device="cpu", poison: bool = True, max_tokens: int
     return {"q": q, "k_new": k_new, "v_new": v_new, "k_pages": k_pages, "v_pages": v_pages}
 
 
+def merge_pools(tensors):
+    """The same data with the two bf16 page pools laid into one,
+    [num_pages, page_size, Hkv, 2, D] (index 0 = K, 1 = V): "kv_pages" replaces
+    "k_pages" and "v_pages".  Works on torch tensors and on numpy bit patterns."""
+    out = {k: v for k, v in tensors.items() if k not in ("k_pages", "v_pages")}
+    k, v = tensors["k_pages"], tensors["v_pages"]
+    if isinstance(k, np.ndarray):
+        out["kv_pages"] = np.ascontiguousarray(np.stack([k, v], axis=3))
+    else:
+        import torch
+
+        out["kv_pages"] = torch.stack([k, v], dim=3).contiguous()
+    return out
+
+
 def bits(t):
     """torch bf16 tensor -> numpy uint16 bit patterns (host copy); uint8
     tensors (8-bit cache pools) come back as they are."""

@@ -20,7 +20,17 @@ MUTATIONS = {
     "noncausal_flag_ignored": ("if causal else np.zeros((l_q, l_kv), dtype=bool)", "if True else None"),
     "noncausal_hides_new_tokens": ("if causal else np.zeros((l_q, l_kv), dtype=bool)",
                                    "if causal else (j >= ctx) & (j > ctx + i)"),
-    "causal_flag_not_forwarded": ("heads=heads, causal=causal)", "heads=heads)"),
+    "causal_flag_not_forwarded": ("res = attend_sequence(qq, kk, vv, sm_scale, heads=heads, causal=causal)",
+                                  "res = attend_sequence(qq, kk, vv, sm_scale, heads=heads)"),
+    "merged_causal_flag_not_forwarded": ("                              sm_scale, heads=heads, causal=causal)",
+                                         "                              sm_scale, heads=heads)"),
+    "merged_reads_halves_swapped": ("bf16_to_f64(rows[:, :, 0, :]), bf16_to_f64(rows[:, :, 1, :])",
+                                    "bf16_to_f64(rows[:, :, 1, :]), bf16_to_f64(rows[:, :, 0, :])"),
+    "merged_update_swaps_halves": ("kv_pages[pg, (ctx + t) % ps, :, 1, :] = v_new[q0 + t]",
+                                   "kv_pages[pg, (ctx + t) % ps, :, 1, :] = k_new[q0 + t]"),
+    "merged_update_at_wrong_position": ("pg = int(page_table[r, (ctx + t) // ps])", "pg = int(page_table[r, t // ps])"),
+    "merged_gather_ignores_table": ("rows = kv_pages[np.asarray(page_table[r, :n_pages], dtype=np.int64)]",
+                                    "rows = kv_pages[np.arange(n_pages)]"),
     "no_mask": ("s[hidden] = -np.inf", "pass"),
     "wrong_gqa_map": ("g = h // hg\n        s = scale", "g = h % hkv\n        s = scale"),
     "missing_scale": ("s = scale * (q[:, h, :] @ k[:, g, :].T)", "s = (q[:, h, :] @ k[:, g, :].T)"),

@@ -609,3 +609,64 @@ def test_fp8_decode_equals_last_prefill_row():
     out_dec, kp2, vp2 = run_oracle_fp8(wl_dec, y)
     assert np.array_equal(kp2, kp) and np.array_equal(vp2, vp)
     assert np.allclose(out_dec[0], out_full[n - 1], rtol=0, atol=1e-12)
+
+
+# ---- merged K|V pool (Sec. 3.1.3 "KV merge") -------------------------------------
+def test_merged_pool_bruteforce_and_equals_two_pool_call():
+    """The pool is filled here token by token from contiguous K/V lists (not by
+    the packing helper), attention is checked against the pure-Python brute
+    force, and the whole call against the two-pool oracle on the same data."""
+    wl = W.ragged(5, num_seqs=4, hq=4, hkv=2, d=8, ps=16, max_q=9, max_ctx=37, p_empty=0.0)
+    x = host_inputs(wl)
+    ps = wl.page_size
+    pool = np.full((wl.num_pages, ps, wl.num_kv_heads, 2, wl.head_dim), W.POISON_BITS, dtype=np.uint16)
+    for r in range(wl.num_seqs):
+        for pos in range(int(wl.ctx_lens[r])):
+            pg = wl.page_table[r, pos // ps]
+            for g in range(wl.num_kv_heads):
+                pool[pg, pos % ps, g, 0] = x["k_pages"][pg, pos % ps, g]
+                pool[pg, pos % ps, g, 1] = x["v_pages"][pg, pos % ps, g]
+    out_m, pool_after = O.update_and_attend_merged(x["q"], x["k_new"], x["v_new"], pool, wl.page_table, wl.cu_q_lens,
+                                                   wl.kv_lens, wl.num_seqs, wl.sm_scale)
+    for r in range(wl.num_seqs):
+        q, k, v = contiguous_kv(wl, x, r)
+        q0, ctx = int(wl.cu_q_lens[r]), int(wl.ctx_lens[r])
+        for i in range(int(wl.q_lens[r])):
+            ref = O.dense_bruteforce(q[i:i + 1].tolist(), k[:ctx + i + 1].tolist(), v[:ctx + i + 1].tolist(), wl.sm_scale)
+            assert np.allclose(out_m[q0 + i], np.asarray(ref[0]), rtol=0, atol=1e-12)
+    out_s, k_after, v_after = run_oracle(wl, x)
+    t = wl.num_tokens
+    assert np.array_equal(out_m[:t], out_s[:t])
+    out_mn, _ = O.update_and_attend_merged(x["q"], x["k_new"], x["v_new"], pool, wl.page_table, wl.cu_q_lens,
+                                           wl.kv_lens, wl.num_seqs, wl.sm_scale, causal=False)
+    assert np.array_equal(out_mn[:t], run_oracle(wl, x, causal=False)[0][:t]) and not np.array_equal(out_mn[:t], out_m[:t])
+    live_or_new = (pool_after[:, :, :, 0, :] != W.POISON_BITS).all(axis=(2, 3))
+    assert np.array_equal(pool_after[live_or_new][:, :, 0], k_after[live_or_new])
+    assert np.array_equal(pool_after[live_or_new][:, :, 1], v_after[live_or_new])
+    # exactly the pre-existing slots and this call's slots hold data
+    written = np.zeros_like(live_or_new)
+    for r in range(wl.num_seqs):
+        for pos in range(int(wl.kv_lens[r])):
+            written[wl.page_table[r, pos // ps], pos % ps] = True
+    assert np.array_equal(live_or_new, written)
+    assert (pool_after[~written] == W.POISON_BITS).all()
+
+
+def test_merged_pool_k_and_v_are_not_swapped():
+    """V constant per (half): if the pool's two halves were read the other way
+    round the output would be the keys' constant."""
+    wl = W.ragged(6, num_seqs=3, hq=4, hkv=2, d=8, ps=16, max_q=4, max_ctx=20, p_empty=0.0)
+    x = host_inputs(wl, poison=False)
+    x["v_pages"][:] = f32_to_bf16_bits(np.full(8, 3.0))
+    x["v_new"][:] = f32_to_bf16_bits(np.full(8, 3.0))
+    m = W.merge_pools(x)
+    assert m["kv_pages"].shape == (wl.num_pages, wl.page_size, 2, 2, 8)
+    out, pool = O.update_and_attend_merged(m["q"], m["k_new"], m["v_new"], m["kv_pages"], wl.page_table, wl.cu_q_lens,
+                                           wl.kv_lens, wl.num_seqs, wl.sm_scale)
+    assert np.allclose(out[:wl.num_tokens], 3.0, atol=1e-12)
+    r = 0
+    pos = int(wl.kv_lens[r]) - 1
+    pg = wl.page_table[r, pos // 16]
+    last_tok = int(wl.cu_q_lens[r + 1]) - 1
+    assert np.array_equal(pool[pg, pos % 16, :, 0], x["k_new"][last_tok])
+    assert np.array_equal(pool[pg, pos % 16, :, 1], x["v_new"][last_tok])
