@@ -49,8 +49,11 @@ inline int narrow_q_tokens(int hg) { return (hg >= 1 && hg <= kNarrowRows && kNa
 // Query tokens per wide tile.
 inline int wide_q_tokens(int hg, int rows) { return rows / hg; }
 
-// LDS ring bytes of one narrow wave: stages x (K tile + V tile).
-inline int narrow_lds_per_wave(int head_dim) { return kNarrowStages * 2 * kNarrowKvTile * head_dim * 2; }
+// LDS bytes of one narrow wave: ring of stages x (K tile + V tile), then the
+// staging area of a unit's Q rows (16 rows of head_dim bf16).
+inline int narrow_lds_per_wave(int head_dim) {
+    return kNarrowStages * 2 * kNarrowKvTile * head_dim * 2 + kNarrowRows * head_dim * 2;
+}
 
 // Default waves per narrow workgroup: the largest divisor of num_kv_heads not
 // above 4 (two workgroups of 64 KB LDS per compute unit at head_dim 128, one

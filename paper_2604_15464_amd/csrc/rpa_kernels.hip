@@ -178,7 +178,7 @@ __device__ __forceinline__ int clamp_page(int page, int num_pages) {
 // wave-wide load brings two tokens' K|V pairs, and K and V rows alternate in the
 // LDS stage.  a.k_pages is the pool, a.v_pages is not used.
 template <int D, int NST, bool KV8, bool MERGED = false>
-__global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a) {
+__global__ void __launch_bounds__(64 * (D > 128 ? 4 : kMaxWaves)) rpa_narrow_kernel(KernelArgs a) {
     static_assert(!MERGED || (!KV8 && D == 128), "the merged layout is built for bf16 at head_dim 128");
     constexpr int ROWB = D * (KV8 ? 1 : 2);     // bytes of one token row of one head
     constexpr int NC = ROWB / 16;               // 16-byte chunks per row
@@ -220,8 +220,11 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     const uint64_t v_delta = (uint64_t)v_pages - (uint64_t)v_new;
     const int tok_n = n / hg; // row n = (token n / hg, head g*hg + n % hg)
     const int hh = n - tok_n * hg;
-    const uint32_t lds_wave = lds_offset(smem) + wave * (NST * STAGEB);
-    const char* lds_wave_ptr = (const char*)smem + wave * (NST * STAGEB);
+    constexpr int QSTAGEB = KSTEPS * 1024;      // a unit's Q rows, staged per wave
+    const uint32_t lds_wave = lds_offset(smem) + wave * (NST * STAGEB + QSTAGEB);
+    const char* lds_wave_ptr = (const char*)smem + wave * (NST * STAGEB + QSTAGEB);
+    const uint32_t lds_q = lds_wave + NST * STAGEB;
+    const char* lds_q_ptr = lds_wave_ptr + NST * STAGEB;
 
     // per-lane constants of the gather: load i of a tile brings token
     // m = i*TPI + lane/NC; the lane fetches the 16-byte chunk that the XOR
@@ -242,61 +245,63 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
     for (int j = 0; j < 2 * NLD; ++j) mg_chunk[j] = (uint32_t)((mg_pos ^ ((2 * j + mg_tok) % NC)) * 16);
 
     // The workgroup walks the units of its bin back to back; the waves never
-    // synchronise with each other.
-    const const_i32_ptr bins = (const_i32_ptr)(uintptr_t)a.bins;
-    const int unit_end = bins[blockIdx.x + 1];
-    for (int ui = bins[blockIdx.x]; ui < unit_end; ++ui) {
-    const rpa_work_unit u = a.units[ui];
-    const int ctx = u.ctx;
-    const const_i32_ptr pt_row = (const_i32_ptr)(uintptr_t)(a.page_table + (size_t)u.seq * a.max_pages_per_seq);
+    // synchronise with each other.  The ring does not drain between units: while
+    // the last tiles of a unit are computed, the Q rows and the first tiles of the
+    // next unit are already on their way (the Q rows through an LDS staging area of
+    // the wave, by the same asynchronous loads, so that every load of the loop is
+    // one the explicit vmcnt bookkeeping knows), and the unit's stores go out
+    // behind them.
+    //
+    // Waiting by count: "vmcnt <= N" with N = the loads requested after the wanted
+    // one.  Loads return in order, so as long as the wanted load is outstanding all
+    // N younger ones are too and the count stays above N; stores requested in
+    // between (never counted here) can only make the wait longer, not shorter.
+    struct UnitCtx {
+        int ctx, kv_begin, kv_end, seq_q0, ntiles;
+        const_i32_ptr pt_row;
+    };
+    auto load_unit = [&](int idx) {
+        // through the constant address space: scalar loads, no vmcnt traffic
+        const const_i32_ptr p = (const_i32_ptr)(uintptr_t)(a.units + idx);
+        rpa_work_unit r;
+        r.seq = p[0], r.q_start = p[1], r.q_pos0 = p[2], r.n_q = p[3], r.kv_begin = p[4], r.kv_end = p[5];
+        r.ctx = p[6], r.seq_q0 = p[7], r.part_row = p[8], r.flags = p[9], r.bin = p[10], r.reserved = p[11];
+        return r;
+    };
+    auto unit_ctx = [&](const rpa_work_unit& w) {
+        UnitCtx c;
+        c.ctx = w.ctx, c.kv_begin = w.kv_begin, c.kv_end = w.kv_end, c.seq_q0 = w.seq_q0;
+        c.ntiles = max(0, (w.kv_end - w.kv_begin + kNarrowKvTile - 1) / kNarrowKvTile);
+        c.pt_row = (const_i32_ptr)(uintptr_t)(a.page_table + (size_t)w.seq * a.max_pages_per_seq);
+        return c;
+    };
 
-    // ---- query operand ---------------------------------------------------------
-    const bool row_ok = tok_n < u.n_q;
-    // last visible KV position of the row (without the causal mask: no limit but kv_end)
-    const int limit_n = row_ok ? (a.causal ? ctx + u.q_pos0 + tok_n : 0x3fffffff) : -1;
-    bf16x8 qreg[KSTEPS];
-    {
-        const uint16_t* qrow = a.q + ((size_t)(u.q_start + (row_ok ? tok_n : 0)) * Hq + g * hg + hh) * D;
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (row_ok) raw = *(const uint4*)(qrow + kk * 32 + quad * 8);
-            qreg[kk] = __builtin_bit_cast(bf16x8, raw);
-        }
-    }
-    // All ordinary loads are complete from here on: inside the loop vmcnt counts
-    // the ring's asynchronous loads only.
-    wait_vmcnt<0>();
-
-    const int kv_begin = u.kv_begin, kv_end = u.kv_end;
-    const int ntiles = max(0, (kv_end - kv_begin + kNarrowKvTile - 1) / kNarrowKvTile);
-
-    auto issue_tile = [&](int t) {
+    // tile t of a unit into ring slot `slot`
+    auto issue_tile = [&](const UnitCtx& c, int t, int slot) {
         if (RPA_ABLATED(a, 4)) return; // measurement: no K/V traffic (the math runs on whatever the LDS holds)
-        const int pos0 = kv_begin + t * kNarrowKvTile;
-        const int slot = t % NST;
+        const int pos0 = c.kv_begin + t * kNarrowKvTile;
         const int pidx = __builtin_amdgcn_readfirstlane(pos0 >> ps_log2);
-        const int page = clamp_page(pt_row[pidx], num_pages); // a tile never straddles pages
+        const int page = clamp_page(c.pt_row[pidx], num_pages); // a tile never straddles pages
         const uint32_t ldsK = lds_wave + slot * STAGEB;
         const uint32_t ldsV = ldsK + VOFF;
-        const int last = kv_end - 1 - pos0; // tokens past the range re-read its last token
+        const int last = c.kv_end - 1 - pos0; // tokens past the range re-read its last token
         if constexpr (MERGED) {
             const size_t page_tok = ((size_t)page << ps_log2);
 #pragma unroll
             for (int j = 0; j < 2 * NLD; ++j) {
                 const int pos = pos0 + min(2 * j + mg_tok, last);
-                const bool cached = pos < ctx;
+                const bool cached = pos < c.ctx;
                 // cached: the token's K|V pair of this head in the pool; new: the K or the V row of the call's inputs
                 const uint64_t addr =
                     cached ? (uint64_t)k_pages + (page_tok + (size_t)(pos & ps_mask)) * tokstride + (uint32_t)g * HEADB +
                                  (uint32_t)mg_sub * ROWB + mg_chunk[j]
-                           : (uint64_t)(mg_sub ? v_new : k_new) + (uint64_t)(u.seq_q0 + pos - ctx) * newstride +
+                           : (uint64_t)(mg_sub ? v_new : k_new) + (uint64_t)(c.seq_q0 + pos - c.ctx) * newstride +
                                  (uint32_t)g * ROWB + mg_chunk[j];
                 async_load16_stream((const void*)addr, ldsK + j * 1024);
             }
             return;
         }
-        if (pos0 + kNarrowKvTile <= ctx) {
+        if (pos0 + kNarrowKvTile <= c.ctx) {
             // whole tile is cached content: one scalar base per pool
             const size_t tile_off = (((size_t)page << ps_log2) + (size_t)(pos0 & ps_mask)) * tokstride;
             const char* kb = k_pages + tile_off;
@@ -314,9 +319,9 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
                 const int pos = pos0 + min(i * TPI + ld_tok, last);
-                const bool cached = pos < ctx;
+                const bool cached = pos < c.ctx;
                 const size_t tokidx = cached ? (((size_t)page << ps_log2) + (size_t)(pos & ps_mask))
-                                             : (size_t)(u.seq_q0 + pos - ctx);
+                                             : (size_t)(c.seq_q0 + pos - c.ctx);
                 // select the pool by adding a wave-uniform pointer difference
                 // (tokstride == newstride here: the merged layout took its own path above)
                 const uint64_t off = (uint64_t)tokidx * tokstride + lane_off[i];
@@ -328,26 +333,101 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         }
     };
 
+    // Q rows of a unit into the wave's staging area: k-step kk of lane i lands at
+    // kk * 1024 + 16 * i, where the same lane reads it back.  A padding row fetches
+    // the tile's first token (always there) and is zeroed after the read.
+    auto issue_q = [&](const rpa_work_unit& w) {
+        const char* qrow =
+            (const char*)(a.q + ((size_t)(w.q_start + (tok_n < w.n_q ? tok_n : 0)) * Hq + g * hg + hh) * D) + quad * 16;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) async_load16(qrow + kk * 64, lds_q + kk * 1024);
+    };
+    bf16x8 qreg[KSTEPS];
+    auto read_q = [&](const rpa_work_unit& w) {
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 raw = *(const uint4*)(lds_q_ptr + kk * 1024 + lane * 16);
+            if (tok_n >= w.n_q) raw = make_uint4(0, 0, 0, 0);
+            qreg[kk] = __builtin_bit_cast(bf16x8, raw);
+        }
+    };
+    // wait until at most `tiles` whole tiles (and the Q rows of the next unit, if
+    // they were requested behind the wanted load) are outstanding
+    auto wait_behind = [&](int tiles, bool q_behind) {
+        const int code = 2 * tiles + (q_behind ? 1 : 0);
+        if (code == 0) wait_vmcnt<0>();
+        else if (code == 1) wait_vmcnt<KSTEPS>();
+        else if (code == 2) wait_vmcnt<LOADS_PER_STAGE>();
+        else if (code == 3) wait_vmcnt<LOADS_PER_STAGE + KSTEPS>();
+        else if (NST >= 3 && code == 4) wait_vmcnt<(NST >= 3 ? 2 : 0) * LOADS_PER_STAGE>();
+        else if (NST >= 3 && code == 5) wait_vmcnt<(NST >= 3 ? 2 : 0) * LOADS_PER_STAGE + KSTEPS>();
+        else if (NST >= 4 && code == 6) wait_vmcnt<(NST >= 4 ? 3 : 0) * LOADS_PER_STAGE>();
+        else if (NST >= 4 && code == 7) wait_vmcnt<(NST >= 4 ? 3 : 0) * LOADS_PER_STAGE + KSTEPS>();
+        else wait_vmcnt<0>();
+    };
+    static_assert(NST <= 4, "wait_behind covers rings of up to four stages");
+
+    const const_i32_ptr bins = (const_i32_ptr)(uintptr_t)a.bins;
+    int ui = bins[blockIdx.x];
+    const int unit_end = bins[blockIdx.x + 1];
+    if (ui >= unit_end) return;
+
+    rpa_work_unit un = load_unit(ui);
+    UnitCtx cn = unit_ctx(un);
+    int sbase = 0; // ring slot of tile 0 of the unit whose loop runs next
+    int pre = 0;   // tiles of that unit already requested
+    issue_q(un);
+    for (; pre < min(NST - 1, cn.ntiles); ++pre) issue_tile(cn, pre, (sbase + pre) % NST);
+    wait_behind(RPA_ABLATED(a, 4) ? 0 : pre, false);
+    read_q(un);
+
+    for (;;) {
+    const rpa_work_unit u = un;
+    const UnitCtx c = cn;
+    const bool has_next = ui + 1 < unit_end;
+    if (has_next) {
+        un = load_unit(ui + 1);
+        cn = unit_ctx(un);
+    }
+    const int lim_next = has_next ? min(NST - 1, cn.ntiles) : 0;
+    int pre_next = 0; // tiles of the next unit requested so far
+    const int ctx = c.ctx;
+    const int kv_begin = c.kv_begin, kv_end = c.kv_end, ntiles = c.ntiles;
+    const const_i32_ptr pt_row = c.pt_row;
+
+    const bool row_ok = tok_n < u.n_q;
+    // last visible KV position of the row (without the causal mask: no limit but kv_end)
+    const int limit_n = row_ok ? (a.causal ? ctx + u.q_pos0 + tok_n : 0x3fffffff) : -1;
+
+    // a predecessor with fewer tiles than the ring is deep has not requested all of
+    // this unit's first tiles
+    for (; pre < min(NST - 1, ntiles); ++pre) issue_tile(c, pre, (sbase + pre) % NST);
+
     f32x4 acc[MT];
 #pragma unroll
     for (int j = 0; j < MT; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY; // running max, log2 domain (score * sm_scale * log2 e)
     float l_run = 0.f;       // this lane's share of the running sum
 
-#pragma unroll
-    for (int s = 0; s < NST - 1; ++s)
-        if (s < ntiles) issue_tile(s);
-
     for (int t = 0; t < ntiles; ++t) {
-        if (t + NST - 1 < ntiles) issue_tile(t + NST - 1);
-        // tiles still in flight behind tile t
-        const int behind = min(NST - 1, ntiles - 1 - t);
-        if (NST >= 4 && behind >= 3) wait_vmcnt<(NST >= 4 ? 3 : 0) * LOADS_PER_STAGE>();
-        else if (NST >= 3 && behind == 2) wait_vmcnt<(NST >= 3 ? 2 : 0) * LOADS_PER_STAGE>();
-        else if (NST >= 2 && behind == 1) wait_vmcnt<(NST >= 2 ? 1 : 0) * LOADS_PER_STAGE>();
-        else wait_vmcnt<0>();
+        // keep the ring full: tile t + NST - 1 of this unit, or, past its end, the
+        // next unit's Q rows and first tiles (the slots they take are those of tiles
+        // this loop has already consumed)
+        const int j = t + NST - 1;
+        if (j < ntiles) {
+            issue_tile(c, j, (sbase + j) % NST);
+        } else {
+            const int kmax = min(j - ntiles + 1, lim_next);
+            while (pre_next < kmax) {
+                if (pre_next == 0) issue_q(un);
+                issue_tile(cn, pre_next, (sbase + ntiles + pre_next) % NST);
+                ++pre_next;
+            }
+        }
+        if (!RPA_ABLATED(a, 4)) wait_behind(min(NST - 1, ntiles - 1 - t) + pre_next, pre_next > 0);
+        else wait_behind(0, pre_next > 0);
 
-        const char* ldsK = lds_wave_ptr + (t % NST) * STAGEB;
+        const char* ldsK = lds_wave_ptr + ((sbase + t) % NST) * STAGEB;
         const char* ldsV = ldsK + VOFF;
         const int pos0 = kv_begin + t * kNarrowKvTile;
         if (RPA_ABLATED(a, 1)) { // measurement: loads and stores only
@@ -451,27 +531,58 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
         }
     }
 
+    // ---- the next unit's Q rows: requested behind its first tile at the latest ----
+    const float m_fin = m_run, l_fin = l_run; // this unit's state; the registers of Q are free for the next unit's rows
+    if (has_next) {
+        if (pre_next == 0) issue_q(un); // nothing of the next unit was requested inside the loop
+        wait_behind(RPA_ABLATED(a, 4) ? 0 : pre_next, false);
+        read_q(un);
+    }
+
     // ---- fused cache update (Alg. 1: "update new KV entries"), once per tile.
     // Readers never take positions >= ctx from the pages (they read k_new / v_new),
-    // so this store races with nothing; it sits after the loop so that only loads
-    // are in flight while the ring's vmcnt bookkeeping runs.
+    // so this store races with nothing.  When the tile's new rows all lie in the
+    // last KV tile of this unit (decode: always) they are still in its ring slot,
+    // which nothing overwrites before the next unit's first step, and are copied
+    // from there (Sec. 3.3: the update goes out from the on-chip block).
     if ((u.flags & 1) && !RPA_ABLATED(a, 2)) {
-        const int c = lane % NC;
-        for (int t = lane / NC; t < u.n_q; t += 64 / NC) {
-            const int pos = ctx + u.q_pos0 + t;
-            const int page = clamp_page(pt_row[pos >> ps_log2], num_pages);
-            const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * ROWB + c * 16; // bytes
-            const size_t dst = (((size_t)page << ps_log2) + (pos & ps_mask)) * tokstride + (size_t)g * HEADB + c * 16;
-            const uint4 kk = *(const uint4*)(k_new + src);
-            const uint4 vv = *(const uint4*)(v_new + src);
+        const int cch = lane % NC;
+        const int p_first = ctx + u.q_pos0;
+        const int last_pos0 = kv_begin + (ntiles - 1) * kNarrowKvTile;
+        const bool in_ring = ntiles > 0 && p_first >= last_pos0 && p_first + u.n_q <= kv_end && !RPA_ABLATED(a, 4);
+        const char* ldsK = lds_wave_ptr + ((sbase + ntiles - 1 + NST) % NST) * STAGEB;
+        const char* ldsV = ldsK + VOFF;
+        // at most 16 consecutive positions: one page, or two (page ids by scalar loads)
+        const int pi_lo = __builtin_amdgcn_readfirstlane(p_first >> ps_log2);
+        const int pi_hi = __builtin_amdgcn_readfirstlane((p_first + u.n_q - 1) >> ps_log2);
+        const int page_lo = clamp_page(pt_row[pi_lo], num_pages);
+        const int page_hi = clamp_page(pt_row[pi_hi], num_pages);
+        auto put_rows = [&](int pos, const uint4& kk, const uint4& vv) {
+            const int page = (pos >> ps_log2) == pi_lo ? page_lo : page_hi;
+            const size_t dst = (((size_t)page << ps_log2) + (pos & ps_mask)) * tokstride + (size_t)g * HEADB + cch * 16;
             store16_streaming((char*)a.k_pages + dst, kk);
             if constexpr (MERGED) store16_streaming((char*)a.k_pages + dst + ROWB, vv); // V sits beside K in the token's row
             else store16_streaming((char*)a.v_pages + dst, vv);
+        };
+        // two separate loops: the one that copies from the ring must hold no global
+        // load, or the compiler's own vmcnt waits would drain the next unit's tiles
+        if (in_ring) {
+            for (int t = lane / NC; t < u.n_q; t += 64 / NC) {
+                const int r = p_first + t - last_pos0;
+                const int off = r * PITCH + ((cch ^ (r % NC)) * 16);
+                put_rows(p_first + t, *(const uint4*)(ldsK + off), *(const uint4*)(ldsV + off));
+                asm volatile("; rows copied from the ring" ::: "memory"); // keeps this block from being merged with the loop below
+            }
+        } else {
+            for (int t = lane / NC; t < u.n_q; t += 64 / NC) {
+                const size_t src = ((size_t)(u.q_start + t) * Hkv + g) * ROWB + cch * 16; // bytes
+                put_rows(p_first + t, *(const uint4*)(k_new + src), *(const uint4*)(v_new + src));
+            }
         }
     }
 
     // ---- finalize (Alg. 1: diag(l)^-1 B_o) or store the partial state ------------
-    float l_tot = l_run + __shfl_xor(l_run, 16);
+    float l_tot = l_fin + __shfl_xor(l_fin, 16);
     l_tot += __shfl_xor(l_tot, 32);
     const int head = g * hg + hh;
     if (!row_ok) {
@@ -511,13 +622,16 @@ __global__ void __launch_bounds__(64 * kMaxWaves) rpa_narrow_kernel(KernelArgs a
                                     acc[JW * vg + 4 * c4 + 2][v] * os, acc[JW * vg + 4 * c4 + 3][v] * os);
             }
         if (quad == 0) {
-            a.part_ml[prow * 2] = m_run;
+            a.part_ml[prow * 2] = m_fin;
             a.part_ml[prow * 2 + 1] = l_tot;
         }
     }
-    // every store and load of this unit is complete before the next unit's ring starts
-    wait_vmcnt<0>();
+    if (!has_next) break;
+    ++ui;
+    sbase = (sbase + ntiles) % NST;
+    pre = pre_next;
     } // units of the bin
+    // stores drain with the end of the wave
 }
 
 
@@ -1383,7 +1497,7 @@ __global__ __launch_bounds__(256) void rpa_copy_kernel(uint4* __restrict__ dst, 
 // ---------------------------------------------------------------------------
 template <int D>
 static size_t narrow_lds_bytes(int waves) {
-    return (size_t)waves * kNarrowStages * 2 * kNarrowKvTile * D * 2;
+    return (size_t)waves * narrow_lds_per_wave(D);
 }
 
 template <int D>
