@@ -189,10 +189,12 @@ typedef struct {
                               event (one more packet on the stream, about 5 us of
                               GPU idle time per call)                                  */
     int32_t wide_persistent; /* 256-row wide tiles at head_dim 64 / 128 with a bf16 cache:
-                              0 = one persistent workgroup per CU walks the (tile, KV
-                              head) items (the next item's Q tile and first K/V
-                              tiles are requested while the current one finishes);
-                              1 = one workgroup per item                               */
+                              0 = when the items are short (under 64 K/V tiles each
+                              on average) one persistent workgroup per CU walks the
+                              (tile, KV head) items (the next item's Q tile and
+                              first K/V tiles are requested while the current one
+                              finishes), else one workgroup per item;
+                              1 = always one workgroup per item                        */
 } rpa_options;
 
 typedef struct rpa_ctx rpa_ctx;

@@ -454,7 +454,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     a.kv_fp8 = c->shape.kv_fp8;
     a.out_scale = 1.f;
     a.kv_merged = c->shape.kv_merged;
-    a.wide_persist_grid = opt_used.wide_persistent == 1 ? 0 : c->num_cus;
+    a.wide_persist_grid = (opt_used.wide_persistent == 1 || !plan.wide_persistent_pays()) ? 0 : c->num_cus;
     if (a.kv_fp8) {
         // The new rows are quantised into the staging copy first; from there on the
         // kernels see bytes only.  K's scale folds into the softmax scale, V's is

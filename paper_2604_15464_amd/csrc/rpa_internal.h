@@ -28,6 +28,15 @@ struct Plan {
     std::vector<rpa_work_unit> wide;   // launch order
     std::vector<rpa_combine_item> items;
     rpa_plan_stats stats{};
+    // Wide launch form: persistent workgroups pay where items are short (the edges of
+    // neighbouring items overlap: config 3, 16 tiles per item on average, -2..4 %);
+    // where items are long the walk itself costs more than the edges it hides
+    // (one sequence of 16 K-32 K tokens: +1.5 %), and one workgroup per item runs.
+    bool wide_persistent_pays() const {
+        int64_t tiles = 0;
+        for (const rpa_work_unit& u : wide) tiles += (u.kv_end - u.kv_begin + kWideKvTile - 1) / kWideKvTile;
+        return !wide.empty() && tiles < (int64_t)64 * (int64_t)wide.size();
+    }
 };
 
 // Validates shape; returns RPA_OK or an error with a message.

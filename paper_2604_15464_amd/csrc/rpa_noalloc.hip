@@ -185,7 +185,7 @@ extern "C" int rpa_update_and_attend_noalloc(const rpa_shape* shape, int device,
     a.kv_fp8 = 0;
     a.out_scale = 1.f;
     a.kv_merged = shape[0].kv_merged;
-    a.wide_persist_grid = s->num_cus;
+    a.wide_persist_grid = plan.wide_persistent_pays() ? s->num_cus : 0;
     a.units = (const rpa_work_unit*)base;
     a.bins = (const int32_t*)(base + bins_off);
     int hrc = launch_narrow(a, (int)n_bins, plan.stats.narrow_waves, stream, nullptr);
