@@ -760,6 +760,36 @@ def test_needles_shapes_and_tile_heights(shape, wide_rows):
             check(wl, res)
 
 
+def _hand_built(seed, hq, hkv, d, ps, q_lens, kv_lens):
+    rng = np.random.default_rng(seed)
+    need = int(W.pages_needed(kv_lens, ps).sum()) + 3
+    return W.Workload(f"hand_{seed}", seed, hq, hkv, d, ps, need, q_lens, kv_lens,
+                      W.make_page_table(kv_lens, ps, need, rng))
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(32, 8, 128), (8, 8, 128), (4, 2, 64), (8, 2, 256)])
+@pytest.mark.parametrize("kv_scales", [None, KV_SCALES])
+def test_narrow_units_back_to_back_and_both_cache_write_paths(hq, hkv, d, kv_scales):
+    """The narrow kernel keeps its ring running across units and writes the cache either
+    from the ring slot of a unit's last tile or, when the new rows do not all lie there,
+    from k_new / v_new.  Lengths chosen per case: new rows inside the last KV tile, new
+    rows spanning two KV tiles, spanning a page boundary, a one-tile unit between long
+    ones, a sequence that is all new, forced cuts so that one workgroup walks many
+    units; with needle inputs every output row names the slot it read."""
+    nq = 16 // (hq // hkv)                     # tokens of a narrow tile
+    q = [1, nq, nq, 1, min(2 * nq, 24), 1, 3, nq, 1, 2]
+    kv = [700, 40 + nq, 16 * 9 + 3, 5, min(2 * nq, 24), 16 * 20, 16 * 4 + 2, 1000, 17, 300]
+    wl = _hand_built(77 + hq + d, hq, hkv, d, 16, q, kv)
+    for variant in (rpa.VARIANT_DECODE,):
+        for chunk in (0, 48, 16):
+            for needles in (None, ("boundaries", chunk), ("spread", 3)):
+                for causal in (True, False):
+                    res = run_case(wl, variant=variant, kv_chunk=chunk, kv_scales=kv_scales, needles=needles,
+                                   causal=causal, pad_tokens=2, narrow_waves=(0, 1, 2)[chunk // 24])
+                    check(wl, res)
+                    assert res["info"]["num_wide_units"] == 0
+
+
 # ---------------------------------------------------------------------------
 # Measurement switches (ablation by leaving a stage out, Sec. 4): they exist in
 # the measurement build of the library only.  Every switch once on a small mixed
