@@ -10,6 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librpa.so")
 LIB_ABLATE = os.path.join(HERE, "librpa_ablate.so")  # measurement build, loaded by ablation.py only
+PROBE = os.path.join(HERE, "wide_loop_probe")        # stand-alone measurement program, no part of the library
 
 SOURCES = ["rpa_api.cpp", "rpa_partition.cpp", "rpa_kernels.hip", "rpa_noalloc.hip"]
 
@@ -57,8 +58,21 @@ def build_ablation_library(verbose: bool = True) -> str:
     return build_library(verbose, extra_flags=("-DRPA_ABLATE",), out=LIB_ABLATE)
 
 
+def build_probe(verbose: bool = True) -> str:
+    """The wide kernel's loop without memory traffic as a program of its own
+    (csrc/wide_loop_probe.hip): core clocks per tile and sustained clock."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wno-unused-command-line-argument", os.path.join(CSRC, "wide_loop_probe.hip"), "-o", PROBE]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + "\n" + res.stderr)
+    return PROBE
+
+
 def build_all(verbose: bool = True):
-    return [build_library(verbose), build_ablation_library(verbose)]
+    return [build_library(verbose), build_ablation_library(verbose), build_probe(verbose)]
 
 
 if __name__ == "__main__":
