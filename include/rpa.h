@@ -139,7 +139,9 @@ typedef struct {
     int64_t partial_rows;    /* fp32 partial rows used                                */
     int64_t workspace_bytes; /* device workspace owned by the context                 */
     int32_t wide_rows;       /* query rows (tokens x heads of a group) per wide tile  */
-    int32_t concurrent;      /* 1: narrow and wide kernels were enqueued side by side  */
+    int32_t concurrent;      /* 1: narrow and wide kernels were enqueued side by side on
+                                two streams; 2: as one launch that holds both kinds of
+                                workgroup                                              */
 } rpa_plan_stats;
 
 /* Tuning knobs; all-zero = defaults.  They change speed only, never results
@@ -181,7 +183,12 @@ typedef struct {
                               forked from and joined to the caller's stream) when both
                               parts are large enough to repay the two extra stream
                               packets; 1 = always one after the other on the caller's
-                              stream; 2 = always side by side                          */
+                              stream; 2 = always side by side; 3 = always side by side
+                              and as two kernels on two streams.  Side by side means
+                              one launch that holds narrow and wide workgroups where
+                              that kernel is built (bf16 cache in separate pools,
+                              head_dim 64 / 128, four waves per narrow workgroup,
+                              128-row wide tiles), else the two-stream form          */
     int32_t stream_ordered_upload; /* 0 = the host waits (a few microseconds) until the
                               call's work list has reached the device before it
                               enqueues the kernels; 1 = the host never waits: the
@@ -302,7 +309,8 @@ int rpa_set_regime_options(rpa_ctx* ctx, int32_t regime, const rpa_options* opt)
  * on the call's stream (at most 1024 calls are kept between two reads).  rpa_profile_read()
  * synchronises on the last recorded event and adds up, over the calls since the
  * previous read, the milliseconds spent in the narrow kernel, the wide kernel
- * and the combine kernel; *calls receives the number of calls covered.        */
+ * and the combine kernel (the one launch of a mixed batch counts as the narrow
+ * kernel); *calls receives the number of calls covered.                        */
 int rpa_profile_enable(rpa_ctx* ctx, int on);
 int rpa_profile_read(rpa_ctx* ctx, float* narrow_ms, float* wide_ms, float* combine_ms,
                      int32_t* calls);

@@ -203,7 +203,7 @@ extern "C" int rpa_set_options(rpa_ctx* c, const rpa_options* opt) {
         o.units_per_cu < 0 || o.narrow_waves < 0 || o.narrow_waves > kMaxWaves ||
         (o.narrow_waves > 0 && c->shape.num_kv_heads % o.narrow_waves != 0) ||
         (o.wide_rows != 0 && o.wide_rows != 128 && o.wide_rows != 256) || o.wide_order < 0 || o.wide_order > 2 ||
-        o.mixed_overlap < 0 || o.mixed_overlap > 2 || o.stream_ordered_upload < 0 || o.stream_ordered_upload > 1 ||
+        o.mixed_overlap < 0 || o.mixed_overlap > 3 || o.stream_ordered_upload < 0 || o.stream_ordered_upload > 1 ||
         o.wide_persistent < 0 || o.wide_persistent > 1 || !options_fit_shape(c->shape, o))
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: bad value");
 #ifdef RPA_ABLATE
@@ -478,20 +478,32 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     // (after the caller's stream has the work list) and joined before the combine.
     // The two kernels touch disjoint query tokens, partial rows and cache slots.
     const bool concurrent = plan.stats.concurrent != 0;
+    // one launch with both kinds of workgroup where that kernel is built, else two
+    // kernels on two streams
+    const bool one_launch = concurrent && opt_used.mixed_overlap != 3 && n_narrow > 0 && n_wide > 0 &&
+                            mixed_launch_built(a, plan.stats.narrow_waves);
+    if (one_launch) {
+        a.wide_units = dev_units + n_narrow;
+        hrc = launch_mixed(a, (int)n_bins, (int)n_wide, stream, pe ? (void**)&pe->ev[0] : nullptr);
+        if (hrc != 0) return hip_fail(c, "mixed kernel launch", (hipError_t)hrc);
+        plan.stats.concurrent = 2;
+    }
     void* wide_stream = stream;
-    if (concurrent) {
+    if (concurrent && !one_launch) {
         e = hipEventRecord(slot.fork, st);
         if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
         e = hipStreamWaitEvent(c->side, slot.fork, 0);
         if (e != hipSuccess) return hip_fail(c, "hipStreamWaitEvent", e);
         wide_stream = (void*)c->side;
     }
-    hrc = launch_narrow(a, (int)n_bins, plan.stats.narrow_waves, stream, pe ? (void**)&pe->ev[0] : nullptr);
-    if (hrc != 0) return hip_fail(c, "narrow kernel launch", (hipError_t)hrc);
-    a.units = dev_units + n_narrow;
-    hrc = launch_wide(a, (int)n_wide, wide_stream, pe ? (void**)&pe->ev[2] : nullptr);
-    if (hrc != 0) return hip_fail(c, "wide kernel launch", (hipError_t)hrc);
-    if (concurrent) {
+    if (!one_launch) {
+        hrc = launch_narrow(a, (int)n_bins, plan.stats.narrow_waves, stream, pe ? (void**)&pe->ev[0] : nullptr);
+        if (hrc != 0) return hip_fail(c, "narrow kernel launch", (hipError_t)hrc);
+        a.units = dev_units + n_narrow;
+        hrc = launch_wide(a, (int)n_wide, wide_stream, pe ? (void**)&pe->ev[2] : nullptr);
+        if (hrc != 0) return hip_fail(c, "wide kernel launch", (hipError_t)hrc);
+    }
+    if (concurrent && !one_launch) {
         e = hipEventRecord(slot.join, c->side);
         if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
         e = hipStreamWaitEvent(st, slot.join, 0);
@@ -511,7 +523,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     }
     if (pe) {
         pe->narrow = n_narrow > 0;
-        pe->wide = n_wide > 0;
+        pe->wide = n_wide > 0 && !one_launch; // the one launch of a mixed batch is timed as the narrow kernel
         pe->combine = n_items > 0;
         ++c->prof_count;
     }

@@ -177,8 +177,11 @@ __device__ __forceinline__ int clamp_page(int page, int num_pages) {
 // merge, Sec. 3.1.3): a token's K and V of one head are 512 contiguous bytes, one
 // wave-wide load brings two tokens' K|V pairs, and K and V rows alternate in the
 // LDS stage.  a.k_pages is the pool, a.v_pages is not used.
-template <int D, int NST, bool KV8, bool MERGED = false>
-__global__ void __launch_bounds__(64 * (D > 128 ? 4 : kMaxWaves)) rpa_narrow_kernel(KernelArgs a) {
+// (The body is a device function so that the mixed-batch kernel below can run it
+// in some of its workgroups: `units` is the narrow unit list, `bin` and `row` what
+// blockIdx.x and blockIdx.y are in a launch of its own.)
+template <int D, int NST, bool KV8, bool MERGED>
+__device__ __forceinline__ void narrow_body(const KernelArgs& a, const rpa_work_unit* units, int bin, int row) {
     static_assert(!MERGED || (!KV8 && D == 128), "the merged layout is built for bf16 at head_dim 128");
     constexpr int ROWB = D * (KV8 ? 1 : 2);     // bytes of one token row of one head
     constexpr int NC = ROWB / 16;               // 16-byte chunks per row
@@ -201,7 +204,7 @@ __global__ void __launch_bounds__(64 * (D > 128 ? 4 : kMaxWaves)) rpa_narrow_ker
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int nwaves = blockDim.x >> 6;
-    const int g = blockIdx.y * nwaves + wave; // KV head of this wave
+    const int g = row * nwaves + wave; // KV head of this wave
     const int n = lane & 15;                  // query row of this lane (MFMA column)
     const int quad = lane >> 4;
 
@@ -262,7 +265,7 @@ __global__ void __launch_bounds__(64 * (D > 128 ? 4 : kMaxWaves)) rpa_narrow_ker
     };
     auto load_unit = [&](int idx) {
         // through the constant address space: scalar loads, no vmcnt traffic
-        const const_i32_ptr p = (const_i32_ptr)(uintptr_t)(a.units + idx);
+        const const_i32_ptr p = (const_i32_ptr)(uintptr_t)(units + idx);
         rpa_work_unit r;
         r.seq = p[0], r.q_start = p[1], r.q_pos0 = p[2], r.n_q = p[3], r.kv_begin = p[4], r.kv_end = p[5];
         r.ctx = p[6], r.seq_q0 = p[7], r.part_row = p[8], r.flags = p[9], r.bin = p[10], r.reserved = p[11];
@@ -368,8 +371,8 @@ __global__ void __launch_bounds__(64 * (D > 128 ? 4 : kMaxWaves)) rpa_narrow_ker
     static_assert(NST <= 4, "wait_behind covers rings of up to four stages");
 
     const const_i32_ptr bins = (const_i32_ptr)(uintptr_t)a.bins;
-    int ui = bins[blockIdx.x];
-    const int unit_end = bins[blockIdx.x + 1];
+    int ui = bins[bin];
+    const int unit_end = bins[bin + 1];
     if (ui >= unit_end) return;
 
     rpa_work_unit un = load_unit(ui);
@@ -634,6 +637,11 @@ __global__ void __launch_bounds__(64 * (D > 128 ? 4 : kMaxWaves)) rpa_narrow_ker
     // stores drain with the end of the wave
 }
 
+template <int D, int NST, bool KV8, bool MERGED = false>
+__global__ void __launch_bounds__(64 * (D > 128 ? 4 : kMaxWaves)) rpa_narrow_kernel(KernelArgs a) {
+    narrow_body<D, NST, KV8, MERGED>(a, a.units, (int)blockIdx.x, (int)blockIdx.y);
+}
+
 
 // ---------------------------------------------------------------------------
 // Wide kernel: query tile of 32 * WAVES rows = (32 * WAVES / h_g) tokens x the h_g
@@ -661,9 +669,11 @@ __global__ void __launch_bounds__(64 * (D > 128 ? 4 : kMaxWaves)) rpa_narrow_ker
 // first K/V tiles are requested before the current item's output rows are
 // stored, so that neither a workgroup launch, nor the Q fetch, nor the drain of
 // the output stores stands between two items.
-template <int D, int WAVES, int NST, bool KV8, bool PERSIST = false>
-__global__ void __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(D > 128 ? 1 : 2)))
-rpa_wide_kernel(KernelArgs a) {
+// (Body as a device function, like the narrow kernel's: `units` is the wide unit
+// list, `block` and `nblocks` what blockIdx.x and gridDim.x are in a launch of
+// its own.)
+template <int D, int WAVES, int NST, bool KV8, bool PERSIST>
+__device__ __forceinline__ void wide_body(const KernelArgs& a, const rpa_work_unit* units, int block, int nblocks) {
     static_assert(!KV8 || D == 128, "the 8-bit wide kernel is built for head_dim 128");
     static_assert(!PERSIST || (!KV8 && WAVES == 8 && NST == 3 && D <= 128), "shape the persistent loop is built for");
     constexpr int NT = 1; // 32-row groups per wave
@@ -693,20 +703,20 @@ rpa_wide_kernel(KernelArgs a) {
     // direction so that the long and the short items of the sorted list even out.
     int round = 0;
     auto item_of_round = [&](int r) {
-        const int idx = r * (int)gridDim.x + ((r & 1) ? (int)gridDim.x - 1 - (int)blockIdx.x : (int)blockIdx.x);
+        const int idx = r * nblocks + ((r & 1) ? nblocks - 1 - block : block);
         return (PERSIST && idx < a.num_wide_items) ? idx : -1;
     };
     // unit records are read through the constant address space: scalar loads, so
     // that everything derived from them stays in scalar registers
     auto load_unit = [&](int idx) {
-        const const_i32_ptr p = (const_i32_ptr)(uintptr_t)(a.units + idx);
+        const const_i32_ptr p = (const_i32_ptr)(uintptr_t)(units + idx);
         rpa_work_unit r;
         r.seq = p[0], r.q_start = p[1], r.q_pos0 = p[2], r.n_q = p[3], r.kv_begin = p[4], r.kv_end = p[5];
         r.ctx = p[6], r.seq_q0 = p[7], r.part_row = p[8], r.flags = p[9], r.bin = p[10], r.reserved = p[11];
         return r;
     };
-    int g = (int)blockIdx.x % Hkv;
-    rpa_work_unit u = load_unit(blockIdx.x / Hkv);
+    int g = block % Hkv;
+    rpa_work_unit u = load_unit(block / Hkv);
     const int hg = a.hg;
     const int Hq = a.num_q_heads;
     const int ps_log2 = a.page_size_log2;
@@ -1400,6 +1410,41 @@ rpa_wide_kernel(KernelArgs a) {
     }
 }
 
+template <int D, int WAVES, int NST, bool KV8, bool PERSIST = false>
+__global__ void __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(D > 128 ? 1 : 2)))
+rpa_wide_kernel(KernelArgs a) {
+    wide_body<D, WAVES, NST, KV8, PERSIST>(a, a.units, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// ---------------------------------------------------------------------------
+// Mixed batches (Sec. 3.4, the "mixed" case of the paper's three): one launch
+// whose workgroups are narrow ones (four waves, one bin and one group of four KV
+// heads each) and wide ones of the 128-row shape (four waves), so that a CU holds
+// one of each: the narrow part is bound by HBM, the wide part by the matrix and
+// vector pipes.  As two kernels on two streams the same pairing costs an event
+// from the second stream back to the first and the wait for it, 15-20 us of idle
+// GPU per call.  The narrow workgroups come first in the grid: the dispatcher
+// spreads consecutive workgroups over the CUs before it doubles up, so each CU
+// gets one narrow workgroup, which streams for the whole kernel, and the wide
+// ones take the second slot of every CU in turn.  (Measured on 128 decode
+// sequences + 4 chunks of 512: 404 us; the two kinds alternating in groups of 8,
+// 16 or 32 ids: 440-460 us, since some CUs then hold two narrow workgroups;
+// wide first: 455 us; wide waves at a raised priority: 418 us; two streams:
+// 418 us.)  A wide item's KV head is item % Hkv, so with Hkv a multiple of 8
+// all items of a head still meet in one XCD's L2, whatever the offset.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) rpa_mixed_kernel(KernelArgs a) {
+    const int nn = a.mixed_narrow_wgs;
+    const bool narrow = (int)blockIdx.x < nn;
+    const int idx = narrow ? (int)blockIdx.x : (int)blockIdx.x - nn;
+    if (narrow)
+        narrow_body<D, kNarrowStages, false, false>(a, a.units, idx % a.mixed_narrow_bins, idx / a.mixed_narrow_bins);
+    else
+        wide_body<D, 4, kWideStagesHalf, false, false>(a, a.wide_units, idx, a.mixed_wide_wgs);
+}
+
+
 // ---------------------------------------------------------------------------
 // Combine: merge the partial states of a tile that was cut into KV ranges.
 // States with different running maxima are rescaled to the common maximum and
@@ -1570,6 +1615,12 @@ int kernels_init(int device, std::string& err) {
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void*)rpa_wide_kernel<256, 4, kWideStagesHalf, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<256>(kWideStagesHalf));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_mixed_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)std::max(narrow_lds_bytes<128>(4), wide_lds_bytes<128>(kWideStagesHalf)));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_mixed_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)std::max(narrow_lds_bytes<64>(4), wide_lds_bytes<64>(kWideStagesHalf)));
     if (e != hipSuccess) {
         err = std::string("hipFuncSetAttribute: ") + hipGetErrorString(e);
         return (int)e;
@@ -1676,6 +1727,33 @@ int launch_wide(const KernelArgs& a_in, int num_units, void* stream, void** ev) 
             RPA_LAUNCH((rpa_wide_kernel<64, 8, kWideStages, false>), grid, dim3(512), wide_lds_bytes<64>(kWideStages), st,
                        ev, a);
     }
+    return (int)hipGetLastError();
+}
+
+// Narrow and wide workgroups in one launch: a.units / a.bins are the narrow list,
+// a.wide_units the wide one.  Built for the bf16 cache (separate pools) at head_dim
+// 64 and 128, four waves per narrow workgroup and 128-row wide tiles.
+bool mixed_launch_built(const KernelArgs& a, int narrow_waves) {
+    const bool half = (a.hg << a.wide_tq_log2) == 128;
+    return !a.kv_fp8 && !a.kv_merged && a.head_dim <= 128 && half && narrow_waves == 4;
+}
+
+int launch_mixed(const KernelArgs& a_in, int num_bins, int num_wide_units, void* stream, void** ev) {
+    KernelArgs a = a_in;
+    if (!mixed_launch_built(a, 4) || a.num_kv_heads % 4 != 0 || num_bins <= 0 || num_wide_units <= 0)
+        return (int)hipErrorInvalidValue;
+    a.mixed_narrow_bins = num_bins;
+    a.mixed_narrow_wgs = num_bins * (a.num_kv_heads / 4);
+    a.mixed_wide_wgs = num_wide_units * a.num_kv_heads;
+    a.num_wide_items = a.mixed_wide_wgs;
+    const dim3 grid((unsigned)(a.mixed_narrow_wgs + a.mixed_wide_wgs));
+    hipStream_t st = (hipStream_t)stream;
+    if (a.head_dim == 128)
+        RPA_LAUNCH(rpa_mixed_kernel<128>, grid, dim3(256),
+                   std::max(narrow_lds_bytes<128>(4), wide_lds_bytes<128>(kWideStagesHalf)), st, ev, a);
+    else
+        RPA_LAUNCH(rpa_mixed_kernel<64>, grid, dim3(256),
+                   std::max(narrow_lds_bytes<64>(4), wide_lds_bytes<64>(kWideStagesHalf)), st, ev, a);
     return (int)hipGetLastError();
 }
 

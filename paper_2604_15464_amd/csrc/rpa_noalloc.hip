@@ -120,11 +120,24 @@ extern "C" int rpa_update_and_attend_noalloc(const rpa_shape* shape, int device,
 
     // Split partials that fit the array: one (m, l) pair and head_dim floats per row.
     const int64_t row_cap = (int64_t)(kPartialBytes / ((size_t)(shape->head_dim + 2) * sizeof(float)));
+    // One stream only.  A large mixed batch runs as one launch that holds both kinds
+    // of workgroup, where that kernel is built; else the wide kernel follows the
+    // narrow one and the plan is made for that.
     rpa_options opt{};
-    opt.mixed_overlap = 1; // one stream only: the wide kernel follows the narrow one
     Plan& plan = s->plan;
-    rc = build_plan(*shape, cu_q_lens, kv_lens, num_seqs, opt, s->num_cus, row_cap, plan, msg);
-    if (rc != RPA_OK) return fail(rc, msg);
+    KernelArgs a{};
+    a.kv_merged = shape[0].kv_merged;
+    a.head_dim = shape->head_dim;
+    a.hg = shape->num_q_heads / shape->num_kv_heads;
+    bool one_launch = false;
+    for (int pass = 0; pass < 2; ++pass) {
+        rc = build_plan(*shape, cu_q_lens, kv_lens, num_seqs, opt, s->num_cus, row_cap, plan, msg);
+        if (rc != RPA_OK) return fail(rc, msg);
+        a.wide_tq_log2 = __builtin_ctz((unsigned)wide_q_tokens(a.hg, plan.stats.wide_rows));
+        one_launch = plan.stats.concurrent && mixed_launch_built(a, plan.stats.narrow_waves);
+        if (one_launch || !plan.stats.concurrent) break;
+        opt.mixed_overlap = 1;
+    }
     const size_t n_narrow = plan.narrow.size(), n_wide = plan.wide.size(), n_items = plan.items.size();
     if (n_narrow + n_wide == 0) return RPA_OK;
 
@@ -162,7 +175,6 @@ extern "C" int rpa_update_and_attend_noalloc(const rpa_shape* shape, int device,
         if (e != hipSuccess) return hip_fail("work list launch", e);
     }
 
-    KernelArgs a{};
     a.q = (const uint16_t*)q;
     a.k_new = (const uint16_t*)k_new;
     a.v_new = (const uint16_t*)v_new;
@@ -174,25 +186,28 @@ extern "C" int rpa_update_and_attend_noalloc(const rpa_shape* shape, int device,
     a.part_o = a.part_ml + (size_t)row_cap * 2;
     a.num_q_heads = shape->num_q_heads;
     a.num_kv_heads = shape->num_kv_heads;
-    a.hg = shape->num_q_heads / shape->num_kv_heads;
-    a.head_dim = shape->head_dim;
     a.page_size_log2 = __builtin_ctz((unsigned)shape->page_size);
     a.max_pages_per_seq = shape->max_pages_per_seq;
     a.num_pages = shape->num_pages;
-    a.wide_tq_log2 = __builtin_ctz((unsigned)wide_q_tokens(a.hg, plan.stats.wide_rows));
     a.scale_log2 = sm_scale * 1.4426950408889634f;
     a.causal = shape->non_causal ? 0 : 1;
     a.kv_fp8 = 0;
     a.out_scale = 1.f;
-    a.kv_merged = shape[0].kv_merged;
     a.wide_persist_grid = plan.wide_persistent_pays() ? s->num_cus : 0;
     a.units = (const rpa_work_unit*)base;
     a.bins = (const int32_t*)(base + bins_off);
-    int hrc = launch_narrow(a, (int)n_bins, plan.stats.narrow_waves, stream, nullptr);
-    if (hrc != 0) return hip_fail("narrow kernel launch", (hipError_t)hrc);
-    a.units = (const rpa_work_unit*)base + n_narrow;
-    hrc = launch_wide(a, (int)n_wide, stream, nullptr);
-    if (hrc != 0) return hip_fail("wide kernel launch", (hipError_t)hrc);
+    int hrc;
+    if (one_launch) {
+        a.wide_units = (const rpa_work_unit*)base + n_narrow;
+        hrc = launch_mixed(a, (int)n_bins, (int)n_wide, stream, nullptr);
+        if (hrc != 0) return hip_fail("mixed kernel launch", (hipError_t)hrc);
+    } else {
+        hrc = launch_narrow(a, (int)n_bins, plan.stats.narrow_waves, stream, nullptr);
+        if (hrc != 0) return hip_fail("narrow kernel launch", (hipError_t)hrc);
+        a.units = (const rpa_work_unit*)base + n_narrow;
+        hrc = launch_wide(a, (int)n_wide, stream, nullptr);
+        if (hrc != 0) return hip_fail("wide kernel launch", (hipError_t)hrc);
+    }
     int max_rows = 0;
     for (const rpa_combine_item& it : plan.items) max_rows = max_rows > it.rows ? max_rows : it.rows;
     hrc = launch_combine((const rpa_combine_item*)(base + items_off), (int)n_items, a.part_o, a.part_ml,

@@ -138,7 +138,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         opt.wide_kv_chunk < 0 || opt.units_per_cu < 0 || opt.narrow_waves < 0 || opt.narrow_waves > kMaxWaves ||
         (opt.narrow_waves > 0 && s.num_kv_heads % opt.narrow_waves != 0) ||
         (opt.wide_rows != 0 && opt.wide_rows != 128 && opt.wide_rows != 256) || opt.wide_order < 0 ||
-        opt.wide_order > 2 || opt.mixed_overlap < 0 || opt.mixed_overlap > 2 || opt.stream_ordered_upload < 0 ||
+        opt.wide_order > 2 || opt.mixed_overlap < 0 || opt.mixed_overlap > 3 || opt.stream_ordered_upload < 0 ||
         opt.stream_ordered_upload > 1 || opt.wide_persistent < 0 || opt.wide_persistent > 1 ||
         !options_fit_shape(s, opt)) {
         err = "bad options";
@@ -246,7 +246,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         const double narrow_bytes =
             (double)total_tiles * kNarrowKvTile * s.num_kv_heads * s.head_dim * 2.0 * kv_elem_bytes;
         const double wide_flops = (double)work_wide * wide_q_tokens(hg, wide_rows) * 4.0 * s.num_q_heads * s.head_dim;
-        concurrent = opt.mixed_overlap == 2 || (narrow_bytes >= 128e6 && wide_flops >= 2e10);
+        concurrent = opt.mixed_overlap >= 2 || (narrow_bytes >= 128e6 && wide_flops >= 2e10);
     }
 
     const int waves = opt.narrow_waves > 0 ? opt.narrow_waves : narrow_waves(s.num_kv_heads, s.head_dim);

@@ -26,7 +26,7 @@ import os
 import sqlite3
 import sys
 
-KERNELS = ("rpa_narrow_kernel", "rpa_wide_kernel", "rpa_combine_kernel", "rpa_copy_kernel")
+KERNELS = ("rpa_narrow_kernel", "rpa_wide_kernel", "rpa_mixed_kernel", "rpa_combine_kernel", "rpa_copy_kernel")
 
 
 def short_name(name: str) -> str:
@@ -125,7 +125,9 @@ def traffic(fetch_dir: str, write_dir: str, out_json: str, out_txt: str, command
     if "prefill" in bench:
         blocks.append((bench["prefill"]["config"], ("rpa_wide_kernel",)))
     if "mixed" in bench:
-        blocks.append((bench["mixed"]["config"], ("rpa_narrow_kernel", "rpa_wide_kernel", "rpa_combine_kernel")))
+        # one launch with both kinds of workgroup, or (other shapes) the two kernels
+        blocks.append((bench["mixed"]["config"], ("rpa_mixed_kernel", "rpa_narrow_kernel", "rpa_wide_kernel",
+                                                  "rpa_combine_kernel")))
     if "long_decode" in bench:
         blocks.append((bench["long_decode"]["config"], ("rpa_narrow_kernel",)))
     used = collections.Counter(k for _, ks in blocks for k in ks if k != "rpa_combine_kernel")

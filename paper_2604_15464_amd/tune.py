@@ -42,7 +42,7 @@ def candidates(regime: str, hkv: int, head_dim: int, kv_fp8: bool):
         for r, order, chunk in itertools.product(rows, (1, 2), (0, 1024)):
             out.append({"wide_rows": r, "wide_order": order, "wide_kv_chunk": chunk})
     else:
-        for r, ov in itertools.product(rows, (1, 2)):
+        for r, ov in itertools.product(rows, (1, 2, 3)):
             out.append({"wide_rows": r, "mixed_overlap": ov})
         for w in waves:
             out.append({"narrow_waves": w, "mixed_overlap": 2})

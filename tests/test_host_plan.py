@@ -133,8 +133,10 @@ def test_mixed_batches_run_side_by_side_when_large_enough():
     for idx in (2, 3):                                # one kind of work only: nothing to overlap
         wl = W.config(idx, scale=0.25)
         assert rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, mixed_overlap=2)[2]["concurrent"] == 0
+    # 3 = side by side as two kernels on two streams, whatever the sizes
+    assert rpa.plan_host(shape_of(c1), c1.cu_q_lens, c1.kv_lens, mixed_overlap=3)[2]["concurrent"] == 1
     with pytest.raises(rpa.RpaError):
-        rpa.plan_host(shape_of(c1), c1.cu_q_lens, c1.kv_lens, mixed_overlap=3)
+        rpa.plan_host(shape_of(c1), c1.cu_q_lens, c1.kv_lens, mixed_overlap=4)
 
 
 def test_plan_with_8bit_cache():

@@ -18,7 +18,7 @@ MAX_ABS = 1.5e-2
 MEAN_ABS = 2e-3
 
 
-def _run_both(wl):
+def _run_both(wl, seqs=None):
     dev = torch.device("cuda:0")
     x = W.materialize(wl, dev, poison=True)
     host = {k: W.bits(v) for k, v in x.items()}
@@ -43,15 +43,18 @@ def _run_both(wl):
     torch.cuda.synchronize()
     ref, kp_ref, vp_ref = O.update_and_attend(host["q"], host["k_new"], host["v_new"], host["k_pages"],
                                               host["v_pages"], wl.page_table, wl.cu_q_lens, wl.kv_lens,
-                                              wl.num_seqs, wl.sm_scale)
+                                              wl.num_seqs, wl.sm_scale, seqs=seqs)
     t = wl.num_tokens
+    rows = np.zeros(t, dtype=bool)      # the rows the oracle computed: all, or those of `seqs`
+    for r in (range(wl.num_seqs) if seqs is None else seqs):
+        rows[wl.cu_q_lens[r]:wl.cu_q_lens[r + 1]] = True
     assert np.array_equal(W.bits(kp2), W.bits(kp1)) and np.array_equal(W.bits(vp2), W.bits(vp1))
     assert np.array_equal(W.bits(kp2), kp_ref) and np.array_equal(W.bits(vp2), vp_ref)
     a = out1[:t].to("cpu").to(torch.float64).numpy()
     b = out2[:t].to("cpu").to(torch.float64).numpy()
     assert np.isfinite(b).all()
     for got in (a, b):
-        err = np.abs(got - ref[:t])
+        err = np.abs(got - ref[:t])[rows]
         assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, (err.max(), err.mean())
     d = np.abs(a - b)
     assert d.max() <= MAX_ABS and d.mean() <= MEAN_ABS
@@ -68,6 +71,17 @@ def test_noalloc_matches_context_entry_point_twice_in_a_row():
     _run_both(small)
     # and a decode batch with other head counts, page size and head_dim
     _run_both(W.ragged(4101, num_seqs=9, hq=8, hkv=2, d=256, ps=64, max_q=1, max_ctx=2500, p_decode=1.0, p_empty=0.0))
+
+
+def test_noalloc_large_mixed_batch():
+    """128 decode sequences and 4 chunks of 512 tokens: large enough that both entry
+    points put narrow and wide workgroups into one launch.  The oracle attends a sample
+    of the sequences (both kinds); the two entry points are compared on every row."""
+    wl = W.config(4)
+    long = [int(r) for r in np.flatnonzero(wl.q_lens > 1)]
+    short = [int(r) for r in np.flatnonzero(wl.q_lens == 1)]
+    info = _run_both(wl, seqs=long[:2] + short[:3] + short[-2:])
+    assert info["concurrent"] == 2
 
 
 def test_noalloc_rejects_what_does_not_fit():
