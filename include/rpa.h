@@ -186,9 +186,10 @@ typedef struct {
                               stream; 2 = always side by side; 3 = always side by side
                               and as two kernels on two streams.  Side by side means
                               one launch that holds narrow and wide workgroups where
-                              that kernel is built (bf16 cache in separate pools,
-                              head_dim 64 / 128, four waves per narrow workgroup,
-                              128-row wide tiles), else the two-stream form          */
+                              that kernel is built (K and V in separate pools,
+                              head_dim 64 / 128, with the 8-bit cache 128 only;
+                              1, 2 or 4 waves per narrow workgroup; 128-row wide
+                              tiles), else the two-stream form                       */
     int32_t stream_ordered_upload; /* 0 = the host waits (a few microseconds) until the
                               call's work list has reached the device before it
                               enqueues the kernels; 1 = the host never waits: the

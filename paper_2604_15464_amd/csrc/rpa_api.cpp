@@ -484,7 +484,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
                             mixed_launch_built(a, plan.stats.narrow_waves);
     if (one_launch) {
         a.wide_units = dev_units + n_narrow;
-        hrc = launch_mixed(a, (int)n_bins, (int)n_wide, stream, pe ? (void**)&pe->ev[0] : nullptr);
+        hrc = launch_mixed(a, (int)n_bins, plan.stats.narrow_waves, (int)n_wide, stream, pe ? (void**)&pe->ev[0] : nullptr);
         if (hrc != 0) return hip_fail(c, "mixed kernel launch", (hipError_t)hrc);
         plan.stats.concurrent = 2;
     }

@@ -105,7 +105,8 @@ struct KernelArgs {
     int32_t kv_merged; // 1: k_pages is one pool [num_pages, page_size, Hkv, 2, D] with K and V side by side
     int32_t num_wide_items;     // wide kernel: (unit, KV head) pairs of the launch
     const rpa_work_unit* wide_units; // mixed-batch kernel: the wide unit list (units / bins are the narrow one)
-    int32_t mixed_narrow_bins;       // ... its narrow bins, narrow workgroups (bins x KV-head groups) and wide workgroups
+    int32_t mixed_narrow_bins;       // ... its narrow bins, waves per narrow task (one bin, that many KV heads),
+    int32_t mixed_narrow_waves;      //     narrow workgroups (four waves: 4 / waves tasks each) and wide workgroups
     int32_t mixed_narrow_wgs;
     int32_t mixed_wide_wgs;
     int32_t wide_persist_grid;  // > 0: workgroups of the persistent wide kernel (one per CU), which walk the items
@@ -116,7 +117,7 @@ struct KernelArgs {
 // (attached to the dispatch, no extra queue packets).
 int launch_narrow(const KernelArgs& a, int num_bins, int waves, void* stream, void** ev);
 bool mixed_launch_built(const KernelArgs& a, int narrow_waves);
-int launch_mixed(const KernelArgs& a, int num_bins, int num_wide_units, void* stream, void** ev);
+int launch_mixed(const KernelArgs& a, int num_bins, int narrow_waves, int num_wide_units, void* stream, void** ev);
 int launch_wide(const KernelArgs& a, int num_units, void* stream, void** ev);
 int launch_combine(const rpa_combine_item* items, int num_items, const float* part_o,
                    const float* part_ml, uint16_t* out, int num_q_heads, int head_dim, int max_rows,

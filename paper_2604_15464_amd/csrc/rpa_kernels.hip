@@ -178,10 +178,11 @@ __device__ __forceinline__ int clamp_page(int page, int num_pages) {
 // wave-wide load brings two tokens' K|V pairs, and K and V rows alternate in the
 // LDS stage.  a.k_pages is the pool, a.v_pages is not used.
 // (The body is a device function so that the mixed-batch kernel below can run it
-// in some of its workgroups: `units` is the narrow unit list, `bin` and `row` what
-// blockIdx.x and blockIdx.y are in a launch of its own.)
+// in some of its workgroups: `units` is the narrow unit list, `bin` the bin and `g`
+// the KV head of the calling wave, both wave-uniform; the waves of a workgroup
+// need not share a bin.)
 template <int D, int NST, bool KV8, bool MERGED>
-__device__ __forceinline__ void narrow_body(const KernelArgs& a, const rpa_work_unit* units, int bin, int row) {
+__device__ __forceinline__ void narrow_body(const KernelArgs& a, const rpa_work_unit* units, int bin, int g) {
     static_assert(!MERGED || (!KV8 && D == 128), "the merged layout is built for bf16 at head_dim 128");
     constexpr int ROWB = D * (KV8 ? 1 : 2);     // bytes of one token row of one head
     constexpr int NC = ROWB / 16;               // 16-byte chunks per row
@@ -203,8 +204,6 @@ __device__ __forceinline__ void narrow_body(const KernelArgs& a, const rpa_work_
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int nwaves = blockDim.x >> 6;
-    const int g = row * nwaves + wave; // KV head of this wave
     const int n = lane & 15;                  // query row of this lane (MFMA column)
     const int quad = lane >> 4;
 
@@ -639,7 +638,8 @@ __device__ __forceinline__ void narrow_body(const KernelArgs& a, const rpa_work_
 
 template <int D, int NST, bool KV8, bool MERGED = false>
 __global__ void __launch_bounds__(64 * (D > 128 ? 4 : kMaxWaves)) rpa_narrow_kernel(KernelArgs a) {
-    narrow_body<D, NST, KV8, MERGED>(a, a.units, (int)blockIdx.x, (int)blockIdx.y);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    narrow_body<D, NST, KV8, MERGED>(a, a.units, (int)blockIdx.x, (int)(blockIdx.y * (blockDim.x >> 6)) + wave);
 }
 
 
@@ -1418,32 +1418,40 @@ rpa_wide_kernel(KernelArgs a) {
 
 // ---------------------------------------------------------------------------
 // Mixed batches (Sec. 3.4, the "mixed" case of the paper's three): one launch
-// whose workgroups are narrow ones (four waves, one bin and one group of four KV
-// heads each) and wide ones of the 128-row shape (four waves), so that a CU holds
-// one of each: the narrow part is bound by HBM, the wide part by the matrix and
-// vector pipes.  As two kernels on two streams the same pairing costs an event
-// from the second stream back to the first and the wait for it, 15-20 us of idle
-// GPU per call.  The narrow workgroups come first in the grid: the dispatcher
-// spreads consecutive workgroups over the CUs before it doubles up, so each CU
-// gets one narrow workgroup, which streams for the whole kernel, and the wide
-// ones take the second slot of every CU in turn.  (Measured on 128 decode
-// sequences + 4 chunks of 512: 404 us; the two kinds alternating in groups of 8,
-// 16 or 32 ids: 440-460 us, since some CUs then hold two narrow workgroups;
-// wide first: 455 us; wide waves at a raised priority: 418 us; two streams:
-// 418 us.)  A wide item's KV head is item % Hkv, so with Hkv a multiple of 8
-// all items of a head still meet in one XCD's L2, whatever the offset.
+// whose workgroups are narrow ones (four waves) and wide ones of the 128-row
+// shape (four waves), so that a CU holds one of each: the narrow part is bound by
+// HBM, the wide part by the matrix and vector pipes.  As two kernels on two
+// streams the same pairing costs an event from the second stream back to the
+// first and the wait for it, 15-20 us of idle GPU per call.  The narrow
+// workgroups come first in the grid: the dispatcher spreads consecutive
+// workgroups over the CUs before it doubles up, so each CU gets one narrow
+// workgroup, which streams for the whole kernel, and the wide ones take the
+// second slot of every CU in turn.  (Measured on 128 decode sequences + 4 chunks
+// of 512: 404 us; the two kinds alternating in groups of 8, 16 or 32 ids:
+// 440-460 us, since some CUs then hold two narrow workgroups; wide first: 455 us;
+// wide waves at a raised priority: 418 us; two streams: 418 us.)
+// A narrow workgroup is 4 / w tasks of w waves, a task being what a workgroup of
+// the narrow kernel's own launch is: one bin and w KV heads, w = 1, 2 or 4 waves
+// as the plan chose (the waves never synchronise with each other, so tasks can
+// share a workgroup).  A wide item's KV head is item % Hkv, so with Hkv a
+// multiple of 8 all items of a head still meet in one XCD's L2, whatever the
+// offset.
 // ---------------------------------------------------------------------------
-template <int D>
+template <int D, bool KV8>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) rpa_mixed_kernel(KernelArgs a) {
     const int nn = a.mixed_narrow_wgs;
-    const bool narrow = (int)blockIdx.x < nn;
-    const int idx = narrow ? (int)blockIdx.x : (int)blockIdx.x - nn;
-    if (narrow)
-        narrow_body<D, kNarrowStages, false, false>(a, a.units, idx % a.mixed_narrow_bins, idx / a.mixed_narrow_bins);
-    else
-        wide_body<D, 4, kWideStagesHalf, false, false>(a, a.wide_units, idx, a.mixed_wide_wgs);
+    if ((int)blockIdx.x < nn) {
+        const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+        const int w = a.mixed_narrow_waves;
+        const int task = (int)blockIdx.x * (4 / w) + wave / w;
+        const int bins = a.mixed_narrow_bins;
+        if (task >= bins * (a.num_kv_heads / w)) return; // the last workgroup may be partly empty
+        narrow_body<D, KV8 ? 2 * kNarrowStages : kNarrowStages, KV8, false>(a, a.units, task % bins,
+                                                                            (task / bins) * w + wave % w);
+    } else {
+        wide_body<D, 4, kWideStagesHalf, KV8, false>(a, a.wide_units, (int)blockIdx.x - nn, a.mixed_wide_wgs);
+    }
 }
-
 
 // ---------------------------------------------------------------------------
 // Combine: merge the partial states of a tile that was cut into KV ranges.
@@ -1616,11 +1624,14 @@ int kernels_init(int device, std::string& err) {
         e = hipFuncSetAttribute((const void*)rpa_wide_kernel<256, 4, kWideStagesHalf, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds_bytes<256>(kWideStagesHalf));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_mixed_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        e = hipFuncSetAttribute((const void*)rpa_mixed_kernel<128, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)std::max(narrow_lds_bytes<128>(4), wide_lds_bytes<128>(kWideStagesHalf)));
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)rpa_mixed_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        e = hipFuncSetAttribute((const void*)rpa_mixed_kernel<64, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)std::max(narrow_lds_bytes<64>(4), wide_lds_bytes<64>(kWideStagesHalf)));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)rpa_mixed_kernel<128, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)std::max(narrow_lds_bytes<128>(4), wide_lds_bytes_kv8(kWideStagesHalf, 4)));
     if (e != hipSuccess) {
         err = std::string("hipFuncSetAttribute: ") + hipGetErrorString(e);
         return (int)e;
@@ -1735,24 +1746,32 @@ int launch_wide(const KernelArgs& a_in, int num_units, void* stream, void** ev) 
 // 64 and 128, four waves per narrow workgroup and 128-row wide tiles.
 bool mixed_launch_built(const KernelArgs& a, int narrow_waves) {
     const bool half = (a.hg << a.wide_tq_log2) == 128;
-    return !a.kv_fp8 && !a.kv_merged && a.head_dim <= 128 && half && narrow_waves == 4;
+    const bool waves_ok = narrow_waves == 1 || narrow_waves == 2 || narrow_waves == 4;
+    if (a.kv_merged || !half || !waves_ok) return false;
+    return a.kv_fp8 ? a.head_dim == 128 : a.head_dim <= 128;
 }
 
-int launch_mixed(const KernelArgs& a_in, int num_bins, int num_wide_units, void* stream, void** ev) {
+int launch_mixed(const KernelArgs& a_in, int num_bins, int narrow_waves, int num_wide_units, void* stream, void** ev) {
     KernelArgs a = a_in;
-    if (!mixed_launch_built(a, 4) || a.num_kv_heads % 4 != 0 || num_bins <= 0 || num_wide_units <= 0)
+    if (!mixed_launch_built(a, narrow_waves) || a.num_kv_heads % narrow_waves != 0 || num_bins <= 0 ||
+        num_wide_units <= 0)
         return (int)hipErrorInvalidValue;
+    const int tasks = num_bins * (a.num_kv_heads / narrow_waves), per_wg = 4 / narrow_waves;
     a.mixed_narrow_bins = num_bins;
-    a.mixed_narrow_wgs = num_bins * (a.num_kv_heads / 4);
+    a.mixed_narrow_waves = narrow_waves;
+    a.mixed_narrow_wgs = (tasks + per_wg - 1) / per_wg;
     a.mixed_wide_wgs = num_wide_units * a.num_kv_heads;
     a.num_wide_items = a.mixed_wide_wgs;
     const dim3 grid((unsigned)(a.mixed_narrow_wgs + a.mixed_wide_wgs));
     hipStream_t st = (hipStream_t)stream;
-    if (a.head_dim == 128)
-        RPA_LAUNCH(rpa_mixed_kernel<128>, grid, dim3(256),
+    if (a.kv_fp8)
+        RPA_LAUNCH((rpa_mixed_kernel<128, true>), grid, dim3(256),
+                   std::max(narrow_lds_bytes<128>(4), wide_lds_bytes_kv8(kWideStagesHalf, 4)), st, ev, a);
+    else if (a.head_dim == 128)
+        RPA_LAUNCH((rpa_mixed_kernel<128, false>), grid, dim3(256),
                    std::max(narrow_lds_bytes<128>(4), wide_lds_bytes<128>(kWideStagesHalf)), st, ev, a);
     else
-        RPA_LAUNCH(rpa_mixed_kernel<64>, grid, dim3(256),
+        RPA_LAUNCH((rpa_mixed_kernel<64, false>), grid, dim3(256),
                    std::max(narrow_lds_bytes<64>(4), wide_lds_bytes<64>(kWideStagesHalf)), st, ev, a);
     return (int)hipGetLastError();
 }

@@ -199,7 +199,7 @@ extern "C" int rpa_update_and_attend_noalloc(const rpa_shape* shape, int device,
     int hrc;
     if (one_launch) {
         a.wide_units = (const rpa_work_unit*)base + n_narrow;
-        hrc = launch_mixed(a, (int)n_bins, (int)n_wide, stream, nullptr);
+        hrc = launch_mixed(a, (int)n_bins, plan.stats.narrow_waves, (int)n_wide, stream, nullptr);
         if (hrc != 0) return hip_fail("mixed kernel launch", (hipError_t)hrc);
     } else {
         hrc = launch_narrow(a, (int)n_bins, plan.stats.narrow_waves, stream, nullptr);

@@ -343,7 +343,7 @@ def test_chunked_prefill_carries_cache_across_calls():
 # Mixed batches: the wide kernel enqueued beside the narrow one (fork / join on a
 # stream of the context) or after it; same results either way.
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("shape", [(4, 2, 64), (32, 8, 128), (16, 2, 128), (8, 2, 256)])
+@pytest.mark.parametrize("shape", [(4, 2, 64), (32, 8, 128), (16, 2, 128), (8, 1, 128), (8, 2, 256)])
 @pytest.mark.parametrize("wide_rows", [128, 256])
 def test_mixed_batch_kernels_side_by_side(shape, wide_rows):
     hq, hkv, d = shape
@@ -356,10 +356,9 @@ def test_mixed_batch_kernels_side_by_side(shape, wide_rows):
         res = run_case(wl, kv_chunk=chunk, wide_kv_chunk=chunk, wide_rows=wide_rows, mixed_overlap=overlap, calls=6)
         check(wl, res)
         assert res["info"]["variant"] == rpa.VARIANT_MIXED
-        # 2: one launch holds both kernels' workgroups where that kernel is built (16-bit
-        # cache, head_dim up to 128, 128-row wide tiles, narrow workgroups of four waves),
-        # else two streams like 3
-        one_launch = overlap == 2 and d <= 128 and wide_rows == 128 and hkv % 4 == 0
+        # 2: one launch holds both kernels' workgroups where that kernel is built
+        # (head_dim up to 128, 128-row wide tiles), else two streams like 3
+        one_launch = overlap == 2 and d <= 128 and wide_rows == 128
         assert res["info"]["concurrent"] == (2 if one_launch else 1 if overlap >= 2 else 0)
 
 
@@ -580,11 +579,12 @@ def test_fp8_cache_wide_kernel(wide_rows, hq, hkv):
 
 def test_fp8_cache_mixed_batch_side_by_side():
     wl = W.ragged(1950, num_seqs=24, hq=32, hkv=8, d=128, ps=16, max_q=200, max_ctx=700, p_decode=0.5)
-    for overlap in (2, 1):
-        res = run_case(wl, kv_scales=KV_SCALES, mixed_overlap=overlap, calls=5)
+    for overlap, rows in ((2, 0), (2, 128), (3, 128), (1, 0)):
+        res = run_case(wl, kv_scales=KV_SCALES, mixed_overlap=overlap, wide_rows=rows, calls=5)
         check(wl, res)
-        # the 8-bit cache has no one-launch kernel: two streams
-        assert res["info"]["concurrent"] == (1 if overlap == 2 else 0)
+        # side by side: one launch with 128-row wide tiles, two streams with 256-row ones
+        side = 2 if res["info"]["wide_rows"] == 128 else 1
+        assert res["info"]["concurrent"] == (side if overlap == 2 else 1 if overlap == 3 else 0)
 
 
 def test_fp8_cache_full_size_prefill_and_mixed():
@@ -598,7 +598,8 @@ def test_fp8_cache_full_size_prefill_and_mixed():
     sample = chunks[:2] + dec[[0, -1]].tolist()
     res = run_case(wl, kv_scales=KV_SCALES, seqs=sample)
     check(wl, res, seqs=sample)
-    assert res["info"]["variant"] == rpa.VARIANT_MIXED and res["info"]["concurrent"] == 1
+    assert res["info"]["variant"] == rpa.VARIANT_MIXED
+    assert res["info"]["concurrent"] == (2 if res["info"]["wide_rows"] == 128 else 1)
 
 
 @pytest.mark.parametrize("scales", [(1.0, 1.0), (0.37, 0.011), (1.0 / 1024, 2.0)])
