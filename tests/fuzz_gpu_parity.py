@@ -5,8 +5,8 @@
 Draws shapes, length mixes, launch knobs, cache types and input recipes at random,
 runs each batch through the C ABI and compares cache and outputs with the CPU oracle
 exactly as tests/test_gpu_parity.py does.  Every case is printed before it runs, so
-a failure names its seed.  (Two runs of 420 s: 3200 cases each, all equal to the
-oracle within the tolerance.)"""
+a failure names its seed.  (Runs of 400-420 s: about 3000 cases each, all equal to
+the oracle within the tolerance.)"""
 import os
 import random
 import sys
@@ -28,7 +28,7 @@ while time.time() < t_end:
               wide_kv_chunk=rng.choice([0, 0, 64, 192]), pad_tokens=rng.choice([0, 3]), pad_seqs=rng.choice([0, 2]),
               narrow_waves=rng.choice([0, 0, 1, 2]) if hkv % 2 == 0 else 0, units_per_cu=rng.choice([0, 2]),
               wide_rows=rng.choice([0, 128, 256]) if d <= 128 else 0, causal=rng.random() < 0.8,
-              mixed_overlap=rng.choice([0, 1, 2]), calls=rng.choice([1, 2]), wide_persistent=rng.choice([0, 0, 1]))
+              mixed_overlap=rng.choice([0, 1, 2, 2, 2, 3]), calls=rng.choice([1, 2]), wide_persistent=rng.choice([0, 0, 1]))
     if rng.random() < 0.3:
         kw["kv_scales"] = rng.choice([(1 / 64, 1 / 32), (0.05, 0.02), (1.0, 1.0)])
     if rng.random() < 0.5:
