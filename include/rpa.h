@@ -21,11 +21,12 @@
  *     and the cache are then undefined.  rpa_last_error() gives a message.
  *   - The library allocates only its own workspace, in rpa_create(); the call
  *     path performs no allocation, creates no stream and synchronises neither
- *     the device nor the caller's stream.  The host does wait, a few
- *     microseconds, for the call's own work list (tens of KB) to reach the
- *     device on a stream of the context (rpa_options.stream_ordered_upload
- *     replaces that wait by an event the caller's stream waits for), and, when
- *     it has run eight calls ahead of the GPU, for the oldest of them to finish.
+ *     the device nor the caller's stream.  For a batch that is not small the
+ *     host does wait, a few microseconds, for the call's own work list (tens of
+ *     KB) to reach the device on a stream of the context
+ *     (rpa_options.stream_ordered_upload selects other forms: an event the
+ *     caller's stream waits for, or no copy at all), and, when it has run eight
+ *     calls ahead of the GPU, for the oldest of them to finish.
  *   - A context serves one stream at a time: calls on one context must be
  *     issued in stream order (the work lists it uploads are reused); a caller
  *     that moves a context between streams orders those streams itself.
@@ -190,12 +191,18 @@ typedef struct {
                               head_dim 64 / 128, with the 8-bit cache 128 only;
                               1, 2 or 4 waves per narrow workgroup; 128-row wide
                               tiles), else the two-stream form                       */
-    int32_t stream_ordered_upload; /* 0 = the host waits (a few microseconds) until the
-                              call's work list has reached the device before it
-                              enqueues the kernels; 1 = the host never waits: the
-                              caller's stream is made to wait for the copy with an
-                              event (one more packet on the stream, about 5 us of
-                              GPU idle time per call)                                  */
+    int32_t stream_ordered_upload; /* how the call's work list reaches the kernels:
+                              3 = it is copied to device memory on a stream of the
+                              context and the host waits (a few microseconds) for
+                              that copy before it enqueues the kernels; 1 = copied,
+                              and the host never waits: the caller's stream is made
+                              to wait for the copy with an event (one more packet
+                              on the stream, about 5 us of GPU idle time per call);
+                              2 = not copied: the kernels read it from the pinned
+                              host memory it was written to (nothing to wait for;
+                              1-3 us more kernel time on a large batch); 0 = 2 for
+                              a call estimated to keep the GPU busy for less than
+                              30 us, which latency bounds, else 3                   */
     int32_t wide_persistent; /* 256-row wide tiles at head_dim 64 / 128 with a bf16 cache:
                               0 = when the items are short (under 64 K/V tiles each
                               on average) one persistent workgroup per CU walks the

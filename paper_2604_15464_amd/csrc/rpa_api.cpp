@@ -16,6 +16,7 @@ using namespace rpa;
 namespace {
 
 constexpr int kRing = 8;  // staging slots: the host may run this many calls ahead of the GPU
+constexpr double kInPlaceListBelowUs = 30.0; // calls estimated shorter than this read their work list from host memory
 constexpr int kGroup = 4; // calls that share one completion event (an event record is a stream
                           // packet of its own and costs the GPU about 5 us of idle time)
 
@@ -203,7 +204,7 @@ extern "C" int rpa_set_options(rpa_ctx* c, const rpa_options* opt) {
         o.units_per_cu < 0 || o.narrow_waves < 0 || o.narrow_waves > kMaxWaves ||
         (o.narrow_waves > 0 && c->shape.num_kv_heads % o.narrow_waves != 0) ||
         (o.wide_rows != 0 && o.wide_rows != 128 && o.wide_rows != 256) || o.wide_order < 0 || o.wide_order > 2 ||
-        o.mixed_overlap < 0 || o.mixed_overlap > 3 || o.stream_ordered_upload < 0 || o.stream_ordered_upload > 1 ||
+        o.mixed_overlap < 0 || o.mixed_overlap > 3 || o.stream_ordered_upload < 0 || o.stream_ordered_upload > 3 ||
         o.wide_persistent < 0 || o.wide_persistent > 1 || !options_fit_shape(c->shape, o))
         return fail(c, RPA_ERR_INVALID_ARG, "rpa_set_options: bad value");
 #ifdef RPA_ABLATE
@@ -409,22 +410,38 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     if (n_wide) std::memcpy(h + n_narrow * sizeof(rpa_work_unit), plan.wide.data(), n_wide * sizeof(rpa_work_unit));
     if (n_items) std::memcpy(h + items_off, plan.items.data(), n_items * sizeof(rpa_combine_item));
     std::memcpy(h + bins_off, plan.bins.data(), plan.bins.size() * sizeof(int32_t));
-    e = hipMemcpyAsync(slot.dev, h, total_bytes, hipMemcpyHostToDevice, c->upload);
-    if (e != hipSuccess) return hip_fail(c, "hipMemcpyAsync", e);
-    // By default the host waits for its own small copy (tens of KB on the library's
-    // stream) instead of making the caller's stream wait for an event: a wait packet
-    // costs the GPU about 5 us of idle time per call, this costs the host a few us
-    // while the GPU still works on the previous call.  The caller's stream is not
-    // synchronised.  With stream_ordered_upload the host never waits: the caller's
-    // stream is ordered after the copy by an event.
-    if (opt_used.stream_ordered_upload) {
-        e = hipEventRecord(slot.uploaded, c->upload);
-        if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
-        e = hipStreamWaitEvent(st, slot.uploaded, 0);
-        if (e != hipSuccess) return hip_fail(c, "hipStreamWaitEvent", e);
+    // How the list reaches the kernels.  A short call is bound by latency: the copy,
+    // the host's wait for it and the launch come one after the other while the GPU
+    // idles, so the kernels read the list where the host wrote it (pinned,
+    // device-visible host memory; a record is read once per unit, by scalar loads
+    // issued ahead of their use): 30 -> 20 us per call on a batch of four short
+    // sequences, 27 -> 18 us on one 512-token prefill.  A long call hides the copy
+    // behind the previous call's kernels, and reading the records over PCIe would
+    // cost its kernels 1-3 us (a 45 us decode batch: +1-2 us): there the list is
+    // copied to device memory on the library's stream and the host waits for that
+    // small copy (a wait packet on the caller's stream instead costs the GPU about
+    // 5 us of idle time per call; stream_ordered_upload = 1 selects it: the host
+    // never waits).  The caller's stream is not synchronised in any form.
+    const int upload = opt_used.stream_ordered_upload;
+    const bool in_place = upload == 2 || (upload == 0 && plan.est_gpu_us < kInPlaceListBelowUs);
+    const char* list = (const char*)slot.dev;
+    if (in_place) {
+        void* mapped = nullptr;
+        e = hipHostGetDevicePointer(&mapped, slot.host, 0);
+        if (e != hipSuccess) return hip_fail(c, "hipHostGetDevicePointer", e);
+        list = (const char*)mapped;
     } else {
-        e = hipStreamSynchronize(c->upload);
-        if (e != hipSuccess) return hip_fail(c, "hipStreamSynchronize", e);
+        e = hipMemcpyAsync(slot.dev, h, total_bytes, hipMemcpyHostToDevice, c->upload);
+        if (e != hipSuccess) return hip_fail(c, "hipMemcpyAsync", e);
+        if (upload == 1) {
+            e = hipEventRecord(slot.uploaded, c->upload);
+            if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
+            e = hipStreamWaitEvent(st, slot.uploaded, 0);
+            if (e != hipSuccess) return hip_fail(c, "hipStreamWaitEvent", e);
+        } else {
+            e = hipStreamSynchronize(c->upload);
+            if (e != hipSuccess) return hip_fail(c, "hipStreamSynchronize", e);
+        }
     }
     (void)hipGetLastError(); // a stale error of an earlier HIP call is not a launch failure of this call
     slot.used = true;
@@ -469,11 +486,11 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
         a.out_scale = c->shape.v_scale;
     }
 
-    const rpa_work_unit* dev_units = (const rpa_work_unit*)slot.dev;
+    const rpa_work_unit* dev_units = (const rpa_work_unit*)list;
     ProfEvents* pe = (c->prof_on && c->prof_count < kProfCalls) ? &c->prof[c->prof_count] : nullptr;
     int hrc;
     a.units = dev_units;
-    a.bins = (const int32_t*)((const char*)slot.dev + bins_off);
+    a.bins = (const int32_t*)(list + bins_off);
     // Mixed batch: the wide kernel goes to the context's side stream, forked here
     // (after the caller's stream has the work list) and joined before the combine.
     // The two kernels touch disjoint query tokens, partial rows and cache slots.
@@ -511,7 +528,7 @@ extern "C" int rpa_update_and_attend(rpa_ctx* c, void* out, const void* q, const
     }
     int max_rows = 0;
     for (const rpa_combine_item& it : plan.items) max_rows = std::max(max_rows, (int)it.rows);
-    hrc = launch_combine((const rpa_combine_item*)((char*)slot.dev + items_off), (int)n_items, c->part_o, c->part_ml,
+    hrc = launch_combine((const rpa_combine_item*)(list + items_off), (int)n_items, c->part_o, c->part_ml,
                          (uint16_t*)out, a.num_q_heads, a.head_dim, max_rows, stream,
                          pe ? (void**)&pe->ev[4] : nullptr);
     if (hrc != 0) return hip_fail(c, "combine kernel launch", (hipError_t)hrc);

@@ -28,6 +28,7 @@ struct Plan {
     std::vector<rpa_work_unit> wide;   // launch order
     std::vector<rpa_combine_item> items;
     rpa_plan_stats stats{};
+    double est_gpu_us = 0; // rough GPU time of the call (narrow bytes at 6 TB/s + wide FLOPs at 1 PFLOP/s)
     // Wide launch form: persistent workgroups pay where items are short (the edges of
     // neighbouring items overlap: config 3, 16 tiles per item on average, -2..4 %);
     // where items are long the walk itself costs more than the edges it hides

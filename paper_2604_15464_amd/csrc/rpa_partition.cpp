@@ -139,7 +139,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         (opt.narrow_waves > 0 && s.num_kv_heads % opt.narrow_waves != 0) ||
         (opt.wide_rows != 0 && opt.wide_rows != 128 && opt.wide_rows != 256) || opt.wide_order < 0 ||
         opt.wide_order > 2 || opt.mixed_overlap < 0 || opt.mixed_overlap > 3 || opt.stream_ordered_upload < 0 ||
-        opt.stream_ordered_upload > 1 || opt.wide_persistent < 0 || opt.wide_persistent > 1 ||
+        opt.stream_ordered_upload > 3 || opt.wide_persistent < 0 || opt.wide_persistent > 1 ||
         !options_fit_shape(s, opt)) {
         err = "bad options";
         return RPA_ERR_INVALID_ARG;
@@ -241,13 +241,13 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     // extra stream packets (about 10 us): the narrow kernel is bound by HBM, the
     // wide one by the matrix and vector pipes, and a CU holds a workgroup of each.
     bool concurrent = false;
-    if (any_narrow && any_wide && opt.mixed_overlap != 1) {
-        const double kv_elem_bytes = s.kv_fp8 ? 1.0 : 2.0;
-        const double narrow_bytes =
-            (double)total_tiles * kNarrowKvTile * s.num_kv_heads * s.head_dim * 2.0 * kv_elem_bytes;
-        const double wide_flops = (double)work_wide * wide_q_tokens(hg, wide_rows) * 4.0 * s.num_q_heads * s.head_dim;
+    const double kv_elem_bytes = s.kv_fp8 ? 1.0 : 2.0;
+    const double narrow_bytes = (double)total_tiles * kNarrowKvTile * s.num_kv_heads * s.head_dim * 2.0 * kv_elem_bytes;
+    const double wide_flops = (double)work_wide * wide_q_tokens(hg, wide_rows) * 4.0 * s.num_q_heads * s.head_dim;
+    if (any_narrow && any_wide && opt.mixed_overlap != 1)
         concurrent = opt.mixed_overlap >= 2 || (narrow_bytes >= 128e6 && wide_flops >= 2e10);
-    }
+    // rough GPU time of the call: the narrow part at 6 TB/s, the wide part at 1 PFLOP/s
+    plan.est_gpu_us = narrow_bytes / 6e6 + wide_flops / 1e9;
 
     const int waves = opt.narrow_waves > 0 ? opt.narrow_waves : narrow_waves(s.num_kv_heads, s.head_dim);
     const int ny = s.num_kv_heads / waves;

@@ -28,7 +28,7 @@ while time.time() < t_end:
               wide_kv_chunk=rng.choice([0, 0, 64, 192]), pad_tokens=rng.choice([0, 3]), pad_seqs=rng.choice([0, 2]),
               narrow_waves=rng.choice([0, 0, 1, 2]) if hkv % 2 == 0 else 0, units_per_cu=rng.choice([0, 2]),
               wide_rows=rng.choice([0, 128, 256]) if d <= 128 else 0, causal=rng.random() < 0.8,
-              mixed_overlap=rng.choice([0, 1, 2, 2, 2, 3]), calls=rng.choice([1, 2]), wide_persistent=rng.choice([0, 0, 1]))
+              mixed_overlap=rng.choice([0, 1, 2, 2, 2, 3]), calls=rng.choice([1, 2]), wide_persistent=rng.choice([0, 0, 1]), upload=rng.choice([0, 0, 1, 2, 3]))
     if rng.random() < 0.3:
         kw["kv_scales"] = rng.choice([(1 / 64, 1 / 32), (0.05, 0.02), (1.0, 1.0)])
     if rng.random() < 0.5:

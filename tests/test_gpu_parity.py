@@ -34,7 +34,7 @@ def plan_cuts(wl, causal=True, kv_scales=None, **knobs):
 
 def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=True, pad_tokens=0,
              pad_seqs=0, seqs=None, calls=1, narrow_waves=0, units_per_cu=0, wide_rows=0, causal=True,
-             mixed_overlap=0, kv_scales=None, needles=None, wide_persistent=0):
+             mixed_overlap=0, kv_scales=None, needles=None, wide_persistent=0, upload=0):
     """Run the HIP path and the oracle on the workload; returns a dict of results.
     needles = (mode, seed): the discriminating inputs of workloads.materialize_needles
     (every output row is the V row of one chosen position) instead of N(0,1) q and K."""
@@ -59,7 +59,7 @@ def run_case(wl, variant=rpa.VARIANT_AUTO, kv_chunk=0, wide_kv_chunk=0, poison=T
                                                 causal=causal, kv_scales=kv_scales)
     ctx.set_options(variant=variant, kv_chunk=kv_chunk, wide_kv_chunk=wide_kv_chunk, narrow_waves=narrow_waves,
                     units_per_cu=units_per_cu, wide_rows=wide_rows, mixed_overlap=mixed_overlap,
-                    wide_persistent=wide_persistent)
+                    wide_persistent=wide_persistent, stream_ordered_upload=upload)
     out = torch.full_like(x["q"], float("nan"))
     sentinel = out.clone()
     for _ in range(calls):
@@ -360,6 +360,22 @@ def test_mixed_batch_kernels_side_by_side(shape, wide_rows):
         # (head_dim up to 128, 128-row wide tiles), else two streams like 3
         one_launch = overlap == 2 and d <= 128 and wide_rows == 128
         assert res["info"]["concurrent"] == (2 if one_launch else 1 if overlap >= 2 else 0)
+
+
+@pytest.mark.parametrize("upload", [0, 1, 2, 3])
+def test_work_list_upload_forms(upload):
+    """The four ways the work list reaches the kernels (copied and waited for by the
+    host, copied and waited for by the stream, read in place from pinned host memory,
+    and the default that picks by the size of the call), each on a small batch, on a
+    mixed batch with splits and on a decode batch, with more calls in a row than there
+    are staging slots."""
+    for wl, kw in ((W.config(1), {}),
+                   (W.ragged(1660, num_seqs=24, hq=32, hkv=8, d=128, ps=16, max_q=200, max_ctx=700, p_decode=0.5),
+                    dict(kv_chunk=64, wide_kv_chunk=64, mixed_overlap=2)),
+                   (W.ragged(1661, num_seqs=40, hq=8, hkv=2, d=256, ps=64, max_q=1, max_ctx=3000, p_decode=1.0,
+                             p_empty=0.0), {})):
+        res = run_case(wl, upload=upload, calls=11, **kw)
+        check(wl, res)
 
 
 def test_many_calls_on_alternating_streams():
