@@ -267,17 +267,24 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     int64_t per_bin = std::max<int64_t>(min_bin, ceil_div(total_tiles, want_bins));
     const int64_t max_piece = opt.kv_chunk > 0 ? ceil_div(opt.kv_chunk, kNarrowKvTile) : ((int64_t)1 << 40);
 
+    // Wide tiles are cut into KV ranges only when there is less than one workgroup
+    // per CU and the ranges stay long: a cut tile writes its rows as fp32 partials
+    // (twice the bytes of the output, per piece) and adds the combine pass, which
+    // costs more than an idle half of the chip gains on anything short (one
+    // 2048-token prefill: 73 us cut into 4, 54 us whole; 1024 tokens: 32 / 29 us).
+    // What gains is a long context under few query tiles, e.g. a 512-token chunk on
+    // 8 K-32 K of context.  Beside the narrow workgroups of a mixed batch the rule
+    // is the same: the wide part has one slot per CU there and ends under the
+    // narrow part's time anyway (128 decode + 4 chunks: 498 us with more cuts, 438
+    // without).
     int64_t chunk_w;
     if (opt.wide_kv_chunk > 0) {
         chunk_w = round_up(opt.wide_kv_chunk, kWideKvTile);
-    } else if (wide_tiles * s.num_kv_heads >= (int64_t)cus * (concurrent ? 1 : 4)) {
-        // enough workgroups as they are.  Beside the narrow kernel the wide one has
-        // one slot per CU and ends under the narrow kernel's time anyway: balance
-        // matters less there than the partial rows and the combine that splits cost.
+    } else if (wide_tiles * s.num_kv_heads >= (int64_t)cus) {
         chunk_w = (int64_t)1 << 30;
     } else {
-        chunk_w = round_up(std::max<int64_t>(512, ceil_div(work_wide * s.num_kv_heads,
-                                                           (int64_t)cus * (concurrent ? 1 : 4))),
+        const int64_t slots = (int64_t)cus * (concurrent ? 1 : 2);
+        chunk_w = round_up(std::max<int64_t>(concurrent ? 512 : 1024, ceil_div(work_wide * s.num_kv_heads, slots)),
                            kWideKvTile);
     }
 
