@@ -40,8 +40,15 @@ def time_workload(wl, steps, warmup, causal=True, kv_scales=None):
         ctx.update_and_attend(x["q"], x["k_new"], x["v_new"], x["k_pages"], x["v_pages"], table,
                               wl.cu_q_lens, wl.kv_lens, wl.sm_scale, out=out)
 
-    for _ in range(warmup):
+    # the requested warm-up, then more until the GPU has been busy for 50 ms: short
+    # rows would otherwise be timed while the clocks of an idle GPU still settle
+    t_w = time.perf_counter()
+    done = 0
+    while done < warmup or time.perf_counter() - t_w < 0.05:
         call()
+        done += 1
+        if done % 32 == 0:
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
