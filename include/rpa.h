@@ -223,8 +223,8 @@ typedef struct rpa_ctx rpa_ctx;
  * GPU (different streams without an ordering between them) need a context each. */
 int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device);
 
-/* Free the workspace.  The caller must have synchronised the stream last used
- * with this context.  NULL is allowed.                                        */
+/* Free the workspace.  Waits for the device first (kernels of the last calls may
+ * still be reading the context's work lists and partials).  NULL is allowed.   */
 void rpa_destroy(rpa_ctx* ctx);
 
 /* The hot path (Algorithm 1).  For each sequence r < num_seqs with

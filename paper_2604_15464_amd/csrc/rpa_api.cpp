@@ -167,6 +167,11 @@ extern "C" int rpa_create(rpa_ctx** out, const rpa_shape* shape, int device) {
 
 extern "C" void rpa_destroy(rpa_ctx* c) {
     if (!c) return;
+    // kernels of the last calls may still read the work lists (some from the pinned
+    // host slots) and the partials
+    int prev = -1;
+    if (hipGetDevice(&prev) == hipSuccess && prev != c->device) (void)hipSetDevice(c->device);
+    (void)hipDeviceSynchronize();
     for (int i = 0; i < kRing; ++i) {
         if (c->ring[i].done) (void)hipEventDestroy(c->ring[i].done);
         if (c->ring[i].fork) (void)hipEventDestroy(c->ring[i].fork);
@@ -184,6 +189,7 @@ extern "C" void rpa_destroy(rpa_ctx* c) {
     for (auto& p : c->prof)
         for (auto& e : p.ev)
             if (e) (void)hipEventDestroy(e);
+    if (prev >= 0 && prev != c->device) (void)hipSetDevice(prev);
     delete c;
 }
 
