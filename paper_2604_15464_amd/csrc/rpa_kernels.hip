@@ -41,8 +41,8 @@ typedef __attribute__((address_space(3))) int2v lds_int2;
 #define RPA_ABLATED(a, bits) false
 #endif
 
-// The wide kernel lets softmax weights grow to 2^kRescaleGap before it moves a
-// row's reference maximum and rescales the accumulator.
+// Both attention kernels let softmax weights grow to 2^kRescaleGap before they
+// move a row's reference maximum and rescale the accumulator.
 constexpr float kRescaleGap = 8.0f;
 
 // ---------------------------------------------------------------------------
@@ -467,9 +467,16 @@ __device__ __forceinline__ void narrow_body(const KernelArgs& a, const rpa_work_
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx * a.scale_log2);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run - m_use);
+        // The reference maximum only moves when the row maximum exceeds it by more
+        // than kRescaleGap (log2 units): weights may reach 2^gap, which fp32 and bf16
+        // hold exactly as well, and the rescale of the accumulator, a multiply per
+        // element, becomes rare (skipped under a wave-uniform branch).  The result is
+        // unchanged: numerator and l share the reference.
+        mx *= a.scale_log2;
+        const float m_new = (mx > m_run + kRescaleGap) ? mx : m_run;
+        const bool dead = m_new == -INFINITY; // nothing visible yet (or a padding row): state stays (0, 0)
+        const float m_use = dead ? 0.f : m_new;
+        const float alpha = dead ? 1.f : fast_exp2(m_run - m_use);
         float p[4];
         float psum = 0.f;
 #pragma unroll
@@ -479,8 +486,10 @@ __device__ __forceinline__ void narrow_body(const KernelArgs& a, const rpa_work_
         }
         l_run = l_run * alpha + psum;
         m_run = m_new;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) { // skip when no row's reference moved
 #pragma unroll
-        for (int j = 0; j < MT; ++j) acc[j] *= alpha;
+            for (int j = 0; j < MT; ++j) acc[j] *= alpha;
+        }
 
         union {
             uint32_t w[2];
@@ -1016,8 +1025,9 @@ __device__ __forceinline__ void wide_body(const KernelArgs& a, const rpa_work_un
             // and bf16 hold exactly as well, and the rescale of O becomes rare.  The
             // result is unchanged: numerator and l share the reference.
             const float m_new = (mx > m_run[nt] + kRescaleGap) ? mx : m_run[nt];
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = fast_exp2(m_run[nt] - m_use);
+            const bool dead = m_new == -INFINITY; // nothing visible yet (or a padding row): state stays (0, 0)
+            const float m_use = dead ? 0.f : m_new;
+            const float alpha = dead ? 1.f : fast_exp2(m_run[nt] - m_use);
             float psum = 0.f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
