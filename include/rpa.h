@@ -174,14 +174,17 @@ typedef struct {
     int32_t wide_rows;     /* query rows per wide tile: 256 (eight waves, one workgroup
                               per CU) or 128 (four waves, two workgroups per CU);
                               0 = chosen per call: 256 if that leaves every CU at
-                              least four workgroups, else 128.  head_dim 256 has the
-                              128-row shape only (one workgroup per CU) and rejects 256 */
+                              least four workgroups, else 128; 128 with the 8-bit
+                              cache.  head_dim 256 has the 128-row shape only (one
+                              workgroup per CU) and rejects 256                       */
     int32_t wide_order;    /* launch order of the wide units: 1 = longest tile first
                               overall; 2 = by sequence, heaviest sequence first,
                               longest tile first inside a sequence (the tiles of a
                               sequence then run at about the same time and share its
-                              K/V in L2); 0 = 2 for a batch of wide work only, 1 when
-                              narrow work runs beside it                              */
+                              K/V in L2); 0 = 2 where the wide launch is the persistent
+                              one (see wide_persistent), the KV heads come in
+                              multiples of 8 and nothing narrow runs beside it,
+                              else 1                                                  */
     int32_t mixed_overlap; /* a batch with narrow and wide work: 0 = the wide kernel
                               runs beside the narrow one (on a stream of the context,
                               forked from and joined to the caller's stream) when both

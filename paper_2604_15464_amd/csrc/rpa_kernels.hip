@@ -712,11 +712,13 @@ __device__ __forceinline__ void wide_body(const KernelArgs& a, const rpa_work_un
     // An item is a (unit, KV head) pair, in launch order.  A persistent workgroup
     // takes item blockIdx.x of every round of gridDim.x items, rounds alternating in
     // direction so that the long and the short items of the sorted list even out.
-    // The direction turns in groups of eight items, so that a workgroup keeps
-    // item % 8 == blockIdx.x % 8: its XCD then sees the same KV heads in every round.
+    // With KV heads in multiples of eight the direction turns in groups of eight
+    // items (which belong to one unit, so the sums stay even): a workgroup then keeps
+    // item % 8 == blockIdx.x % 8 and its XCD sees the same KV heads in every round.
     int round = 0;
     auto item_of_round = [&](int r) {
-        const int back = (nblocks & 7) == 0 ? nblocks - 8 - (block & ~7) + (block & 7) : nblocks - 1 - block;
+        const int back =
+            ((nblocks | Hkv) & 7) == 0 ? nblocks - 8 - (block & ~7) + (block & 7) : nblocks - 1 - block;
         const int idx = r * nblocks + ((r & 1) ? back : block);
         return (PERSIST && idx < a.num_wide_items) ? idx : -1;
     };

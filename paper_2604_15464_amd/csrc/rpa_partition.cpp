@@ -190,6 +190,12 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     int wide_rows = opt.wide_rows;
     if (s.head_dim > 128) {
         wide_rows = kWideRows; // the only shape built for this head_dim
+    } else if (wide_rows == 0 && s.kv_fp8) {
+        // 8-bit cache: the widening of the operands makes the loop heavier in vector
+        // work, and two independent 4-wave workgroups per CU hide that better than one
+        // of eight waves (8 x 2048: 333 against 361 us, one 16 K sequence: 2274
+        // against 2376 us; one 4 K sequence: 175 against 172 us)
+        wide_rows = kWideRows;
     } else if (wide_rows == 0) {
         int64_t tiles256 = 0;
         const int32_t tq256 = wide_q_tokens(hg, 256);
@@ -357,12 +363,21 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     }
 
     // Wide units longest first: the hardware dispatches workgroups in index order,
-    // so the short units fill the gaps at the end.  A batch of wide work only goes
-    // by sequence instead (measured on 8 x 2048: kernel 293 -> 288 us, on 16 x 1024:
-    // 178 -> 167 us, one sequence: the same order either way); beside narrow
-    // workgroups longest first stays (128 decode + 4 chunks: 403 / 406 us).
+    // so the short units fill the gaps at the end.  Where the launch is the
+    // persistent one (256-row tiles over a bf16 cache in separate pools, short
+    // items, nothing narrow beside them) the workgroups walk a fixed schedule with
+    // no tail to fill, and the units go by sequence instead, so that the tiles of a
+    // sequence run at about the same time and share its K/V in L2 (8 x 2048: HBM
+    // traffic 1.78 -> 1.0 x algorithmic, kernel 293 -> 288 us; 16 x 1024: 178 -> 167
+    // us).  One workgroup per item by sequence is slower (head_dim 256, 8 x 2048: 775
+    // against 733 us; 8-bit cache: 349 against 339 us): the last sequence's long
+    // tiles come last.
     auto span = [](const rpa_work_unit& u) { return (int64_t)(u.kv_end - u.kv_begin) * u.n_q; };
-    const int order = opt.wide_order != 0 ? opt.wide_order : (any_narrow ? 1 : 2);
+    // (with KV heads in multiples of 8 only: there an XCD serves one head of the
+    // sequences in flight; Hq 8 / Hkv 1, 8 x 2048: 82 us longest first, 88 us by sequence)
+    const bool persistent = !any_narrow && wide_rows == 256 && !s.kv_fp8 && !s.kv_merged && s.head_dim <= 128 &&
+                            s.num_kv_heads % 8 == 0 && opt.wide_persistent != 1 && plan.wide_persistent_pays();
+    const int order = opt.wide_order != 0 ? opt.wide_order : (persistent ? 2 : 1);
     if (order != 2) {
         std::stable_sort(plan.wide.begin(), plan.wide.end(),
                          [&](const rpa_work_unit& a, const rpa_work_unit& b) { return span(a) > span(b); });
