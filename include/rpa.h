@@ -175,8 +175,8 @@ typedef struct {
                               per CU) or 128 (four waves, two workgroups per CU);
                               0 = chosen per call: 256 if that leaves every CU at
                               least four workgroups, else 128; 128 with the 8-bit
-                              cache.  head_dim 256 has the 128-row shape only (one
-                              workgroup per CU) and rejects 256                       */
+                              cache and at head_dim 64.  head_dim 256 has the 128-row
+                              shape only (one workgroup per CU) and rejects 256       */
     int32_t wide_order;    /* launch order of the wide units: 1 = longest tile first
                               overall; 2 = by sequence, heaviest sequence first,
                               longest tile first inside a sequence (the tiles of a
