@@ -215,7 +215,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     }
     bool any_narrow = false, any_wide = false;
     std::vector<Tile> tiles;
-    int64_t work_wide = 0, wide_tiles = 0;
+    int64_t work_wide = 0, wide_tiles = 0, longest_wide = 0; // KV positions of all wide tiles, their number, the longest
     for (int32_t r = 0; r < n; ++r) {
         const int32_t lq = cu[r + 1] - cu[r];
         if (lq == 0) continue;
@@ -234,6 +234,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
             tiles.push_back(t);
             if (wide) {
                 work_wide += t.kv_hi;
+                longest_wide = std::max<int64_t>(longest_wide, t.kv_hi);
                 ++wide_tiles;
             }
         }
@@ -285,13 +286,25 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     // costs more than an idle half of the chip gains on anything short (one
     // 2048-token prefill: 73 us cut into 4, 54 us whole; 1024 tokens: 32 / 29 us).
     // What gains is a long context under few query tiles, e.g. a 512-token chunk on
-    // 8 K-32 K of context.  Beside the narrow workgroups of a mixed batch the rule
-    // is the same: the wide part has one slot per CU there and ends under the
-    // narrow part's time anyway (128 decode + 4 chunks: 498 us with more cuts, 438
-    // without).
+    // 8 K-32 K of context.  Beside the narrow workgroups of a mixed batch the wide
+    // part has one slot per CU and usually ends under the narrow part's time (128
+    // decode + 4 chunks at Hkv 8: 498 us with more cuts, 438 without); it is cut
+    // there only when its longest item alone outlasts both the narrow part and the
+    // wide part's own share per slot, i.e. when a few long items are the tail of the
+    // call (the same batch at Hq 16 / Hkv 2: 238 us whole, 160-169 us cut).
     int64_t chunk_w;
     if (opt.wide_kv_chunk > 0) {
         chunk_w = round_up(opt.wide_kv_chunk, kWideKvTile);
+    } else if (concurrent && wide_tiles * s.num_kv_heads >= (int64_t)cus) {
+        // in K/V tiles of the wide kernel: its share per slot, the narrow part's
+        // duration (6 TB/s) at about 2 us per wide tile beside it, the longest item
+        const double per_slot = (double)work_wide / kWideKvTile * s.num_kv_heads / cus;
+        const double narrow_tiles = narrow_bytes / 6e6 / 2.0;
+        const double target = std::max(per_slot, narrow_tiles);
+        const double longest = (double)longest_wide / kWideKvTile;
+        chunk_w = longest > 1.25 * target
+                      ? round_up(std::max<int64_t>(1024, (int64_t)(0.75 * target * kWideKvTile)), kWideKvTile)
+                      : (int64_t)1 << 30;
     } else if (wide_tiles * s.num_kv_heads >= (int64_t)cus) {
         chunk_w = (int64_t)1 << 30;
     } else {
