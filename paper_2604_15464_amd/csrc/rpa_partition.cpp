@@ -271,7 +271,10 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     // (The 8-bit cache has twice the positions, hence twice the arithmetic, per
     // byte: eight waves per CU there, measured 6 % faster than four, unless a wide
     // workgroup is to fit beside them.)
-    const int waves_per_cu = (s.kv_fp8 && !concurrent) ? 2 * kNarrowWavesPerCu : kNarrowWavesPerCu;
+    // (head_dim 64 has half the bytes per wave in flight: eight waves there too, 200 -> 195 us
+    // on 256 sequences of 512-4096 positions)
+    const int waves_per_cu =
+        ((s.kv_fp8 || s.head_dim == 64) && !concurrent) ? 2 * kNarrowWavesPerCu : kNarrowWavesPerCu;
     const int wgs_per_cu = std::max(1, std::min(kLdsBytesPerCu / lds_per_wg, waves_per_cu / waves));
     const int64_t slots = (int64_t)cus * wgs_per_cu;
     const int oversub = opt.units_per_cu > 0 ? opt.units_per_cu : 1;
