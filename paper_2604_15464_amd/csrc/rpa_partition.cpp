@@ -203,15 +203,33 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         // against 2376 us; one 4 K sequence: 175 against 172 us)
         wide_rows = kWideRows;
     } else if (wide_rows == 0) {
-        int64_t tiles256 = 0;
+        // 256 rows also when there is one workgroup per CU and the items are long and
+        // full: such a launch is bound by throughput, where the 8-wave shape moves
+        // half the K/V per row (16 chunks of 128 tokens on 8 K of context: 285 against
+        // 318 us; 32 of 64 tokens on 4 K: 163 against 178 us), while short items are
+        // bound by their own length and run better as twice as many workgroups (8
+        // chunks of 256 on 2 K: 80 against 91 us; one 4 K sequence: 144 against 150 us).
+        // (Not beside narrow work: there a CU holds a 4-wave wide workgroup and a narrow one.)
+        int64_t tiles256 = 0, work256 = 0, tokens = 0;
+        bool narrow_beside = false;
         const int32_t tq256 = wide_q_tokens(hg, 256);
         for (int32_t r = 0; r < n; ++r) {
             const int32_t lq = cu[r + 1] - cu[r];
             const bool wide = !narrow_only && (opt.variant == RPA_VARIANT_PREFILL ||
                                                (opt.variant != RPA_VARIANT_DECODE && lq > narrow_max_q));
-            if (lq > 0 && wide) tiles256 += ceil_div(lq, tq256);
+            if (lq > 0 && !wide) narrow_beside = true;
+            if (lq <= 0 || !wide) continue;
+            tiles256 += ceil_div(lq, tq256);
+            tokens += lq;
+            for (int32_t i0 = 0; i0 < lq; i0 += tq256)
+                work256 += s.non_causal ? kv[r] : kv[r] - lq + std::min(lq, i0 + tq256);
         }
-        wide_rows = tiles256 * s.num_kv_heads >= 4 * (int64_t)std::max(1, num_cus) ? 256 : kWideRows;
+        const int64_t cus1 = std::max(1, num_cus);
+        const bool many = tiles256 * s.num_kv_heads >= 4 * cus1;
+        const bool long_and_full = !narrow_beside && tiles256 * s.num_kv_heads >= cus1 &&
+                                   work256 >= tiles256 * 64 * kWideKvTile &&
+                                   tokens * 10 >= tiles256 * tq256 * 9;
+        wide_rows = (many || long_and_full) ? 256 : kWideRows;
     }
     bool any_narrow = false, any_wide = false;
     std::vector<Tile> tiles;
