@@ -119,11 +119,11 @@ TRAFFIC_SOURCE = ("profiles/hbm_traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE
 
 def narrow_part(wl):
     """The sequences of a batch that the narrow kernel serves by default (at most
-    two narrow tiles of query tokens), as a workload of their own: only its
+    one narrow tile of query tokens), as a workload of their own: only its
     lengths are used, for byte counts."""
     from paper_2604_15464_amd import workloads as W
     hg = wl.num_q_heads // wl.num_kv_heads
-    keep = wl.q_lens <= 2 * (16 // hg)
+    keep = wl.q_lens <= 16 // hg
     return W.Workload(wl.name + "[narrow]", wl.seed, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size,
                       wl.num_pages, wl.q_lens[keep], wl.kv_lens[keep], wl.page_table[keep])
 

@@ -71,7 +71,7 @@ int check_shape(const rpa_shape& s, std::string& err) {
 
 int classify_batch(const rpa_shape& s, const int32_t* cu, int32_t n) {
     const int hg = s.num_q_heads / s.num_kv_heads;
-    const int64_t narrow_max_q = 2 * (int64_t)narrow_q_tokens(hg);
+    const int64_t narrow_max_q = narrow_q_tokens(hg); // one narrow tile, as in build_plan
     const bool narrow_only = (s.kv_fp8 && s.head_dim != 128) || s.kv_merged;
     bool any_narrow = false, any_wide = false;
     for (int32_t r = 0; r < n; ++r) {
@@ -180,7 +180,10 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     }
 
     // ---- regime per sequence (Sec. 3.4) ---------------------------------
-    const int64_t narrow_max_q = 2 * (int64_t)tq_narrow; // up to two narrow tiles
+    // Narrow up to one narrow tile of query tokens (16 / h_g): a second tile would
+    // stream the sequence's K/V a second time (256 sequences of 8 tokens on 2 K of
+    // context at h_g 4: 683 us narrow, 495 us wide).
+    const int64_t narrow_max_q = tq_narrow;
     // the 8-bit cache has a wide kernel at head_dim 128 only; elsewhere, and with the
     // merged K|V pool, every batch runs narrow
     const bool narrow_only = (s.kv_fp8 && s.head_dim != 128) || s.kv_merged;
