@@ -97,7 +97,8 @@ typedef enum {
     RPA_VARIANT_AUTO = 0,
     RPA_VARIANT_DECODE = 1,  /* every query tile through the narrow split-KV kernel   */
     RPA_VARIANT_PREFILL = 2, /* every query tile through the wide MFMA tile kernel    */
-    RPA_VARIANT_MIXED = 3    /* short-query sequences narrow, the rest wide           */
+    RPA_VARIANT_MIXED = 3    /* sequences of up to 16 / (Hq / Hkv) query tokens (one
+                                narrow tile) narrow, the rest wide                    */
 } rpa_variant;
 
 /* One unit of work: a query tile of one sequence against a range of that
