@@ -329,12 +329,22 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         chunk_w = longest > 1.25 * target
                       ? round_up(std::max<int64_t>(1024, (int64_t)(0.75 * target * kWideKvTile)), kWideKvTile)
                       : (int64_t)1 << 30;
-    } else if (wide_tiles * s.num_kv_heads >= (int64_t)cus) {
-        chunk_w = (int64_t)1 << 30;
     } else {
-        const int64_t slots = (int64_t)cus * (concurrent ? 1 : 2);
-        chunk_w = round_up(std::max<int64_t>(concurrent ? 512 : 1024, ceil_div(work_wide * s.num_kv_heads, slots)),
-                           kWideKvTile);
+        // Alone, the wide kernel has two slots per CU with 128-row tiles and one with
+        // 256-row tiles.  Between one workgroup per CU and one per slot only long
+        // items are cut (8 K positions and more on average: four 256-token chunks on
+        // 16 K of context 352 -> 296 us, one 1024-token chunk 364 -> 342 us); shorter
+        // ones lose more to the partials than the idle slots cost (two 512-token
+        // chunks on 4 K: 103 us whole, 108 us cut).
+        const int64_t n_wg = wide_tiles * s.num_kv_heads;
+        const int64_t slots = (int64_t)cus * ((concurrent || wide_rows == 256) ? 1 : 2);
+        const bool long_items = wide_tiles > 0 && work_wide >= wide_tiles * 8192;
+        if (n_wg >= slots || (n_wg >= (int64_t)cus && !long_items))
+            chunk_w = (int64_t)1 << 30;
+        else
+            chunk_w = round_up(
+                std::max<int64_t>(concurrent ? 512 : 1024, ceil_div(work_wide * s.num_kv_heads, (int64_t)cus * (concurrent ? 1 : 2))),
+                kWideKvTile);
     }
 
     for (int attempt = 0; attempt < 32; ++attempt) {
