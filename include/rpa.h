@@ -187,9 +187,10 @@ typedef struct {
                               one (see wide_persistent), the KV heads come in
                               multiples of 8 and nothing narrow runs beside it,
                               else 1                                                  */
-    int32_t mixed_overlap; /* a batch with narrow and wide work: 0 = the wide kernel
-                              runs beside the narrow one (on a stream of the context,
-                              forked from and joined to the caller's stream) when both
+    int32_t mixed_overlap; /* a batch with narrow and wide work: 0 = side by side as
+                              one launch wherever that kernel is built (below), else
+                              with the wide kernel on a stream of the context (forked
+                              from and joined to the caller's stream) when both
                               parts are large enough to repay the two extra stream
                               packets; 1 = always one after the other on the caller's
                               stream; 2 = always side by side; 3 = always side by side

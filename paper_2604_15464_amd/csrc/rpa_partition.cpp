@@ -278,12 +278,19 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     const double kv_elem_bytes = s.kv_fp8 ? 1.0 : 2.0;
     const double narrow_bytes = (double)total_tiles * kNarrowKvTile * s.num_kv_heads * s.head_dim * 2.0 * kv_elem_bytes;
     const double wide_flops = (double)work_wide * wide_q_tokens(hg, wide_rows) * 4.0 * s.num_q_heads * s.head_dim;
+    const int waves = opt.narrow_waves > 0 ? opt.narrow_waves : narrow_waves(s.num_kv_heads, s.head_dim);
+    // Where one launch can hold both kinds of workgroup (the shapes that kernel is
+    // built for) a mixed batch of any size runs that way: it costs no packet, and a
+    // small batch saves a whole kernel's latency (4 sequences: 20 -> 14 us; the mixed
+    // recipe at 1/16 of its size: 38 -> 21 us, at 1/4: 63 -> 51 us).  As two kernels on
+    // two streams only when both parts repay the event packets.
+    const bool one_launch_shape = !s.kv_merged && (s.kv_fp8 ? s.head_dim == 128 : s.head_dim <= 128) &&
+                                  wide_rows == kWideRows && (waves == 1 || waves == 2 || waves == 4);
     if (any_narrow && any_wide && opt.mixed_overlap != 1)
-        concurrent = opt.mixed_overlap >= 2 || (narrow_bytes >= 128e6 && wide_flops >= 2e10);
+        concurrent = opt.mixed_overlap >= 2 || one_launch_shape || (narrow_bytes >= 128e6 && wide_flops >= 2e10);
     // rough GPU time of the call: the narrow part at 6 TB/s, the wide part at 1 PFLOP/s
     plan.est_gpu_us = narrow_bytes / 6e6 + wide_flops / 1e9;
 
-    const int waves = opt.narrow_waves > 0 ? opt.narrow_waves : narrow_waves(s.num_kv_heads, s.head_dim);
     const int ny = s.num_kv_heads / waves;
     const int lds_per_wg = waves * narrow_lds_per_wave(s.head_dim); // the same with the 8-bit cache: half the row, twice the stages
     // Four resident waves (one 64 KB workgroup at head_dim 128) per CU already

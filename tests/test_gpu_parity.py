@@ -416,7 +416,15 @@ def test_many_calls_on_alternating_streams():
 
 
 def test_small_mixed_batch_stays_on_one_stream():
+    """A tiny mixed batch: one launch with both kinds of workgroup where that kernel is
+    built; where it is not (head_dim 256), narrow and wide kernels one after the other
+    on the caller's stream rather than two streams' worth of event packets."""
     wl = W.config(1)
+    res = run_case(wl)
+    check(wl, res)
+    assert res["info"]["variant"] == rpa.VARIANT_MIXED and res["info"]["concurrent"] == 2
+    wl = W.ragged(1777, num_seqs=6, hq=8, hkv=2, d=256, ps=16, max_q=60, max_ctx=200, p_decode=0.5)
+    assert (wl.q_lens == 1).any() and (wl.q_lens > 8).any()
     res = run_case(wl)
     check(wl, res)
     assert res["info"]["variant"] == rpa.VARIANT_MIXED and res["info"]["concurrent"] == 0

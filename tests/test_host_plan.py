@@ -127,9 +127,14 @@ def test_mixed_batches_run_side_by_side_when_large_enough():
     c4 = W.config(4)
     assert rpa.plan_host(shape_of(c4), c4.cu_q_lens, c4.kv_lens)[2]["concurrent"] == 1
     assert rpa.plan_host(shape_of(c4), c4.cu_q_lens, c4.kv_lens, mixed_overlap=1)[2]["concurrent"] == 0
-    c1 = W.config(1)                                  # both parts tiny: not worth two stream packets
-    assert rpa.plan_host(shape_of(c1), c1.cu_q_lens, c1.kv_lens)[2]["concurrent"] == 0
-    assert rpa.plan_host(shape_of(c1), c1.cu_q_lens, c1.kv_lens, mixed_overlap=2)[2]["concurrent"] == 1
+    c1 = W.config(1)                                  # tiny, but one launch can hold both parts: side by side
+    assert rpa.plan_host(shape_of(c1), c1.cu_q_lens, c1.kv_lens)[2]["concurrent"] == 1
+    assert rpa.plan_host(shape_of(c1), c1.cu_q_lens, c1.kv_lens, mixed_overlap=1)[2]["concurrent"] == 0
+    # where that launch is not built (head_dim 256) a tiny batch is not worth two stream packets
+    t256 = W.ragged(77, num_seqs=6, hq=8, hkv=2, d=256, ps=16, max_q=60, max_ctx=200, p_decode=0.5)
+    assert (t256.q_lens == 1).any() and (t256.q_lens > 8).any()
+    assert rpa.plan_host(shape_of(t256), t256.cu_q_lens, t256.kv_lens)[2]["concurrent"] == 0
+    assert rpa.plan_host(shape_of(t256), t256.cu_q_lens, t256.kv_lens, mixed_overlap=2)[2]["concurrent"] == 1
     for idx in (2, 3):                                # one kind of work only: nothing to overlap
         wl = W.config(idx, scale=0.25)
         assert rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, mixed_overlap=2)[2]["concurrent"] == 0
