@@ -176,7 +176,8 @@ typedef struct {
                               per CU) or 128 (four waves, two workgroups per CU);
                               0 = chosen per call: 256 if that leaves every CU at
                               least four workgroups, or one of long (64 K/V tiles
-                              or more on average), full tiles, else 128; 128 with the 8-bit
+                              or more on average), full tiles, else 128; 128 beside
+                              narrow work (a mixed batch), with the 8-bit
                               cache and at head_dim 64.  head_dim 256 has the 128-row
                               shape only (one workgroup per CU) and rejects 256       */
     int32_t wide_order;    /* launch order of the wide units: 1 = longest tile first

@@ -212,7 +212,6 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         // 318 us; 32 of 64 tokens on 4 K: 163 against 178 us), while short items are
         // bound by their own length and run better as twice as many workgroups (8
         // chunks of 256 on 2 K: 80 against 91 us; one 4 K sequence: 144 against 150 us).
-        // (Not beside narrow work: there a CU holds a 4-wave wide workgroup and a narrow one.)
         int64_t tiles256 = 0, work256 = 0, tokens = 0;
         bool narrow_beside = false;
         const int32_t tq256 = wide_q_tokens(hg, 256);
@@ -229,10 +228,12 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         }
         const int64_t cus1 = std::max(1, num_cus);
         const bool many = tiles256 * s.num_kv_heads >= 4 * cus1;
-        const bool long_and_full = !narrow_beside && tiles256 * s.num_kv_heads >= cus1 &&
-                                   work256 >= tiles256 * 64 * kWideKvTile &&
+        const bool long_and_full = tiles256 * s.num_kv_heads >= cus1 && work256 >= tiles256 * 64 * kWideKvTile &&
                                    tokens * 10 >= tiles256 * tq256 * 9;
-        wide_rows = (many || long_and_full) ? 256 : kWideRows;
+        // beside narrow work: 128 rows, the shape that shares a CU and a launch with
+        // narrow workgroups (64 decode sequences + 8 x 2048 prefill: 367 us against 389
+        // us as two kernels with 256-row tiles; 128 + one 8 K prefill: 756 / 837 us)
+        wide_rows = (!narrow_beside && (many || long_and_full)) ? 256 : kWideRows;
     }
     bool any_narrow = false, any_wide = false;
     std::vector<Tile> tiles;
