@@ -247,3 +247,55 @@ def test_empty_batches():
     # sequences with q_len 0 contribute nothing
     units, items, stats = rpa.plan_host(shape_of(wl), [0, 0, 3, 3], [5, 10, 7])
     assert set(units[:, F["seq"]].tolist()) == {1}
+
+
+def test_default_launch_rules():
+    """What the partitioner picks when no knob is set, on the cases each rule was measured
+    on: tile height, unit order, cuts and the narrow / wide line."""
+    def plan(wl, **kw):
+        kvs = kw.pop("kv_scales", None)
+        return rpa.plan_host(shape_of(wl, kv_scales=kvs), wl.cu_q_lens, wl.kv_lens, **kw)
+
+    def seq_runs(units):
+        s = units[:, F["seq"]]
+        return 1 + int(np.count_nonzero(s[1:] != s[:-1]))
+
+    # prefill 8 x 2048: 256-row tiles in the persistent launch, one sequence after the other
+    units, _, st = plan(W.config(3))
+    assert st["wide_rows"] == 256 and st["max_splits"] == 1 and seq_runs(units) == 8
+    # the same lengths with one KV head, at head_dim 256, over the 8-bit cache: longest tile first overall
+    for wl, kw in ((W.regime("prefill", hq=8, hkv=1), {}), (W.regime("prefill", d=256, ps=64), {}),
+                   (W.regime("prefill"), {"kv_scales": (1 / 64, 1 / 32)})):
+        units, _, st = plan(wl, **kw)
+        assert seq_runs(units) > 8
+        span = (units[:, F["kv_end"]] - units[:, F["kv_begin"]]).astype(np.int64) * units[:, F["n_q"]]
+        assert np.all(span[1:] <= span[:-1])
+    # head_dim 64 and the 8-bit cache: 128-row tiles
+    assert plan(W.regime("prefill", d=64))[2]["wide_rows"] == 128
+    assert plan(W.regime("prefill"), kv_scales=(1 / 64, 1 / 32))[2]["wide_rows"] == 128
+    # a mixed batch: 128-row tiles and side by side, however much of it is prefill
+    for wl in (W.config(4), W.config(1)):
+        st = plan(wl)[2]
+        assert st["variant"] == rpa.VARIANT_MIXED and st["wide_rows"] == 128 and st["concurrent"] == 1
+    rng = np.random.default_rng(11)
+    q = np.concatenate([np.ones(64, dtype=np.int64), np.full(8, 2048, dtype=np.int64)])
+    kv = np.concatenate([np.full(64, 2049, dtype=np.int64), np.full(8, 2048, dtype=np.int64)])
+    heavy = W._finish("prefill_heavy_mixed", 11, 32, 8, 128, 16, q, kv, rng)
+    st = plan(heavy)[2]
+    assert st["wide_rows"] == 128 and st["concurrent"] == 1
+    # long items under few query tiles are cut, short ones are not
+    assert plan(W.uniform(4, 256, 16384 + 256, ps=16))[2]["max_splits"] > 1
+    assert plan(W.uniform(1, 512, 8192 + 512, ps=16))[2]["max_splits"] > 1
+    assert plan(W.uniform(2, 512, 4096 + 512, ps=16))[2]["max_splits"] == 1
+    assert plan(W.uniform(1, 2048, 2048, ps=16))[2]["max_splits"] == 1
+    # long, full items with one workgroup per CU: 256-row tiles
+    assert plan(W.uniform(16, 128, 8192 + 128, ps=16))[2]["wide_rows"] == 256
+    assert plan(W.uniform(8, 256, 2048 + 256, ps=16))[2]["wide_rows"] == 128
+    # narrow up to one narrow tile of query tokens (16 / h_g = 4 here), wide beyond
+    assert plan(W.uniform(64, 4, 1024, ps=16))[2]["variant"] == rpa.VARIANT_DECODE
+    assert plan(W.uniform(64, 5, 1024, ps=16))[2]["variant"] == rpa.VARIANT_PREFILL
+    # the mixed recipe with two KV heads: its long chunks are cut, with eight they are not
+    assert plan(W.regime("mixed", hq=16, hkv=2))[2]["max_splits"] > 1
+    units, _, st = plan(W.config(4))
+    wide = units[(units[:, F["flags"]] & 2) != 0]
+    assert np.all(wide[:, F["part_row"]] < 0)
