@@ -186,8 +186,8 @@ typedef struct {
                               sequence then run at about the same time and share its
                               K/V in L2); 0 = 2 where the wide launch is the persistent
                               one (see wide_persistent), the KV heads come in
-                              multiples of 8 and nothing narrow runs beside it,
-                              else 1                                                  */
+                              multiples of 8, the sequences are of about one length
+                              and nothing narrow runs beside it, else 1               */
     int32_t mixed_overlap; /* a batch with narrow and wide work: 0 = side by side as
                               one launch wherever that kernel is built (below), else
                               with the wide kernel on a stream of the context (forked
