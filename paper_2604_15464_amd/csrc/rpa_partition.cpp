@@ -302,8 +302,13 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
     // workgroup is to fit beside them.)
     // (head_dim 64 has half the bytes per wave in flight: eight waves there too, 200 -> 195 us
     // on 256 sequences of 512-4096 positions)
-    const int waves_per_cu =
-        ((s.kv_fp8 || s.head_dim == 64) && !concurrent) ? 2 * kNarrowWavesPerCu : kNarrowWavesPerCu;
+    // (Both only on a batch large enough to keep that many workgroups busy, about 200
+    // MB of K/V: below, twice the bins mean sequences cut in pieces and a combine
+    // pass that a short call cannot repay.  128 sequences of 512 positions: head_dim
+    // 64 28 against 32 us, 8-bit cache 35 against 39 us.)
+    const int waves_per_cu = ((s.kv_fp8 || s.head_dim == 64) && !concurrent && narrow_bytes >= 192e6)
+                                 ? 2 * kNarrowWavesPerCu
+                                 : kNarrowWavesPerCu;
     const int wgs_per_cu = std::max(1, std::min(kLdsBytesPerCu / lds_per_wg, waves_per_cu / waves));
     const int64_t slots = (int64_t)cus * wgs_per_cu;
     const int oversub = opt.units_per_cu > 0 ? opt.units_per_cu : 1;

@@ -75,7 +75,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--max-len", type=int, default=32768)
-    ap.add_argument("--head-dim", type=int, default=128, choices=(128, 256))
+    ap.add_argument("--head-dim", type=int, default=128, choices=(64, 128, 256))
     ap.add_argument("--kv-fp8", action="store_true",
                     help="decode table with the 8-bit (E4M3) KV cache; bytes counted at one byte per cached element")
     args = ap.parse_args()
