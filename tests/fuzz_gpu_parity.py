@@ -33,16 +33,28 @@ while time.time() < t_end:
         kw["kv_scales"] = rng.choice([(1 / 64, 1 / 32), (0.05, 0.02), (1.0, 1.0)])
     if rng.random() < 0.5:
         kw["needles"] = (rng.choice(["boundaries", "spread", "random"]), rng.randint(0, 99))
-    wl = W.ragged(90000 + base + i, num_seqs=rng.randint(1, 40), hq=hq, hkv=hkv, d=d,
-                  ps=rng.choice([16, 32, 64, 128, 256]), max_q=rng.choice([1, 5, 40, 200, 500]),
-                  max_ctx=rng.choice([0, 50, 700, 2500, 6000]), p_decode=rng.choice([0.1, 0.5, 0.9, 1.0]),
-                  p_empty=rng.choice([0.0, 0.1]))
+    seqs = None
+    if rng.random() < 0.04:
+        # now and then a batch large enough for the launch forms that small ones never reach
+        # (persistent wide workgroups, 256-row tiles by count, cut long items); the oracle
+        # attends a sample of its sequences, the cache is compared in full
+        wl = W.ragged(90000 + base + i, num_seqs=rng.randint(8, 40), hq=hq, hkv=hkv, d=d,
+                      ps=rng.choice([16, 64, 256]), max_q=rng.choice([600, 1500, 2500]),
+                      max_ctx=rng.choice([0, 2500, 9000]), p_decode=rng.choice([0.0, 0.3, 0.8]), p_empty=0.0)
+        seqs = sorted(rng.sample(range(wl.num_seqs), 3))
+        kw["calls"] = 1
+    else:
+        wl = W.ragged(90000 + base + i, num_seqs=rng.randint(1, 40), hq=hq, hkv=hkv, d=d,
+                      ps=rng.choice([16, 32, 64, 128, 256]), max_q=rng.choice([1, 5, 40, 200, 500]),
+                      max_ctx=rng.choice([0, 50, 700, 2500, 6000]), p_decode=rng.choice([0.1, 0.5, 0.9, 1.0]),
+                      p_empty=rng.choice([0.0, 0.1]))
     if wl.num_tokens == 0: continue
-    print(f"case {i}: hq{hq} hkv{hkv} d{d} ps{wl.page_size} seqs{wl.num_seqs} tok{wl.num_tokens} kvmax{int(wl.kv_lens.max())} {kw}", flush=True)
+    print(f"case {i}: hq{hq} hkv{hkv} d{d} ps{wl.page_size} seqs{wl.num_seqs} tok{wl.num_tokens} kvmax{int(wl.kv_lens.max())} {kw}"
+          + (f" oracle on sequences {seqs}" if seqs else ""), flush=True)
     try:
-        res = T.run_case(wl, **kw)
+        res = T.run_case(wl, seqs=seqs, **kw)
     except rpa.RpaError as e:
         assert e.code in (rpa.ERR_WORKSPACE, rpa.ERR_INVALID_ARG, rpa.ERR_UNSUPPORTED), str(e)
         print("   rejected:", e, flush=True); continue
-    T.check(wl, res); n_ok += 1
+    T.check(wl, res, seqs=seqs); n_ok += 1
 print("fuzz ok:", n_ok, "cases")
