@@ -96,6 +96,14 @@ __device__ __forceinline__ void async_load16_base(const void* sbase, uint32_t vo
                  : "memory", "m0");
 }
 
+// ... and the non-temporal hint of async_load16_stream
+__device__ __forceinline__ void async_load16_base_stream(const void* sbase, uint32_t voff, uint32_t lds_byte_off) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0 nt"
+                 :
+                 : "s"(sbase), "v"(voff), "s"(lds_byte_off)
+                 : "memory", "m0");
+}
+
 #pragma clang diagnostic pop
 
 // A pointer whose value is the same in every lane, moved to scalar registers in
@@ -772,6 +780,11 @@ __device__ __forceinline__ void wide_body(const KernelArgs& a, const rpa_work_un
     int wave_limit = -1;           // positions above it are hidden from every row of the wave
     int wave_min_limit = 1 << 30;  // positions up to it are visible to every live row of the wave
     int kv_begin = 0, kv_end = 0, ntiles = 0;
+    // The sequence has this one query tile: its K/V rows are read once in this call
+    // (per KV head), like the narrow kernel's, and take the same non-temporal loads
+    // (256 sequences of 8 query tokens on 2 K of context: 394 -> 347 us; of 16: 401 ->
+    // 384 us).  Tiles that share a sequence re-read its rows from L2 and must not.
+    bool stream_kv = false;
     const int ld_tok = lane / NC;
     const int ld_chunk = lane % NC;
     uint32_t lane_voff[NLD]; // byte offset of the lane's chunk of load i from the first token of the wave's share
@@ -802,6 +815,7 @@ __device__ __forceinline__ void wide_body(const KernelArgs& a, const rpa_work_un
     kv_begin = u.kv_begin;
     kv_end = u.kv_end;
     ntiles = max(0, (kv_end - kv_begin + KT - 1) / KT);
+    stream_kv = (u.flags & 4) != 0;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
         const int r = WPOS * wave + i * TPI + ld_tok; // row inside the 64-position tile
@@ -836,10 +850,18 @@ __device__ __forceinline__ void wide_body(const KernelArgs& a, const rpa_work_un
             const uint64_t boff = tok0 * tokstride;
             const char* kb = uniform_ptr((all_cached ? k_pages : k_new) + boff);
             const char* vb = uniform_ptr((all_cached ? v_pages : v_new) + boff);
+            if (stream_kv) {
 #pragma unroll
-            for (int i = 0; i < NLD; ++i) {
-                async_load16_base(kb, lane_voff[i], ldsK + i * 1024);
-                async_load16_base(vb, lane_voff[i], ldsV + i * 1024);
+                for (int i = 0; i < NLD; ++i) {
+                    async_load16_base_stream(kb, lane_voff[i], ldsK + i * 1024);
+                    async_load16_base_stream(vb, lane_voff[i], ldsV + i * 1024);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < NLD; ++i) {
+                    async_load16_base(kb, lane_voff[i], ldsK + i * 1024);
+                    async_load16_base(vb, lane_voff[i], ldsV + i * 1024);
+                }
             }
         } else {
             // the share straddles the cached/new boundary or the end of the range:

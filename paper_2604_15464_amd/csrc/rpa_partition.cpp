@@ -87,6 +87,7 @@ namespace {
 struct Tile {
     int32_t seq, q_pos0, n_q, kv_hi, ctx, seq_q0;
     bool wide;
+    bool alone; // the only query tile of its sequence: no other tile reads these K/V rows
 };
 
 void emit_units(const Tile& t, int64_t chunk, int align, int num_q_heads, int64_t& part_cursor,
@@ -114,7 +115,7 @@ void emit_units(const Tile& t, int64_t chunk, int align, int num_q_heads, int64_
         u.ctx = t.ctx;
         u.seq_q0 = t.seq_q0;
         u.part_row = n_s > 1 ? (int32_t)(base + s * rows) : -1;
-        u.flags = (s == n_s - 1 ? 1 : 0) | (t.wide ? 2 : 0);
+        u.flags = (s == n_s - 1 ? 1 : 0) | (t.wide ? 2 : 0) | (t.alone ? 4 : 0);
         units.push_back(u);
     }
 }
@@ -253,7 +254,7 @@ int build_plan(const rpa_shape& s, const int32_t* cu, const int32_t* kv, int32_t
         const int32_t ctx = kv[r] - lq;
         const int32_t tq = wide ? wide_q_tokens(hg, wide_rows) : tq_narrow;
         for (int32_t i0 = 0; i0 < lq; i0 += tq) {
-            Tile t{r, i0, std::min(tq, lq - i0), 0, ctx, cu[r], wide};
+            Tile t{r, i0, std::min(tq, lq - i0), 0, ctx, cu[r], wide, lq <= tq};
             t.kv_hi = s.non_causal ? kv[r] : ctx + i0 + t.n_q; // last position any row of the tile sees, + 1
             tiles.push_back(t);
             if (wide) {
