@@ -116,9 +116,9 @@ typedef struct {
     int32_t seq_q0;     /* cu_q_lens[r]                                               */
     int32_t part_row;   /* first row of this unit's split partial, or -1: write out   */
     int32_t flags;      /* bit 0: this unit writes the tile's new K/V into the pages;
-                           bit 1: wide kernel (else narrow); bit 2: the tile is its
-                           sequence's only one, so its K/V rows are read once in
-                           this call (the wide kernel then streams them)             */
+                           bit 1: wide kernel (else narrow); bit 2 (wide units): the
+                           tile is its sequence's only one, so its K/V rows are read
+                           once in this call and the wide kernel streams them        */
     int32_t bin;        /* narrow units: index of the workgroup that runs the unit     */
     int32_t reserved;
 } rpa_work_unit;

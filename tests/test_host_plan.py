@@ -299,3 +299,25 @@ def test_default_launch_rules():
     units, _, st = plan(W.config(4))
     wide = units[(units[:, F["flags"]] & 2) != 0]
     assert np.all(wide[:, F["part_row"]] < 0)
+
+
+def test_only_tile_of_a_sequence_is_flagged():
+    """Bit 2 of a wide unit's flags: the unit's tile is the only query tile of its sequence,
+    so no other tile of the call reads the same K/V rows (the wide kernel streams them)."""
+    wl = W.ragged(4242, num_seqs=30, hq=32, hkv=8, d=128, ps=16, max_q=120, max_ctx=900, p_decode=0.3)
+    units, _, st = rpa.plan_host(shape_of(wl), wl.cu_q_lens, wl.kv_lens, wide_kv_chunk=256)
+    tq = {False: 16 // 4, True: st["wide_rows"] // 4}
+    tiles = {}
+    for u in units:
+        tiles.setdefault(int(u[F["seq"]]), set()).add(int(u[F["q_pos0"]]))
+    seen = set()
+    for u in units:
+        seq, wide = int(u[F["seq"]]), bool(u[F["flags"]] & 2)
+        alone = bool(u[F["flags"]] & 4)
+        if not wide:                      # the narrow kernel streams every K/V row anyway
+            assert not alone
+            continue
+        assert alone == (len(tiles[seq]) == 1), (seq, tiles[seq])
+        assert alone == (wl.q_lens[seq] <= tq[wide])
+        seen.add(alone)
+    assert seen == {True, False}
