@@ -392,6 +392,11 @@ def main():
         steps3 = args.steps
         dt3, prof3, _ = time_steps(ctx3, x3, table3, wl3, steps3, args.warmup)
         info3 = ctx3.plan_info()
+        # what this box's matrix pipe sustains, measured right behind the timed steps
+        # (launches of MFMAs alone on every CU, 5-8 ms each; the rate falls within
+        # milliseconds of matrix load, so the last of four is the one reported)
+        probe = [ctx3.mfma_probe(6000) for _ in range(4)]
+        mfma_only_tf = probe[-1][1] / (probe[-1][0] * 1e-3) / 1e12
         ctx3.close()
         flops = wl3.algorithmic_flops()
         wide_ms = prof3["wide_ms"] / max(1, prof3["calls"])
@@ -410,6 +415,12 @@ def main():
                          "frac": round(tf_k / MFMA_BF16_PEAK_TFLOPS, 4),
                          "traffic": load_traffic(wl3.name, "rpa_wide_kernel"), "traffic_source": TRAFFIC_SOURCE,
                          "avg_kernel_ms": round(wide_ms, 5)},
+            "mfma_only": {"value": round(mfma_only_tf, 1), "unit": "TFLOP/s",
+                          "frac_of_peak": round(mfma_only_tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                          "kernel_frac_of_it": round(tf_k / mfma_only_tf, 4),
+                          "launches_TFLOPs": [round(fl / (ms * 1e-3) / 1e12, 1) for ms, fl in probe],
+                          "what": "rpa_mfma_probe: bf16 32x32x16 MFMAs alone on pseudo-random operands, 8 waves on "
+                                  "each CU, no memory traffic; four launches of 6000 steps, the last one reported"},
         }
         del x3, table3
         torch.cuda.empty_cache()

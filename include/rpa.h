@@ -344,6 +344,15 @@ int rpa_profile_read(rpa_ctx* ctx, float* narrow_ms, float* wide_ms, float* comb
 int rpa_copy_probe(rpa_ctx* ctx, void* dst, const void* src, size_t bytes, void* stream,
                    float* ms);
 
+/* Measurement aid (not part of the paper's method): a kernel of bf16 MFMAs
+ * (32x32x16) and nothing else, one workgroup of eight waves per compute unit,
+ * `steps` (1 .. 2^20) steps of 32 MFMAs per wave, on `stream`; no memory is read
+ * or written.  It shows the matrix rate the machine sustains with every compute
+ * unit busy, the figure the wide kernel's TFLOP/s stand against on that machine.
+ * *flops (if not NULL) receives the FLOPs of the launch; if ms is not NULL the
+ * call waits for the kernel and stores its duration in milliseconds.         */
+int rpa_mfma_probe(rpa_ctx* ctx, int32_t steps, void* stream, float* ms, double* flops);
+
 /* Host-only planning, no GPU needed: the work partition that
  * rpa_update_and_attend would use on a device with `num_cus` compute units
  * (Alg. 1's loops over sequences, Q blocks and KV blocks, flattened into units;

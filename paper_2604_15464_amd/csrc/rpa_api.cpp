@@ -311,6 +311,32 @@ extern "C" int rpa_copy_probe(rpa_ctx* c, void* dst, const void* src, size_t byt
     return RPA_OK;
 }
 
+extern "C" int rpa_mfma_probe(rpa_ctx* c, int32_t steps, void* stream, float* ms, double* flops) {
+    if (!c) return RPA_ERR_INVALID_ARG;
+    if (steps < 1 || steps > (1 << 20)) return fail(c, RPA_ERR_INVALID_ARG, "rpa_mfma_probe: steps must be in [1, 2^20]");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, "hipSetDevice", e);
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    if (ms) {
+        for (auto& x : ev) {
+            e = hipEventCreate(&x);
+            if (e != hipSuccess) return hip_fail(c, "hipEventCreate", e);
+        }
+    }
+    int rc = launch_mfma(steps, c->num_cus, stream, ms ? (void**)ev : nullptr);
+    if (rc == 0 && ms) {
+        e = hipEventSynchronize(ev[1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(ms, ev[0], ev[1]);
+        rc = (int)e;
+    }
+    for (auto& x : ev)
+        if (x) (void)hipEventDestroy(x);
+    if (rc != 0) return hip_fail(c, "rpa_mfma_probe", (hipError_t)rc);
+    // workgroups x 8 waves x steps x 32 MFMAs of 2 * 32 * 32 * 16 FLOPs
+    if (flops) *flops = (double)c->num_cus * 8.0 * (double)steps * 32.0 * 32768.0;
+    return RPA_OK;
+}
+
 extern "C" int rpa_plan_host(const rpa_shape* shape, const int32_t* cu_q_lens, const int32_t* kv_lens,
                              int32_t num_seqs, const rpa_options* opt, int num_cus, rpa_work_unit* units,
                              int32_t max_units, rpa_combine_item* items, int32_t max_items,

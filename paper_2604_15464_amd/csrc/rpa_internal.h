@@ -124,6 +124,7 @@ int launch_combine(const rpa_combine_item* items, int num_items, const float* pa
                    const float* part_ml, uint16_t* out, int num_q_heads, int head_dim, int max_rows,
                    void* stream, void** ev);
 int launch_copy(void* dst, const void* src, size_t n16, int num_cus, void* stream, void** ev);
+int launch_mfma(int steps, int num_cus, void* stream, void** ev);
 // new K/V rows (bf16, `elems` elements each, a multiple of 8) -> E4M3 bytes of x * inv_scale
 int launch_quantize(const void* k_new, const void* v_new, void* k8, void* v8, size_t elems, float inv_k, float inv_v,
                     int num_cus, void* stream);

@@ -1585,6 +1585,46 @@ __global__ __launch_bounds__(256) void rpa_copy_kernel(uint4* __restrict__ dst, 
 }
 
 // ---------------------------------------------------------------------------
+// A loop of bf16 MFMAs and nothing else: eight waves per workgroup (two per SIMD,
+// as in the wide kernel), 32 MFMAs 32x32x16 per step over four accumulators and
+// four register sets per operand, no memory access.  Not part of the method: it
+// measures the matrix rate the chip sustains with every CU busy and operands that
+// look like data, which is what the wide kernel's TFLOP/s figure stands against
+// on a given machine.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void rpa_mfma_kernel(int steps) {
+    // operands: pseudo-random bf16 values of either sign in [0.5, 2), different in
+    // every lane and register (with near-constant operands the same loop runs at
+    // the nominal rate: what the chip sustains depends on how many bits toggle)
+    bf16x8 x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint32_t w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t h = (threadIdx.x * 32u + i * 4u + k + 1u) * 2654435761u;
+            h ^= h >> 15;
+            h *= 2246822519u;
+            h ^= h >> 13;
+            w[k] = (h & 0x80ff80ffu) | 0x3f003f00u;
+        }
+        x[i] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+    }
+    f32x16 o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[i][e] = 0.f;
+    for (int t = 0; t < steps; ++t) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i)
+            o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[i & 3], x[4 + ((i >> 2) & 3)], o[i & 3], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) asm volatile("" ::"v"(o[i])); // the results are wanted by nobody else
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 template <int D>
@@ -1726,6 +1766,12 @@ int launch_copy(void* dst, const void* src, size_t n16, int num_cus, void* strea
     const size_t cap = (size_t)num_cus * 8;
     dim3 grid((unsigned)(want < cap ? want : cap));
     RPA_LAUNCH(rpa_copy_kernel, grid, dim3(256), 0, (hipStream_t)stream, ev, (uint4*)dst, (const uint4*)src, n16);
+    return (int)hipGetLastError();
+}
+
+int launch_mfma(int steps, int num_cus, void* stream, void** ev) {
+    if (steps <= 0 || num_cus <= 0) return 0;
+    RPA_LAUNCH(rpa_mfma_kernel, dim3((unsigned)num_cus), dim3(512), 0, (hipStream_t)stream, ev, steps);
     return (int)hipGetLastError();
 }
 

@@ -65,7 +65,7 @@ _lib = None
 
 EXPORTS = ("rpa_create", "rpa_destroy", "rpa_update_and_attend", "rpa_last_error", "rpa_plan_info",
            "rpa_set_options", "rpa_set_regime_options", "rpa_plan_host", "rpa_profile_enable", "rpa_profile_read",
-           "rpa_copy_probe", "rpa_update_and_attend_noalloc", "rpa_noalloc_last_error")
+           "rpa_copy_probe", "rpa_mfma_probe", "rpa_update_and_attend_noalloc", "rpa_noalloc_last_error")
 
 
 ABLATE_LIB_PATH = os.path.join(_HERE, "librpa_ablate.so")   # measurement build: the same code with -DRPA_ABLATE
@@ -114,6 +114,8 @@ def load_library(path):
     l.rpa_plan_host.restype = C.c_int
     l.rpa_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
     l.rpa_copy_probe.restype = C.c_int
+    l.rpa_mfma_probe.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_double)]
+    l.rpa_mfma_probe.restype = C.c_int
     l.rpa_update_and_attend_noalloc.argtypes = [C.POINTER(Shape), C.c_int] + [C.c_void_p] * 7 + [
         C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
     l.rpa_update_and_attend_noalloc.restype = C.c_int
@@ -289,6 +291,17 @@ class RaggedPagedAttention:
         if rc != RPA_OK:
             raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())
         return ms.value if timed else None
+
+    def mfma_probe(self, steps, device=None):
+        """A launch of bf16 MFMAs alone on every compute unit; returns (milliseconds, FLOPs)."""
+        import torch
+
+        ms, flops = C.c_float(), C.c_double()
+        rc = self._lib.rpa_mfma_probe(self._ctx, int(steps), torch.cuda.current_stream(device).cuda_stream,
+                                      C.byref(ms), C.byref(flops))
+        if rc != RPA_OK:
+            raise RpaError(rc, self._lib.rpa_last_error(self._ctx).decode())
+        return ms.value, flops.value
 
     def update_and_attend_raw(self, out_ptr, q_ptr, k_new_ptr, v_new_ptr, k_pages_ptr, v_pages_ptr,
                               page_table_ptr, cu_q_lens, kv_lens, num_seqs, sm_scale, stream_ptr):

@@ -308,6 +308,27 @@ def test_copy_probe_copies_and_checks_arguments():
     ctx.close()
 
 
+def test_mfma_probe_runs_and_checks_arguments():
+    """The matrix-rate probe: FLOPs as counted by hand, a rate between a tenth of
+    and the published dense bf16 peak, more steps take longer (not in proportion:
+    the rate the chip sustains falls within milliseconds of matrix load)."""
+    wl = W.config(1)
+    ctx = rpa.RaggedPagedAttention.for_workload(wl)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    ctx.mfma_probe(500)                                   # warm-up
+    ms1, fl1 = ctx.mfma_probe(1000)
+    ms2, fl2 = ctx.mfma_probe(2000)
+    assert fl1 == cus * 8 * 1000 * 32 * (2 * 32 * 32 * 16) and fl2 == 2 * fl1
+    for ms, fl in ((ms1, fl1), (ms2, fl2)):
+        assert 250.0 < fl / (ms * 1e-3) / 1e12 < 2500.0
+    assert 1.5 < ms2 / ms1 < 4.0
+    with pytest.raises(rpa.RpaError):
+        ctx.mfma_probe(0)
+    with pytest.raises(rpa.RpaError):
+        ctx.mfma_probe((1 << 20) + 1)
+    ctx.close()
+
+
 def test_chunked_prefill_carries_cache_across_calls():
     """Four calls of 128 tokens must leave the same cache as one call of 512 and
     give outputs within tolerance of the single-call oracle."""
