@@ -296,7 +296,10 @@ extern "C" int rpa_copy_probe(rpa_ctx* c, void* dst, const void* src, size_t byt
     if (ms) {
         for (auto& x : ev) {
             e = hipEventCreate(&x);
-            if (e != hipSuccess) return hip_fail(c, "hipEventCreate", e);
+            if (e != hipSuccess) {
+                if (ev[0]) (void)hipEventDestroy(ev[0]);
+                return hip_fail(c, "hipEventCreate", e);
+            }
         }
     }
     int rc = launch_copy(dst, src, bytes / 16, c->num_cus, stream, ms ? (void**)ev : nullptr);
@@ -320,7 +323,10 @@ extern "C" int rpa_mfma_probe(rpa_ctx* c, int32_t steps, void* stream, float* ms
     if (ms) {
         for (auto& x : ev) {
             e = hipEventCreate(&x);
-            if (e != hipSuccess) return hip_fail(c, "hipEventCreate", e);
+            if (e != hipSuccess) {
+                if (ev[0]) (void)hipEventDestroy(ev[0]);
+                return hip_fail(c, "hipEventCreate", e);
+            }
         }
     }
     int rc = launch_mfma(steps, c->num_cus, stream, ms ? (void**)ev : nullptr);
