@@ -5,8 +5,8 @@
 Draws shapes, length mixes, launch knobs, cache types and input recipes at random,
 runs each batch through the C ABI and compares cache and outputs with the CPU oracle
 exactly as tests/test_gpu_parity.py does.  Every case is printed before it runs, so
-a failure names its seed.  (Runs of 400-420 s: about 3000 cases each, all equal to
-the oracle within the tolerance.)"""
+a failure names its seed.  (Runs of 300-840 s on different seed bases: 1900-6000 cases each,
+all equal to the oracle within the tolerance.)"""
 import os
 import random
 import sys
