@@ -26,7 +26,8 @@ import os
 import sqlite3
 import sys
 
-KERNELS = ("rpa_narrow_kernel", "rpa_wide_kernel", "rpa_mixed_kernel", "rpa_combine_kernel", "rpa_copy_kernel")
+KERNELS = ("rpa_narrow_kernel", "rpa_wide_kernel", "rpa_mixed_kernel", "rpa_combine_kernel", "rpa_copy_kernel", "rpa_mfma_kernel",
+           "rpa_quantize_kernel")
 
 
 def short_name(name: str) -> str:
